@@ -1,0 +1,118 @@
+"""Pins for the oracle's backward (O10): torch CPU autograd on the dense definition of
+the layer (float64), central finite differences, and the adjoint identity of the pack."""
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+import moe_workloads as wl
+from oracle import moe_oracle as orc
+
+
+def _setup(seed=0, T=9, d=6, E=4, k=2, f=5):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, d))
+    W1 = [rng.standard_normal((f, d)) / np.sqrt(d) for _ in range(E)]
+    W3 = [rng.standard_normal((f, d)) / np.sqrt(d) for _ in range(E)]
+    W2 = [rng.standard_normal((d, f)) / np.sqrt(f) for _ in range(E)]
+    idx = wl.random_routing(T, E, k, seed + 1)
+    w = rng.random((T, k)) + 0.1
+    dout = rng.standard_normal((T, d))
+    dest = (np.arange(E) // 2).astype(np.int32)
+    return x, W1, W3, W2, idx, w, dout, dest
+
+
+def _oracle_backward(x, W1, W3, W2, idx, w, dout, dest, R=2):
+    T, k = idx.shape
+    cnt, off, _, _, s2r, r2s = orc.dispatch_maps(idx, dest, R)
+    xp = orc.pack_rows(x, r2s, k)
+    y, G, U = orc.expert_ffn(xp, cnt, off, W1, W3, W2)
+    dy, dw = orc.combine_bwd(dout, y, s2r, w)
+    dxp, dW1, dW3, dW2 = orc.expert_ffn_bwd(dy, xp, G, U, cnt, off, W1, W3, W2)
+    dx = orc.dispatch_bwd(dxp, s2r, T, k)
+    return dx, dw, dW1, dW3, dW2
+
+
+def test_backward_matches_autograd_of_the_dense_definition():
+    x, W1, W3, W2, idx, w, dout, dest = _setup()
+    dx, dw, dW1, dW3, dW2 = _oracle_backward(x, W1, W3, W2, idx, w, dout, dest)
+    xt = torch.tensor(x, requires_grad=True)
+    wt = torch.tensor(w, requires_grad=True)
+    t1 = [torch.tensor(a, requires_grad=True) for a in W1]
+    t3 = [torch.tensor(a, requires_grad=True) for a in W3]
+    t2 = [torch.tensor(a, requires_grad=True) for a in W2]
+    rows = []
+    for t in range(x.shape[0]):
+        acc = 0
+        for j in range(idx.shape[1]):
+            e = int(idx[t, j])
+            h = F.silu(F.linear(xt[t], t1[e])) * F.linear(xt[t], t3[e])
+            acc = acc + wt[t, j] * F.linear(h, t2[e])
+        rows.append(acc)
+    out = torch.stack(rows)
+    out.backward(torch.tensor(dout))
+    np.testing.assert_allclose(dx, xt.grad.numpy(), rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(dw, wt.grad.numpy(), rtol=1e-11, atol=1e-13)
+    for e in range(len(W1)):
+        np.testing.assert_allclose(dW1[e], t1[e].grad.numpy(), rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(dW3[e], t3[e].grad.numpy(), rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(dW2[e], t2[e].grad.numpy(), rtol=1e-11, atol=1e-13)
+
+
+def test_backward_matches_central_finite_differences():
+    x, W1, W3, W2, idx, w, dout, dest = _setup(seed=5, T=5, d=4, E=2, k=2, f=3)
+    dest = np.array([0, 1], np.int32)
+    dx, dw, dW1, dW3, dW2 = _oracle_backward(x, W1, W3, W2, idx, w, dout, dest)
+
+    def loss(x_, w_, W1_, W3_, W2_):
+        return float(np.sum(orc.layer_dense(x_, idx, w_, W1_, W3_, W2_) * dout))
+
+    h = 1e-6
+
+    def fd(arr, grad, rebuild):
+        g = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            i = it.multi_index
+            a = arr.copy(); a[i] += h
+            b = arr.copy(); b[i] -= h
+            g[i] = (rebuild(a) - rebuild(b)) / (2 * h)
+        np.testing.assert_allclose(grad, g, rtol=2e-6, atol=2e-8)
+
+    fd(x, dx, lambda a: loss(a, w, W1, W3, W2))
+    fd(w, dw, lambda a: loss(x, a, W1, W3, W2))
+    fd(W1[1], dW1[1], lambda a: loss(x, w, [W1[0], a], W3, W2))
+    fd(W3[0], dW3[0], lambda a: loss(x, w, W1, [a, W3[1]], W2))
+    fd(W2[1], dW2[1], lambda a: loss(x, w, W1, W3, [W2[0], a]))
+
+
+def test_dispatch_bwd_is_the_transpose_of_the_pack():
+    rng = np.random.default_rng(3)
+    T, E, k, d = 40, 8, 3, 5
+    idx = wl.random_routing(T, E, k, 4)
+    _, _, _, _, s2r, r2s = orc.dispatch_maps(idx, np.zeros(E, np.int32), 1)
+    x = rng.standard_normal((T, d))
+    g = rng.standard_normal((T * k, d))
+    lhs = np.sum(orc.pack_rows(x, r2s, k) * g)
+    rhs = np.sum(x * orc.dispatch_bwd(g, s2r, T, k))
+    assert abs(lhs - rhs) < 1e-10 * abs(lhs)
+    # combine_bwd's dy is the transpose of combine in y
+    w = rng.random((T, k))
+    dout = rng.standard_normal((T, d))
+    y = rng.standard_normal((T * k, d))
+    dy, dw = orc.combine_bwd(dout, y, s2r, w)
+    assert abs(np.sum(orc.combine(y, s2r, w) * dout) - np.sum(y * dy)) < 1e-10
+    assert abs(np.sum(orc.combine(y, s2r, w) * dout) - np.sum(w * dw)) < 1e-10
+
+
+def test_experts_without_weights_get_no_gradient_and_zero_dx():
+    x, W1, W3, W2, idx, w, dout, dest = _setup(seed=7)
+    W1[2] = W3[2] = W2[2] = None
+    T, k = idx.shape
+    cnt, off, _, _, s2r, r2s = orc.dispatch_maps(idx, dest, 2)
+    xp = orc.pack_rows(x, r2s, k)
+    y, G, U = orc.expert_ffn(xp, cnt, off, W1, W3, W2)
+    assert np.all(y[off[2]:off[2] + cnt[2]] == 0)
+    dy, _ = orc.combine_bwd(dout, y, s2r, w)
+    dxp, dW1, dW3, dW2 = orc.expert_ffn_bwd(dy, xp, G, U, cnt, off, W1, W3, W2)
+    assert dW1[2] is None and dW3[2] is None and dW2[2] is None
+    assert np.all(dxp[off[2]:off[2] + cnt[2]] == 0)
