@@ -1,0 +1,181 @@
+/*
+ * moe.h -- C ABI of the one-GPU MoE hot path (gfx950 / MI355X).
+ *
+ * One GPU's share of an expert-parallel Mixture-of-Experts layer under a given
+ * expert-placement map: top-k gating, dispatch into contiguous per-(destination
+ * rank, expert) buffers, grouped SwiGLU expert FFN on the resident experts,
+ * weighted combine, and the backward of the last three.
+ *
+ * Structure of the layer: paper Sec. 2.1 "Expert Parallelism" and Fig.
+ * "MoE-structure" (gate network as router, data moved to the activated experts,
+ * experts are replicated FFNs, results merged back).  Placement semantics: paper
+ * Sec. 3.2 "Relationships between Two Communications" (an expert obtained by
+ * all-gather is computed locally, its data chunk is not sent) and the domain rule
+ * of Sec. 4.1 / Algorithm 1 (which rank the tokens of a non-resident expert go
+ * to).  Per-peer contiguous chunks: Sec. 3.2 "All-to-All Communication Modeling".
+ *
+ * Conventions
+ *   - Every function returns 0 (MOE_OK) or a negative moe_status.  Nothing throws
+ *     or aborts across this boundary.  moe_strerror() names a status.
+ *   - Pointers marked [dev] are device pointers the CALLER owns (allocated with
+ *     any HIP allocator), 16-byte aligned, row-major, dense.  Pointers marked
+ *     [host] are host memory, read during the call only.
+ *   - The library owns only the opaque moe_ctx and its small device workspace.
+ *   - All compute calls are asynchronous on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream), do no host synchronisation and copy
+ *     nothing back to the host: counts and offsets stay on the device.
+ *   - Arguments are validated on the host before anything is launched; on error
+ *     nothing is launched.
+ *   - Slot s = t*k + j is token t's j-th selected expert; S = T*k; rows of the
+ *     packed buffers are numbered 0..S-1.
+ *   - Storage type `dtype` applies to x, Wg, expert weights, packed buffers and
+ *     outputs.  Accumulation is always fp32.  Indices are int32.
+ *   - Calls on one moe_ctx must not overlap in time (they share its workspace).
+ */
+#ifndef MOE_HOTPATH_MOE_H
+#define MOE_HOTPATH_MOE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_ctx moe_ctx;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_EINVAL = -1,       /* bad argument (range, NULL, alignment, size) */
+  MOE_EUNSUPPORTED = -2, /* valid but outside what the kernels cover */
+  MOE_ENOMEM = -3,       /* workspace allocation failed */
+  MOE_EHIP = -4          /* a HIP runtime call failed */
+} moe_status;
+
+/* Limits of the kernels. */
+#define MOE_MAX_EXPERTS 256
+#define MOE_MAX_TOPK 16
+#define MOE_MAX_RANKS 256
+
+typedef struct {
+  int32_t T_max;       /* largest T any call will pass (sizes the workspace)        */
+  int32_t d;           /* d_model; multiple of 8                                      */
+  int32_t E;           /* experts, 1..MOE_MAX_EXPERTS                                 */
+  int32_t k;           /* top-k, 1..min(E, MOE_MAX_TOPK)                              */
+  int32_t f;           /* ffn_dim; multiple of 8                                      */
+  int32_t R;           /* virtual ranks, 1..MOE_MAX_RANKS                             */
+  int32_t local_rank;  /* this GPU's rank, 0..R-1                                     */
+  int32_t dtype;       /* moe_dtype                                                   */
+  int32_t renormalize; /* 1: gate weights = softmax over the selected k; 0: over all E */
+} moe_config;
+
+const char* moe_strerror(int status);
+
+/* Create / destroy a context.  moe_create validates cfg, allocates the device
+ * workspace on the current device (O(T_max*k + E) integers) and installs the
+ * default placement dest_rank[e] = e / ceil(E/R).  *out is NULL on error. */
+int moe_create(moe_ctx** out, const moe_config* cfg);
+int moe_destroy(moe_ctx* ctx);
+
+/* Expert-placement map (paper Sec. 3.2, Sec. 4.1): expert_dest_rank [host][E],
+ * each in [0,R).  dest_rank[e] == local_rank  <=>  expert e is resident (home or
+ * migrated here): its tokens are packed into the local compute region.  Any other
+ * value: its tokens are packed into that rank's send buffer.  Copies the map to
+ * the device with a synchronous copy. */
+int moe_set_placement(moe_ctx* ctx, const int32_t* expert_dest_rank);
+
+/* Which kernels moe_expert_ffn uses.  MOE_FFN_AUTO (default): the bf16 MFMA kernels when
+ * dtype is bf16, d % 256 == 0 and f % 128 == 0, else the vector-ALU kernels.  MOE_FFN_VALU:
+ * always the vector-ALU kernels (any shape and both dtypes; a slow cross-check). */
+#define MOE_FFN_AUTO 0
+#define MOE_FFN_VALU 1
+int moe_set_ffn_path(moe_ctx* ctx, int path);
+
+/* Gating (Sec. 2.1: "a gate network as the router").
+ *   logits[t,e] = sum_c x[t,c]*Wg[e,c] (+ bias[e]);  the k largest per token in
+ *   descending order, equal logits ordered by ascending expert id;  weights =
+ *   softmax over the selected k (renormalize) or over all E, computed in fp32.
+ * x [dev][T,d] dtype; Wg [dev][E,d] dtype; bias [dev][E] fp32 or NULL;
+ * logits [dev][T,E] fp32 out, or NULL (then the workspace holds them);
+ * topk_idx [dev][T,k] int32 out; topk_w [dev][T,k] fp32 out.  0 <= T <= T_max. */
+int moe_route(moe_ctx* ctx, const void* x, const void* Wg, const float* bias, int32_t T,
+              float* logits, int32_t* topk_idx, float* topk_w, void* stream);
+
+/* The selection and weights alone, from given fp32 logits [dev][T,E]: pure
+ * comparisons, so topk_idx is reproducible bit for bit from the same logits. */
+int moe_route_logits(moe_ctx* ctx, const float* logits, int32_t T, int32_t* topk_idx,
+                     float* topk_w, void* stream);
+
+/* Dispatch (Sec. 2.1 data rearrangement; Sec. 3.2 per-peer chunks and the rule
+ * that a fetched expert keeps its chunk local).  Segments are ordered by
+ * (dest_rank[e], e); inside a segment rows follow ascending slot id (stable), so
+ * exactly one permutation is correct.
+ *   expert_counts[e]  = number of slots routed to e
+ *   expert_offsets[e] = first packed row of e's segment
+ *   rank_counts[r], rank_offsets[r] (R+1 entries, last = S): rank r's chunk
+ *   slot_to_row[s], row_to_slot[row]: the permutation and its inverse
+ *   x_packed[slot_to_row[t*k+j]] = x[t]   (bit copy)
+ * Rows [rank_offsets[local_rank], rank_offsets[local_rank+1]) are the compute
+ * region; every other rank's range is that rank's send buffer.
+ * x [dev][T,d]; topk_idx [dev][T,k] with every entry in [0,E) (entries outside
+ * are not detected on the host; they are skipped on the device and leave their
+ * slot unmapped); all outputs [dev], int32 except x_packed [dev][T*k,d] dtype.
+ * x and x_packed may be NULL together to compute the maps only. */
+int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int32_t T,
+                 void* x_packed, int32_t* slot_to_row, int32_t* row_to_slot,
+                 int32_t* expert_counts, int32_t* expert_offsets, int32_t* rank_counts,
+                 int32_t* rank_offsets, void* stream);
+
+/* Grouped SwiGLU expert FFN (Sec. 2.1: experts are replicated FFNs; Sec. 3.1: the
+ * experts of one GPU are computed one after another on their own tokens).  For
+ * every expert e whose three table entries are non-NULL and every row r of its
+ * segment [expert_offsets[e], +expert_counts[e]):
+ *   g = x_r W1[e]^T, u = x_r W3[e]^T, h = silu(g)*u, y_r = h W2[e]^T
+ * W1,W3,W2: [host][E] tables of device pointers; W1[e],W3[e] [dev][f,d],
+ * W2[e] [dev][d,f], dtype; an expert with NULL entries is not computed and its
+ * rows of y_packed are left untouched.  In production the non-NULL set is the
+ * resident set; loopback tests pass every expert.
+ * y_packed [dev][S,d] dtype out.  G_save,U_save [dev][S,f] dtype out or both NULL:
+ * the pre-activation projections kept for the backward.  bf16: h (and g,u when
+ * saved) are rounded to bf16 between the two GEMMs. */
+int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* expert_counts,
+                   const int32_t* expert_offsets, const void* const* W1, const void* const* W3,
+                   const void* const* W2, int32_t T, void* y_packed, void* G_save, void* U_save,
+                   void* stream);
+
+/* Combine / un-permute (Sec. 2.1: the second rearrangement, after the experts).
+ *   out[t] = sum_{j<k} topk_w[t,j] * y_packed[slot_to_row[t*k+j]], j ascending, fp32.
+ * y_packed [dev][S,d] must hold every row (remote rows are what came back from the
+ * other ranks; the caller supplies them).  out [dev][T,d] dtype. */
+int moe_combine(moe_ctx* ctx, const void* y_packed, const int32_t* slot_to_row,
+                const float* topk_w, int32_t T, void* out, void* stream);
+
+/* Backward of combine:  dy_packed[row(t,j)] = topk_w[t,j]*dout[t];
+ *                       dtopk_w[t,j] = <dout[t], y_packed[row(t,j)]>.
+ * dout [dev][T,d]; dy_packed [dev][S,d] out; dtopk_w [dev][T,k] fp32 out. */
+int moe_combine_bwd(moe_ctx* ctx, const void* dout, const void* y_packed,
+                    const int32_t* slot_to_row, const float* topk_w, int32_t T,
+                    void* dy_packed, float* dtopk_w, void* stream);
+
+/* Backward of the expert FFN for every expert with non-NULL table entries:
+ *   dH = dY W2; dG = dH*u*silu'(g); dU = dH*silu(g); dX = dG W1 + dU W3;
+ *   dW2 = dY^T H; dW1 = dG^T X; dW3 = dU^T X        (H = silu(G)*U recomputed)
+ * dy_packed,x_packed [dev][S,d]; G_save,U_save [dev][S,f] from the forward;
+ * dx_packed [dev][S,d] out (rows of experts not computed are left untouched);
+ * dW1,dW3,dW2: [host][E] tables of device pointers to fp32 [f,d],[f,d],[d,f],
+ * overwritten (not accumulated); NULL entry = that gradient is not wanted. */
+int moe_expert_ffn_bwd(moe_ctx* ctx, const void* dy_packed, const void* x_packed,
+                       const void* G_save, const void* U_save, const int32_t* expert_counts,
+                       const int32_t* expert_offsets, const void* const* W1,
+                       const void* const* W3, const void* const* W2, int32_t T, void* dx_packed,
+                       float* const* dW1, float* const* dW3, float* const* dW2, void* stream);
+
+/* Backward of dispatch (transpose of the pack): dx[t] = sum_j dx_packed[slot_to_row[t*k+j]]. */
+int moe_dispatch_bwd(moe_ctx* ctx, const void* dx_packed, const int32_t* slot_to_row, int32_t T,
+                     void* dx, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_HOTPATH_MOE_H */

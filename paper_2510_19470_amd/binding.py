@@ -1,0 +1,265 @@
+"""ctypes binding of libmoe_hip.so.  Same names as the C entry points in include/moe.h.
+
+Argument marshalling only: tensors must already live on the GPU; outputs that are not
+passed in are allocated with torch.empty on the same device.  There is no CPU fallback:
+if the library is missing and cannot be built, importing the symbols raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, c_char_p, c_float, c_int, c_int32, c_void_p
+from typing import List, Optional, Sequence
+
+import torch
+
+MOE_F32, MOE_BF16 = 0, 1
+MOE_FFN_AUTO, MOE_FFN_VALU = 0, 1
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libmoe_hip.so"
+_lib = None
+
+
+class MoEError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {moe_strerror(status)} ({status})")
+
+
+class MoEConfigC(ctypes.Structure):
+    _fields_ = [("T_max", c_int32), ("d", c_int32), ("E", c_int32), ("k", c_int32),
+                ("f", c_int32), ("R", c_int32), ("local_rank", c_int32), ("dtype", c_int32),
+                ("renormalize", c_int32)]
+
+
+def library_path() -> str:
+    return os.path.join(_PKG, _LIB_NAME)
+
+
+def load_library(build_if_missing: bool = True):
+    """Load libmoe_hip.so from the package directory (building it first if absent)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        if not build_if_missing:
+            raise ImportError(f"{path} is missing: run `python -m paper_2510_19470_amd.build`")
+        from . import build as _build
+        _build.build(verbose=False)
+    lib = ctypes.CDLL(path)
+    P = c_void_p
+    lib.moe_strerror.restype = c_char_p
+    lib.moe_strerror.argtypes = [c_int]
+    lib.moe_create.argtypes = [POINTER(c_void_p), POINTER(MoEConfigC)]
+    lib.moe_destroy.argtypes = [P]
+    lib.moe_set_placement.argtypes = [P, POINTER(c_int32)]
+    lib.moe_set_ffn_path.argtypes = [P, c_int]
+    lib.moe_route.argtypes = [P, P, P, P, c_int32, P, P, P, P]
+    lib.moe_route_logits.argtypes = [P, P, c_int32, P, P, P]
+    lib.moe_dispatch.argtypes = [P, P, P, c_int32, P, P, P, P, P, P, P, P]
+    lib.moe_expert_ffn.argtypes = [P, P, P, P, P, P, P, c_int32, P, P, P, P]
+    lib.moe_combine.argtypes = [P, P, P, P, c_int32, P, P]
+    lib.moe_combine_bwd.argtypes = [P, P, P, P, P, c_int32, P, P, P]
+    lib.moe_expert_ffn_bwd.argtypes = [P, P, P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P]
+    lib.moe_dispatch_bwd.argtypes = [P, P, P, c_int32, P, P]
+    for name in ("moe_create", "moe_destroy", "moe_set_placement", "moe_set_ffn_path", "moe_route",
+                 "moe_route_logits", "moe_dispatch", "moe_expert_ffn", "moe_combine",
+                 "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd"):
+        getattr(lib, name).restype = c_int
+    _lib = lib
+    return lib
+
+
+def moe_strerror(status: int) -> str:
+    return load_library().moe_strerror(int(status)).decode()
+
+
+# ------------------------------------------------------------------ marshalling
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("tensors passed to the HIP path must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError("tensors passed to the HIP path must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _table(ts: Sequence[Optional[torch.Tensor]]):
+    arr = (c_void_p * len(ts))()
+    for i, t in enumerate(ts):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise MoEError(status, where)
+
+
+class MoEContext:
+    """Owns a moe_ctx*.  `cfg` fields mirror moe_config."""
+
+    def __init__(self, T_max: int, d: int, E: int, k: int, f: int, R: int, local_rank: int = 0,
+                 dtype: int = MOE_BF16, renormalize: int = 1):
+        self.cfg = MoEConfigC(T_max, d, E, k, f, R, local_rank, dtype, renormalize)
+        self.handle = c_void_p()
+        _check(load_library().moe_create(ctypes.byref(self.handle), ctypes.byref(self.cfg)),
+               "moe_create")
+        self.torch_dtype = torch.bfloat16 if dtype == MOE_BF16 else torch.float32
+
+    def close(self) -> None:
+        if self.handle:
+            load_library().moe_destroy(self.handle)
+            self.handle = c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def moe_create(**kw) -> MoEContext:
+    return MoEContext(**kw)
+
+
+def moe_destroy(ctx: MoEContext) -> None:
+    ctx.close()
+
+
+def moe_set_placement(ctx: MoEContext, expert_dest_rank: Sequence[int]) -> None:
+    arr = (c_int32 * ctx.cfg.E)(*[int(v) for v in expert_dest_rank])
+    if len(expert_dest_rank) != ctx.cfg.E:
+        raise ValueError("expert_dest_rank must have E entries")
+    _check(load_library().moe_set_placement(ctx.handle, arr), "moe_set_placement")
+
+
+def moe_set_ffn_path(ctx: MoEContext, path: int) -> None:
+    _check(load_library().moe_set_ffn_path(ctx.handle, path), "moe_set_ffn_path")
+
+
+def moe_route(ctx, x, Wg, bias=None, logits=None, topk_idx=None, topk_w=None, want_logits=False):
+    T, k, E = x.shape[0], ctx.cfg.k, ctx.cfg.E
+    dev = x.device
+    if logits is None and want_logits:
+        logits = torch.empty((T, E), dtype=torch.float32, device=dev)
+    if topk_idx is None:
+        topk_idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+    if topk_w is None:
+        topk_w = torch.empty((T, k), dtype=torch.float32, device=dev)
+    _check(load_library().moe_route(ctx.handle, _ptr(x), _ptr(Wg), _ptr(bias), T, _ptr(logits),
+                                    _ptr(topk_idx), _ptr(topk_w), _stream()), "moe_route")
+    return topk_idx, topk_w, logits
+
+
+def moe_route_logits(ctx, logits, topk_idx=None, topk_w=None):
+    T, k = logits.shape[0], ctx.cfg.k
+    if topk_idx is None:
+        topk_idx = torch.empty((T, k), dtype=torch.int32, device=logits.device)
+    if topk_w is None:
+        topk_w = torch.empty((T, k), dtype=torch.float32, device=logits.device)
+    _check(load_library().moe_route_logits(ctx.handle, _ptr(logits), T, _ptr(topk_idx),
+                                           _ptr(topk_w), _stream()), "moe_route_logits")
+    return topk_idx, topk_w
+
+
+class DispatchOut:
+    __slots__ = ("x_packed", "slot_to_row", "row_to_slot", "expert_counts", "expert_offsets",
+                 "rank_counts", "rank_offsets")
+
+
+def moe_dispatch(ctx, x, topk_idx, out: Optional[DispatchOut] = None, T: Optional[int] = None):
+    """x may be None (maps only).  `out` re-uses previously allocated outputs."""
+    k, E, R, d = ctx.cfg.k, ctx.cfg.E, ctx.cfg.R, ctx.cfg.d
+    T = topk_idx.shape[0] if T is None else T
+    dev = topk_idx.device
+    if out is None:
+        out = DispatchOut()
+        i32 = dict(dtype=torch.int32, device=dev)
+        out.x_packed = None if x is None else torch.empty((T * k, d), dtype=x.dtype, device=dev)
+        out.slot_to_row = torch.empty(T * k, **i32)
+        out.row_to_slot = torch.empty(T * k, **i32)
+        out.expert_counts = torch.empty(E, **i32)
+        out.expert_offsets = torch.empty(E, **i32)
+        out.rank_counts = torch.empty(R, **i32)
+        out.rank_offsets = torch.empty(R + 1, **i32)
+    _check(load_library().moe_dispatch(
+        ctx.handle, _ptr(x), _ptr(topk_idx), T, _ptr(out.x_packed), _ptr(out.slot_to_row),
+        _ptr(out.row_to_slot), _ptr(out.expert_counts), _ptr(out.expert_offsets),
+        _ptr(out.rank_counts), _ptr(out.rank_offsets), _stream()), "moe_dispatch")
+    return out
+
+
+def moe_expert_ffn(ctx, x_packed, expert_counts, expert_offsets, W1, W3, W2, y_packed=None,
+                   G_save=None, U_save=None, save=False):
+    S = x_packed.shape[0]
+    T = S // ctx.cfg.k
+    if y_packed is None:
+        y_packed = torch.zeros_like(x_packed)
+    if save and G_save is None:
+        G_save = torch.zeros((S, ctx.cfg.f), dtype=x_packed.dtype, device=x_packed.device)
+        U_save = torch.zeros((S, ctx.cfg.f), dtype=x_packed.dtype, device=x_packed.device)
+    t1, t3, t2 = _table(W1), _table(W3), _table(W2)
+    _check(load_library().moe_expert_ffn(
+        ctx.handle, _ptr(x_packed), _ptr(expert_counts), _ptr(expert_offsets), t1, t3, t2, T,
+        _ptr(y_packed), _ptr(G_save), _ptr(U_save), _stream()), "moe_expert_ffn")
+    return y_packed, G_save, U_save
+
+
+def moe_combine(ctx, y_packed, slot_to_row, topk_w, out=None):
+    T = topk_w.shape[0]
+    if out is None:
+        out = torch.empty((T, ctx.cfg.d), dtype=y_packed.dtype, device=y_packed.device)
+    _check(load_library().moe_combine(ctx.handle, _ptr(y_packed), _ptr(slot_to_row), _ptr(topk_w),
+                                      T, _ptr(out), _stream()), "moe_combine")
+    return out
+
+
+def moe_combine_bwd(ctx, dout, y_packed, slot_to_row, topk_w, dy_packed=None, dtopk_w=None):
+    T = topk_w.shape[0]
+    if dy_packed is None:
+        dy_packed = torch.empty_like(y_packed)
+    if dtopk_w is None:
+        dtopk_w = torch.empty_like(topk_w)
+    _check(load_library().moe_combine_bwd(
+        ctx.handle, _ptr(dout), _ptr(y_packed), _ptr(slot_to_row), _ptr(topk_w), T,
+        _ptr(dy_packed), _ptr(dtopk_w), _stream()), "moe_combine_bwd")
+    return dy_packed, dtopk_w
+
+
+def moe_expert_ffn_bwd(ctx, dy_packed, x_packed, G_save, U_save, expert_counts, expert_offsets,
+                       W1, W3, W2, dx_packed=None, dW1=None, dW3=None, dW2=None):
+    """dW1/dW3/dW2: lists of fp32 tensors (or None per expert); allocated for every expert
+    with weights when not given."""
+    S = x_packed.shape[0]
+    T = S // ctx.cfg.k
+    dev = x_packed.device
+    if dx_packed is None:
+        dx_packed = torch.zeros_like(x_packed)
+
+    def grads(ws):
+        return [None if w is None else torch.empty(w.shape, dtype=torch.float32, device=dev)
+                for w in ws]
+    dW1 = grads(W1) if dW1 is None else dW1
+    dW3 = grads(W3) if dW3 is None else dW3
+    dW2 = grads(W2) if dW2 is None else dW2
+    _check(load_library().moe_expert_ffn_bwd(
+        ctx.handle, _ptr(dy_packed), _ptr(x_packed), _ptr(G_save), _ptr(U_save),
+        _ptr(expert_counts), _ptr(expert_offsets), _table(W1), _table(W3), _table(W2), T,
+        _ptr(dx_packed), _table(dW1), _table(dW3), _table(dW2), _stream()), "moe_expert_ffn_bwd")
+    return dx_packed, dW1, dW3, dW2
+
+
+def moe_dispatch_bwd(ctx, dx_packed, slot_to_row, dx=None):
+    T = dx_packed.shape[0] // ctx.cfg.k
+    if dx is None:
+        dx = torch.empty((T, ctx.cfg.d), dtype=dx_packed.dtype, device=dx_packed.device)
+    _check(load_library().moe_dispatch_bwd(ctx.handle, _ptr(dx_packed), _ptr(slot_to_row), T,
+                                           _ptr(dx), _stream()), "moe_dispatch_bwd")
+    return dx

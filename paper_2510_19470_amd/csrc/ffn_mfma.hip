@@ -1,0 +1,294 @@
+// Grouped SwiGLU expert FFN on the matrix cores (bf16 in, fp32 accumulate) for gfx950.
+// (Paper Sec. 2.1: experts are replicated FFNs; Sec. 3.1: computation latency is
+// dominated by the expert GEMMs and the experts of one GPU run on their own tokens.)
+//
+// Two launches walk a device-built tile list (no host sync on the token counts):
+//   gate/up : H[r, n] = silu(x_r . W1[e][n,:]) * (x_r . W3[e][n,:])   (SwiGLU fused)
+//   down    : Y[r, c] = H[r,:] . W2[e][c,:]
+// Every operand is contiguous along the contraction dimension, so each lane feeds the
+// MFMA with one 16-byte LDS read per operand fragment.
+//
+// Tiling: 512 threads = 8 wavefronts (2 along rows x 4 along columns), block tile
+// 256 rows x 256 weight rows x 64 (k), wavefront tile 128 x 64 = 4 x 2 MFMA 32x32x16
+// accumulators (128 fp32 registers).  For gate/up the 256 weight rows are 128 rows of W1
+// and the matching 128 rows of W3, laid out so that a wavefront owns gate and up of the
+// same columns and applies silu(g)*u in registers.  The weight rows are the MFMA "A"
+// operand and the token rows the "B" operand: a lane then holds 4 consecutive output
+// columns of one token row and stores them as one 8-byte write.
+// LDS: 2 stages x (32 KB tokens + 32 KB weights) = 128 KB, 16-byte chunks XOR-swizzled by
+// row so that the 16-byte fragment reads of 16 consecutive rows fall on distinct banks.
+// Global loads of stage t+1 are issued before the MFMAs of stage t and written to LDS
+// after them: one barrier per k-step.
+// Tile order: tiles of one expert that share a weight panel (same column block) are
+// consecutive, and the block index is remapped so that each of the 8 XCDs (private L2)
+// works on a contiguous range of that order.
+#include "moe_internal.h"
+#include "numeric.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = MFMA_BM;       // token rows per block tile
+constexpr int BNW = 256;          // weight rows per block tile
+constexpr int BK = 64;            // k per stage
+constexpr int NT = 512;           // threads
+constexpr int STAGE_VEC = 2048;   // uint4 per operand per stage (256 rows x 8 chunks)
+
+__device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
+
+// tile list entry: (mtile index << 12) | column block
+__global__ __launch_bounds__(256) void mfma_sched_kernel(
+    const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets,
+    const void* const* __restrict__ present, int E, int S, int max_mtiles, int nt_up, int nt_down,
+    TileSched* __restrict__ sched, MTile* __restrict__ mt, uint32_t* __restrict__ order_up,
+    uint32_t* __restrict__ order_down) {
+  __shared__ int32_t start[MOE_MAX_EXPERTS + 1];
+  __shared__ int bad;
+  const int tid = threadIdx.x;
+  if (tid == 0) {
+    start[0] = 0;
+    bad = 0;
+  }
+  __syncthreads();
+  // per-expert tile counts (E <= 256: one expert per thread), then an inclusive scan
+  int mine = 0;
+  if (tid < E && present[tid] != nullptr) {
+    const int n = counts[tid], o = offsets[tid];
+    if (n < 0 || o < 0 || (long)o + n > (long)S) bad = 1;  // caller's arrays are inconsistent
+    else mine = (n + BM - 1) / BM;
+  }
+  start[tid + 1] = mine;
+  __syncthreads();
+  for (int off = 1; off < 256; off <<= 1) {
+    int v = 0;
+    if (tid >= off) v = start[tid + 1 - off];
+    __syncthreads();
+    if (tid >= off) start[tid + 1] += v;
+    __syncthreads();
+  }
+  const int total_m = (bad || start[E] > max_mtiles) ? 0 : start[E];
+  if (blockIdx.x == 0 && tid == 0) sched->n_mtiles = total_m;
+  const int gsz = gridDim.x * blockDim.x;
+  const int gid = blockIdx.x * blockDim.x + tid;
+  for (int i = gid; i < total_m; i += gsz) {
+    int lo = 0, hi = E;  // largest e with start[e] <= i
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (start[mid] <= i) lo = mid; else hi = mid;
+    }
+    const int m = i - start[lo];
+    MTile t;
+    t.expert = lo;
+    t.row0 = offsets[lo] + m * BM;
+    t.rows = min(BM, counts[lo] - m * BM);
+    t.pad = 0;
+    mt[i] = t;
+  }
+  // tile order: expert by expert; inside an expert column block by column block, and for
+  // one column block all of the expert's row blocks in a row (they share a weight panel)
+  for (int pass = 0; pass < 2; ++pass) {
+    const int nt = pass == 0 ? nt_up : nt_down;
+    uint32_t* order = pass == 0 ? order_up : order_down;
+    const int total = total_m * nt;
+    for (int L = gid; L < total; L += gsz) {
+      int lo = 0, hi = E;
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (start[mid] * nt <= L) lo = mid; else hi = mid;
+      }
+      const int me = start[lo + 1] - start[lo];
+      const int rel = L - start[lo] * nt;
+      const int n = rel / me, m = rel % me;
+      order[L] = ((uint32_t)(start[lo] + m) << 12) | (uint32_t)n;
+    }
+  }
+}
+
+template <bool GATED>
+__global__ __launch_bounds__(NT) void ffn_mfma_kernel(
+    const uint16_t* __restrict__ A, const TileSched* __restrict__ sched,
+    const MTile* __restrict__ mt, const uint32_t* __restrict__ order, int n_tiles_n,
+    const void* const* __restrict__ Bt0, const void* const* __restrict__ Bt1, int K, int N,
+    uint16_t* __restrict__ C, uint16_t* __restrict__ Gs, uint16_t* __restrict__ Us) {
+  __shared__ uint4 lds[4 * STAGE_VEC];  // [stage][A|B][2048]
+
+  const int total = sched->n_mtiles * n_tiles_n;
+  const int per_xcd = (total + 7) >> 3;
+  const int slot = blockIdx.x >> 3;
+  const int L = (blockIdx.x & 7) * per_xcd + slot;
+  if (slot >= per_xcd || L >= total) return;
+  const uint32_t ent = order[L];
+  const MTile tl = mt[ent >> 12];
+  const int nblk = ent & 0xfff;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+
+  // ---- global -> LDS assignment: 4 token chunks and 4 weight chunks (16 B) per thread
+  const int ld_row = tid >> 3, ld_ch = tid & 7;
+  const uint4* a_src[4];
+  const uint4* b_src[4];
+  const uint16_t* B0 = (const uint16_t*)Bt0[tl.expert];
+  const uint16_t* B1 = GATED ? (const uint16_t*)Bt1[tl.expert] : nullptr;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = ld_row + i * 64;
+    const int arow = min(row, tl.rows - 1);
+    a_src[i] = (const uint4*)(A + (size_t)(tl.row0 + arow) * K) + ld_ch;
+    const uint16_t* bp;
+    if (GATED)
+      bp = (row < 128 ? B0 : B1) + (size_t)(nblk * 128 + (row & 127)) * K;
+    else
+      bp = B0 + (size_t)(nblk * 256 + row) * K;
+    b_src[i] = (const uint4*)bp + ld_ch;
+  }
+  const int st_off = ld_row * 8 + (ld_ch ^ swz(ld_row));  // + i*512 per chunk
+
+  // ---- fragment read offsets (uint4 units inside one operand stage)
+  const int fr_row = lane & 31, fr_half = lane >> 5;
+  const int fr_swz = swz(fr_row);
+  int fr_a[4], fr_b[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) fr_a[i] = (wm * 128 + i * 32 + fr_row) * 8;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) fr_b[j] = (j * 128 + wn * 32 + fr_row) * 8;
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+
+  uint4 pa[4], pb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    pa[i] = a_src[i][0];
+    pb[i] = b_src[i][0];
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    lds[st_off + i * 512] = pa[i];
+    lds[STAGE_VEC + st_off + i * 512] = pb[i];
+  }
+  __syncthreads();
+
+  const int KT = K / BK;
+  for (int kt = 0; kt < KT; ++kt) {
+    const int cur = (kt & 1) * 2 * STAGE_VEC;
+    const int nxt = ((kt + 1) & 1) * 2 * STAGE_VEC;
+    const bool more = kt + 1 < KT;
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        pa[i] = a_src[i][(kt + 1) * 8];
+        pb[i] = b_src[i][(kt + 1) * 8];
+      }
+    }
+    const uint4* As = lds + cur;
+    const uint4* Bs = lds + cur + STAGE_VEC;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int ch = (kk * 2 + fr_half) ^ fr_swz;
+      bf16x8 xa[4], wb[2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) xa[i] = __builtin_bit_cast(bf16x8, As[fr_a[i] + ch]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) wb[j] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ch]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[j], xa[i], acc[j][i], 0, 0, 0);
+    }
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        lds[nxt + st_off + i * 512] = pa[i];
+        lds[nxt + STAGE_VEC + st_off + i * 512] = pb[i];
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: lane holds, per 32x32 accumulator, token row (lane&31) and the weight
+  // rows 8*g + 4*(lane>>5) + {0..3}, g = 0..3
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m_local = wm * 128 + i * 32 + fr_row;
+    if (m_local >= tl.rows) continue;
+    const size_t rbase = (size_t)(tl.row0 + m_local) * N;
+    if (GATED) {
+      const int col0 = nblk * 128 + wn * 32 + 4 * fr_half;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float h[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float gv = acc[0][i][g * 4 + r], uv = acc[1][i][g * 4 + r];
+          h[r] = silu_f(gv) * uv;
+        }
+        const size_t o = rbase + col0 + 8 * g;
+        *reinterpret_cast<uint2*>(C + o) = make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+        if (Gs != nullptr) {
+          *reinterpret_cast<uint2*>(Gs + o) =
+              make_uint2(pack_bf16x2(acc[0][i][g * 4], acc[0][i][g * 4 + 1]),
+                         pack_bf16x2(acc[0][i][g * 4 + 2], acc[0][i][g * 4 + 3]));
+          *reinterpret_cast<uint2*>(Us + o) =
+              make_uint2(pack_bf16x2(acc[1][i][g * 4], acc[1][i][g * 4 + 1]),
+                         pack_bf16x2(acc[1][i][g * 4 + 2], acc[1][i][g * 4 + 3]));
+        }
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col0 = nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const size_t o = rbase + col0 + 8 * g;
+          *reinterpret_cast<uint2*>(C + o) =
+              make_uint2(pack_bf16x2(acc[j][i][g * 4], acc[j][i][g * 4 + 1]),
+                         pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]));
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+bool ffn_mfma_supported(const moe_ctx* c) {
+  const int d = c->cfg.d, f = c->cfg.f;
+  return c->cfg.dtype == MOE_BF16 && d % 256 == 0 && f % 128 == 0 && f / 128 < 4096 &&
+         d / 256 < 4096;
+}
+
+size_t ffn_mfma_order_entries(const moe_ctx* c) {
+  const int nt_up = c->cfg.f / 128, nt_down = c->cfg.d / 256;
+  return (size_t)c->max_mtiles[1] * (nt_up > nt_down ? nt_up : nt_down);
+}
+
+int launch_ffn_mfma(moe_ctx* c, const int32_t* counts, const int32_t* offsets, const void* x_packed,
+                    void* y_packed, void* G, void* U, hipStream_t s) {
+  const int d = c->cfg.d, f = c->cfg.f, E = c->cfg.E;
+  const int nt_up = f / 128, nt_down = d / 256;
+  const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
+  const void* const* W3 = c->d_wtab + 1 * MOE_MAX_EXPERTS;
+  const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
+  const int max_mt = c->max_mtiles[1];
+  hipLaunchKernelGGL(mfma_sched_kernel, dim3(32), dim3(256), 0, s, counts, offsets, W1, E,
+                     c->S_max, max_mt, nt_up, nt_down, c->d_sched[1], c->d_mtiles[1], c->d_order_up, c->d_order_down);
+  const int grid_up = ((max_mt * nt_up + 7) / 8) * 8;
+  const int grid_down = ((max_mt * nt_down + 7) / 8) * 8;
+  hipLaunchKernelGGL((ffn_mfma_kernel<true>), dim3(grid_up), dim3(NT), 0, s,
+                     (const uint16_t*)x_packed, c->d_sched[1], c->d_mtiles[1], c->d_order_up, nt_up,
+                     W1, W3, d, f, (uint16_t*)c->d_H, (uint16_t*)G, (uint16_t*)U);
+  hipLaunchKernelGGL((ffn_mfma_kernel<false>), dim3(grid_down), dim3(NT), 0, s,
+                     (const uint16_t*)c->d_H, c->d_sched[1], c->d_mtiles[1], c->d_order_down,
+                     nt_down, W2, (const void* const*)nullptr, f, d, (uint16_t*)y_packed,
+                     (uint16_t*)nullptr, (uint16_t*)nullptr);
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+}

@@ -1,0 +1,338 @@
+// Host side of the C ABI: argument validation, the context and its device workspace,
+// and the launches.  No entry point synchronises with the device except moe_create,
+// moe_destroy and moe_set_placement.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "moe_internal.h"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <typename T>
+hipError_t dev_alloc(T** p, size_t n) {
+  return hipMalloc(reinterpret_cast<void**>(p), std::max<size_t>(n, 1) * sizeof(T));
+}
+
+void free_all(moe_ctx* c) {
+  (void)hipFree(c->d_dest_rank);
+  (void)hipFree(c->d_seg_order);
+  (void)hipFree(c->d_chunk_hist);
+  (void)hipFree(c->d_ticket);
+  (void)hipFree(c->d_logits);
+  (void)hipFree(c->d_wtab);
+  for (int i = 0; i < 2; ++i) {
+    (void)hipFree(c->d_sched[i]);
+    (void)hipFree(c->d_mtiles[i]);
+  }
+  (void)hipFree(c->d_order_up);
+  (void)hipFree(c->d_order_down);
+  (void)hipFree(c->d_H);
+  (void)hipFree(c->d_dG);
+  (void)hipFree(c->d_dU);
+}
+
+int check_ctx_T(const moe_ctx* c, int32_t T) {
+  if (c == nullptr) return MOE_EINVAL;
+  if (T < 0 || T > c->cfg.T_max) return MOE_EINVAL;
+  return MOE_OK;
+}
+
+// Refresh the device copy of the pointer tables when the host tables changed.
+// rows: 0 W1, 1 W3, 2 W2, 3 dW1, 4 dW3, 5 dW2; a NULL table leaves its row as it is.
+int sync_tables(moe_ctx* c, const void* const* const tabs[6], hipStream_t s) {
+  const int E = c->cfg.E;
+  bool changed = !c->wtab_valid;
+  for (int r = 0; r < 6; ++r) {
+    if (tabs[r] == nullptr) continue;
+    if (std::memcmp(c->h_wtab[r], tabs[r], sizeof(void*) * E) != 0) {
+      std::memcpy(c->h_wtab[r], tabs[r], sizeof(void*) * E);
+      changed = true;
+    }
+  }
+  if (changed) {
+    if (hipMemcpyAsync(c->d_wtab, c->h_wtab, sizeof(c->h_wtab), hipMemcpyHostToDevice, s) !=
+        hipSuccess)
+      return MOE_EHIP;
+    c->wtab_valid = 1;
+  }
+  return MOE_OK;
+}
+
+int check_weight_tables(const moe_ctx* c, const void* const* W1, const void* const* W3,
+                        const void* const* W2) {
+  if (W1 == nullptr || W3 == nullptr || W2 == nullptr) return MOE_EINVAL;
+  for (int e = 0; e < c->cfg.E; ++e) {
+    const int n = (W1[e] != nullptr) + (W3[e] != nullptr) + (W2[e] != nullptr);
+    if (n != 0 && n != 3) return MOE_EINVAL;  // an expert is present with all three or none
+    if (!aligned16(W1[e]) || !aligned16(W3[e]) || !aligned16(W2[e])) return MOE_EINVAL;
+  }
+  return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_strerror(int status) {
+  switch (status) {
+    case MOE_OK: return "ok";
+    case MOE_EINVAL: return "invalid argument";
+    case MOE_EUNSUPPORTED: return "unsupported configuration";
+    case MOE_ENOMEM: return "out of device memory";
+    case MOE_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int moe_create(moe_ctx** out, const moe_config* cfg) {
+  if (out == nullptr) return MOE_EINVAL;
+  *out = nullptr;
+  if (cfg == nullptr) return MOE_EINVAL;
+  if (cfg->dtype != MOE_F32 && cfg->dtype != MOE_BF16) return MOE_EINVAL;
+  if (cfg->E < 1 || cfg->E > MOE_MAX_EXPERTS) return MOE_EINVAL;
+  if (cfg->k < 1 || cfg->k > cfg->E || cfg->k > MOE_MAX_TOPK) return MOE_EINVAL;
+  if (cfg->R < 1 || cfg->R > MOE_MAX_RANKS) return MOE_EINVAL;
+  if (cfg->local_rank < 0 || cfg->local_rank >= cfg->R) return MOE_EINVAL;
+  if (cfg->T_max < 0 || cfg->d < 8 || cfg->f < 8) return MOE_EINVAL;
+  if (cfg->d % 8 != 0 || cfg->f % 8 != 0) return MOE_EINVAL;
+  if (cfg->renormalize != 0 && cfg->renormalize != 1) return MOE_EINVAL;
+  const long long S = (long long)cfg->T_max * cfg->k;
+  if (S > (1ll << 22)) return MOE_EUNSUPPORTED;                           // grid / int32 headroom
+  if (S * std::max(cfg->d, cfg->f) > (1ll << 40)) return MOE_EUNSUPPORTED;
+
+  moe_ctx* c = new (std::nothrow) moe_ctx();
+  if (c == nullptr) return MOE_ENOMEM;
+  std::memset(c, 0, sizeof(*c));
+  c->cfg = *cfg;
+  c->elem = cfg->dtype == MOE_BF16 ? 2 : 4;
+  c->ffn_path = MOE_FFN_AUTO;
+  c->S_max = (int32_t)S;
+  if (hipGetDevice(&c->device) != hipSuccess) {
+    delete c;
+    return MOE_EHIP;
+  }
+  const int E = cfg->E;
+  c->n_chunks_max = std::max<int>(1, (int)((S + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK));
+  c->max_mtiles[0] = (int)(S / GENERIC_BM) + E;
+  c->max_mtiles[1] = (int)(S / MFMA_BM) + E;
+  bool ok = true;
+  ok = ok && dev_alloc(&c->d_dest_rank, E) == hipSuccess;
+  ok = ok && dev_alloc(&c->d_seg_order, E) == hipSuccess;
+  ok = ok && dev_alloc(&c->d_chunk_hist, (size_t)c->n_chunks_max * E) == hipSuccess;
+  ok = ok && dev_alloc(&c->d_ticket, 1) == hipSuccess;
+  ok = ok && dev_alloc(&c->d_logits, (size_t)cfg->T_max * E) == hipSuccess;
+  ok = ok && dev_alloc(&c->d_wtab, 6 * MOE_MAX_EXPERTS) == hipSuccess;
+  for (int i = 0; i < 2 && ok; ++i) {
+    ok = ok && dev_alloc(&c->d_sched[i], 1) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_mtiles[i], c->max_mtiles[i]) == hipSuccess;
+  }
+  if (ok && ffn_mfma_supported(c)) {
+    const size_t n = ffn_mfma_order_entries(c);
+    ok = ok && dev_alloc(&c->d_order_up, n) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_order_down, n) == hipSuccess;
+  }
+  ok = ok && hipMalloc(&c->d_H, std::max<size_t>((size_t)S * cfg->f * c->elem, 16)) == hipSuccess;
+  ok = ok && hipMemset(c->d_ticket, 0, sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMemset(c->d_wtab, 0, sizeof(void*) * 6 * MOE_MAX_EXPERTS) == hipSuccess;
+  if (!ok) {
+    (void)hipGetLastError();
+    free_all(c);
+    delete c;
+    return MOE_ENOMEM;
+  }
+  int32_t dest[MOE_MAX_EXPERTS];
+  const int per = (E + cfg->R - 1) / cfg->R;
+  for (int e = 0; e < E; ++e) dest[e] = e / per;
+  const int st = moe_set_placement(c, dest);
+  if (st != MOE_OK) {
+    free_all(c);
+    delete c;
+    return st;
+  }
+  *out = c;
+  return MOE_OK;
+}
+
+int moe_destroy(moe_ctx* c) {
+  if (c == nullptr) return MOE_OK;
+  (void)hipDeviceSynchronize();
+  free_all(c);
+  delete c;
+  return MOE_OK;
+}
+
+int moe_set_placement(moe_ctx* c, const int32_t* expert_dest_rank) {
+  if (c == nullptr || expert_dest_rank == nullptr) return MOE_EINVAL;
+  const int E = c->cfg.E;
+  for (int e = 0; e < E; ++e)
+    if (expert_dest_rank[e] < 0 || expert_dest_rank[e] >= c->cfg.R) return MOE_EINVAL;
+  int32_t order[MOE_MAX_EXPERTS];
+  for (int e = 0; e < E; ++e) order[e] = e;
+  std::stable_sort(order, order + E, [&](int a, int b) {
+    return expert_dest_rank[a] < expert_dest_rank[b];
+  });
+  if (hipMemcpy(c->d_dest_rank, expert_dest_rank, sizeof(int32_t) * E, hipMemcpyHostToDevice) !=
+          hipSuccess ||
+      hipMemcpy(c->d_seg_order, order, sizeof(int32_t) * E, hipMemcpyHostToDevice) != hipSuccess)
+    return MOE_EHIP;
+  return MOE_OK;
+}
+
+int moe_set_ffn_path(moe_ctx* c, int path) {
+  if (c == nullptr || (path != MOE_FFN_AUTO && path != MOE_FFN_VALU)) return MOE_EINVAL;
+  c->ffn_path = path;
+  return MOE_OK;
+}
+
+int moe_route_logits(moe_ctx* c, const float* logits, int32_t T, int32_t* topk_idx, float* topk_w,
+                     void* stream) {
+  int st = check_ctx_T(c, T);
+  if (st != MOE_OK) return st;
+  if (T == 0) return MOE_OK;
+  if (logits == nullptr || topk_idx == nullptr || topk_w == nullptr) return MOE_EINVAL;
+  if (!aligned16(logits) || !aligned16(topk_idx) || !aligned16(topk_w)) return MOE_EINVAL;
+  return launch_route_select(c, logits, T, topk_idx, topk_w, (hipStream_t)stream);
+}
+
+int moe_route(moe_ctx* c, const void* x, const void* Wg, const float* bias, int32_t T,
+              float* logits, int32_t* topk_idx, float* topk_w, void* stream) {
+  int st = check_ctx_T(c, T);
+  if (st != MOE_OK) return st;
+  if (T == 0) return MOE_OK;
+  if (x == nullptr || Wg == nullptr || topk_idx == nullptr || topk_w == nullptr) return MOE_EINVAL;
+  if (!aligned16(x) || !aligned16(Wg) || !aligned16(bias) || !aligned16(logits) ||
+      !aligned16(topk_idx) || !aligned16(topk_w))
+    return MOE_EINVAL;
+  float* L = logits != nullptr ? logits : c->d_logits;
+  st = launch_gate_logits(c, x, Wg, bias, T, L, (hipStream_t)stream);
+  if (st != MOE_OK) return st;
+  return launch_route_select(c, L, T, topk_idx, topk_w, (hipStream_t)stream);
+}
+
+int moe_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int32_t T, void* x_packed,
+                 int32_t* slot_to_row, int32_t* row_to_slot, int32_t* expert_counts,
+                 int32_t* expert_offsets, int32_t* rank_counts, int32_t* rank_offsets,
+                 void* stream) {
+  int st = check_ctx_T(c, T);
+  if (st != MOE_OK) return st;
+  if (expert_counts == nullptr || expert_offsets == nullptr || rank_counts == nullptr ||
+      rank_offsets == nullptr)
+    return MOE_EINVAL;
+  if ((x == nullptr) != (x_packed == nullptr)) return MOE_EINVAL;
+  if (T > 0 && (topk_idx == nullptr || slot_to_row == nullptr || row_to_slot == nullptr))
+    return MOE_EINVAL;
+  if (!aligned16(x) || !aligned16(x_packed) || !aligned16(topk_idx) || !aligned16(slot_to_row) ||
+      !aligned16(row_to_slot))
+    return MOE_EINVAL;
+  return launch_dispatch(c, x, topk_idx, T, x_packed, slot_to_row, row_to_slot, expert_counts,
+                         expert_offsets, rank_counts, rank_offsets, (hipStream_t)stream);
+}
+
+int moe_expert_ffn(moe_ctx* c, const void* x_packed, const int32_t* expert_counts,
+                   const int32_t* expert_offsets, const void* const* W1, const void* const* W3,
+                   const void* const* W2, int32_t T, void* y_packed, void* G_save, void* U_save,
+                   void* stream) {
+  int st = check_ctx_T(c, T);
+  if (st != MOE_OK) return st;
+  st = check_weight_tables(c, W1, W3, W2);
+  if (st != MOE_OK) return st;
+  if (T == 0) return MOE_OK;
+  if (x_packed == nullptr || y_packed == nullptr || expert_counts == nullptr ||
+      expert_offsets == nullptr)
+    return MOE_EINVAL;
+  if ((G_save == nullptr) != (U_save == nullptr)) return MOE_EINVAL;
+  if (!aligned16(x_packed) || !aligned16(y_packed) || !aligned16(G_save) || !aligned16(U_save))
+    return MOE_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  const void* const* tabs[6] = {W1, W3, W2, nullptr, nullptr, nullptr};
+  st = sync_tables(c, tabs, s);
+  if (st != MOE_OK) return st;
+  if (c->ffn_path == MOE_FFN_AUTO && ffn_mfma_supported(c))
+    return launch_ffn_mfma(c, expert_counts, expert_offsets, x_packed, y_packed, G_save, U_save, s);
+  st = launch_build_sched(c, expert_counts, expert_offsets, 0, s);
+  if (st != MOE_OK) return st;
+  return launch_ffn_generic(c, x_packed, y_packed, G_save, U_save, c->d_H, s);
+}
+
+int moe_combine(moe_ctx* c, const void* y_packed, const int32_t* slot_to_row, const float* topk_w,
+                int32_t T, void* out, void* stream) {
+  int st = check_ctx_T(c, T);
+  if (st != MOE_OK) return st;
+  if (T == 0) return MOE_OK;
+  if (y_packed == nullptr || slot_to_row == nullptr || topk_w == nullptr || out == nullptr)
+    return MOE_EINVAL;
+  if (!aligned16(y_packed) || !aligned16(out)) return MOE_EINVAL;
+  return launch_combine(c, y_packed, slot_to_row, topk_w, T, out, (hipStream_t)stream);
+}
+
+int moe_combine_bwd(moe_ctx* c, const void* dout, const void* y_packed, const int32_t* slot_to_row,
+                    const float* topk_w, int32_t T, void* dy_packed, float* dtopk_w,
+                    void* stream) {
+  int st = check_ctx_T(c, T);
+  if (st != MOE_OK) return st;
+  if (T == 0) return MOE_OK;
+  if (dout == nullptr || y_packed == nullptr || slot_to_row == nullptr || topk_w == nullptr ||
+      dy_packed == nullptr || dtopk_w == nullptr)
+    return MOE_EINVAL;
+  if (!aligned16(dout) || !aligned16(y_packed) || !aligned16(dy_packed)) return MOE_EINVAL;
+  return launch_combine_bwd(c, dout, y_packed, slot_to_row, topk_w, T, dy_packed, dtopk_w,
+                            (hipStream_t)stream);
+}
+
+int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, const void* G_save,
+                       const void* U_save, const int32_t* expert_counts,
+                       const int32_t* expert_offsets, const void* const* W1, const void* const* W3,
+                       const void* const* W2, int32_t T, void* dx_packed, float* const* dW1,
+                       float* const* dW3, float* const* dW2, void* stream) {
+  int st = check_ctx_T(c, T);
+  if (st != MOE_OK) return st;
+  st = check_weight_tables(c, W1, W3, W2);
+  if (st != MOE_OK) return st;
+  if (dW1 == nullptr || dW3 == nullptr || dW2 == nullptr) return MOE_EINVAL;
+  for (int e = 0; e < c->cfg.E; ++e)
+    if (!aligned16(dW1[e]) || !aligned16(dW3[e]) || !aligned16(dW2[e])) return MOE_EINVAL;
+  if (T == 0) return MOE_OK;
+  if (dy_packed == nullptr || x_packed == nullptr || G_save == nullptr || U_save == nullptr ||
+      expert_counts == nullptr || expert_offsets == nullptr || dx_packed == nullptr)
+    return MOE_EINVAL;
+  if (!aligned16(dy_packed) || !aligned16(x_packed) || !aligned16(G_save) || !aligned16(U_save) ||
+      !aligned16(dx_packed))
+    return MOE_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  if (c->d_dG == nullptr) {  // first backward call: allocate the temporaries
+    const size_t bytes = std::max<size_t>((size_t)c->S_max * c->cfg.f * c->elem, 16);
+    if (hipMalloc(&c->d_dG, bytes) != hipSuccess || hipMalloc(&c->d_dU, bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      (void)hipFree(c->d_dG);
+      c->d_dG = nullptr;
+      return MOE_ENOMEM;
+    }
+  }
+  const void* const* tabs[6] = {W1,
+                                W3,
+                                W2,
+                                reinterpret_cast<const void* const*>(dW1),
+                                reinterpret_cast<const void* const*>(dW3),
+                                reinterpret_cast<const void* const*>(dW2)};
+  st = sync_tables(c, tabs, s);
+  if (st != MOE_OK) return st;
+  st = launch_build_sched(c, expert_counts, expert_offsets, 0, s);
+  if (st != MOE_OK) return st;
+  return launch_ffn_bwd_generic(c, dy_packed, x_packed, G_save, U_save, expert_counts,
+                                expert_offsets, dx_packed, c->d_dG, c->d_dU, c->d_H, s);
+}
+
+int moe_dispatch_bwd(moe_ctx* c, const void* dx_packed, const int32_t* slot_to_row, int32_t T,
+                     void* dx, void* stream) {
+  int st = check_ctx_T(c, T);
+  if (st != MOE_OK) return st;
+  if (T == 0) return MOE_OK;
+  if (dx_packed == nullptr || slot_to_row == nullptr || dx == nullptr) return MOE_EINVAL;
+  if (!aligned16(dx_packed) || !aligned16(dx)) return MOE_EINVAL;
+  return launch_dispatch_bwd(c, dx_packed, slot_to_row, T, dx, (hipStream_t)stream);
+}
+
+}  // extern "C"

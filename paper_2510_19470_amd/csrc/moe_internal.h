@@ -1,0 +1,86 @@
+// Internal declarations shared by the HIP translation units of libmoe_hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern in memory
+
+// One row block of one expert segment, as the grouped GEMMs see it.
+struct MTile {
+  int32_t expert;
+  int32_t row0;   // first packed row
+  int32_t rows;   // valid rows (1..BM)
+  int32_t pad;
+};
+
+// Tile schedule built on the device from expert_counts/offsets (no host sync).
+struct TileSched {
+  int32_t n_mtiles;     // number of valid MTile entries
+  int32_t pad[3];
+};
+
+struct moe_ctx {
+  moe_config cfg;
+  int device;
+  int elem;               // bytes per stored element
+  int ffn_path;           // MOE_FFN_AUTO / MOE_FFN_VALU
+  // placement
+  int32_t* d_dest_rank;   // [E]
+  int32_t* d_seg_order;   // [E] experts in (dest_rank, id) order
+  // dispatch workspace
+  int32_t n_chunks_max;   // slot chunks of DISPATCH_CHUNK
+  int32_t* d_chunk_hist;  // [n_chunks_max][E] counts, then exclusive prefix over chunks
+  int32_t* d_ticket;      // [1] arrival counter of the fused histogram+scan
+  float* d_logits;        // [T_max][E] when the caller does not want the logits
+  // expert weight pointer tables: device copy [6][MOE_MAX_EXPERTS] (W1, W3, W2, dW1, dW3,
+  // dW2), refreshed only when the host tables change
+  const void** d_wtab;
+  const void* h_wtab[6][MOE_MAX_EXPERTS];
+  int wtab_valid;
+  // grouped GEMM schedules: [0] 64-row tiles (vector ALU path), [1] 256-row tiles (MFMA)
+  TileSched* d_sched[2];
+  MTile* d_mtiles[2];
+  int32_t max_mtiles[2];
+  // activations between the two GEMMs, and the backward's temporaries (allocated on the
+  // first backward call)
+  uint32_t* d_order_up;   // MFMA tile order of the gate/up GEMM
+  uint32_t* d_order_down; // ... and of the down GEMM
+  int32_t S_max;          // T_max*k
+  void* d_H;              // [T_max*k][f]
+  void* d_dG;             // [T_max*k][f]
+  void* d_dU;             // [T_max*k][f]
+};
+
+#define DISPATCH_CHUNK 1024      // slots per histogram / ranking block
+#define GENERIC_BM 64
+#define MFMA_BM 256
+
+// ---- launchers (defined in the .hip files); all return a moe_status ----
+int launch_route_select(const moe_ctx* c, const float* logits, int T, int32_t* idx, float* w,
+                        hipStream_t s);
+int launch_gate_logits(const moe_ctx* c, const void* x, const void* Wg, const float* bias, int T,
+                       float* logits, hipStream_t s);
+int launch_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int T, void* x_packed,
+                    int32_t* slot_to_row, int32_t* row_to_slot, int32_t* expert_counts,
+                    int32_t* expert_offsets, int32_t* rank_counts, int32_t* rank_offsets,
+                    hipStream_t s);
+int launch_combine(const moe_ctx* c, const void* y_packed, const int32_t* slot_to_row,
+                   const float* w, int T, void* out, hipStream_t s);
+int launch_combine_bwd(const moe_ctx* c, const void* dout, const void* y_packed,
+                       const int32_t* slot_to_row, const float* w, int T, void* dy_packed,
+                       float* dw, hipStream_t s);
+int launch_dispatch_bwd(const moe_ctx* c, const void* dx_packed, const int32_t* slot_to_row, int T,
+                        void* dx, hipStream_t s);
+int launch_build_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets, int which,
+                       hipStream_t s);
+int launch_ffn_generic(moe_ctx* c, const void* x_packed, void* y_packed, void* G, void* U,
+                       void* H_tmp, hipStream_t s);
+bool ffn_mfma_supported(const moe_ctx* c);
+size_t ffn_mfma_order_entries(const moe_ctx* c);
+int launch_ffn_mfma(moe_ctx* c, const int32_t* counts, const int32_t* offsets, const void* x_packed,
+                    void* y_packed, void* G, void* U, hipStream_t s);
+int launch_ffn_bwd_generic(moe_ctx* c, const void* dy, const void* xp, const void* G,
+                           const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
+                           void* dG_tmp, void* dU_tmp, void* H_tmp, hipStream_t s);

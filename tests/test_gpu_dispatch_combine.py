@@ -1,0 +1,148 @@
+"""GPU parity: dispatch (bit-exact maps, counts, offsets, bit copy of rows), combine and the
+row-wise backward kernels."""
+import numpy as np
+import pytest
+import torch
+
+import moe_workloads as wl
+from oracle import moe_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_dispatch(cfg, idx_np, dest, x_stored):
+    from gpu_common import DEV, moe, i32, to_device, to_host_bits
+    ctx = moe.moe_create(T_max=max(cfg.T, 1), d=cfg.d, E=cfg.E, k=cfg.k, f=cfg.f, R=cfg.R,
+                         local_rank=cfg.local_rank,
+                         dtype=moe.MOE_BF16 if cfg.dtype == "bf16" else moe.MOE_F32)
+    moe.moe_set_placement(ctx, dest)
+    x = to_device(x_stored, cfg.dtype)
+    idx = torch.from_numpy(idx_np).to(DEV)
+    out = moe.moe_dispatch(ctx, x, idx)
+    torch.cuda.synchronize()
+    want = orc.dispatch_maps(idx_np, dest, cfg.R)
+    got = (out.expert_counts, out.expert_offsets, out.rank_counts, out.rank_offsets,
+           out.slot_to_row, out.row_to_slot)
+    for name, g, w in zip(("counts", "offsets", "rank_counts", "rank_offsets", "slot_to_row",
+                           "row_to_slot"), got, want):
+        assert np.array_equal(i32(g), w), name
+    xp_want = orc.pack_rows(x_stored, want[5], cfg.k)
+    xp_got = to_host_bits(out.x_packed)
+    assert np.array_equal(xp_got, xp_want.view(xp_got.dtype))       # bit copy
+    # a second call on the same context gives the same answer (workspace state is reset)
+    out2 = moe.moe_dispatch(ctx, x, idx)
+    torch.cuda.synchronize()
+    assert torch.equal(out.slot_to_row, out2.slot_to_row)
+    assert torch.equal(out.row_to_slot, out2.row_to_slot)
+    assert torch.equal(out.x_packed.view(torch.int16 if cfg.dtype == "bf16" else torch.int32),
+                       out2.x_packed.view(torch.int16 if cfg.dtype == "bf16" else torch.int32))
+    ctx.close()
+    return want
+
+
+@pytest.mark.parametrize("name", ["tiny", "small", "mixtral", "finegrained", "train"])
+def test_dispatch_full_size_configs(name):
+    from gpu_common import say, vals
+    cfg = wl.CONFIGS[name]
+    say(f"[dispatch] config={name} T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} S={cfg.S}")
+    inp = wl.make_inputs(cfg, experts="none")
+    L = orc.gate_logits(vals(inp.x, cfg.dtype), vals(inp.Wg, cfg.dtype), inp.bias).astype(np.float32)
+    idx = orc.topk_select(L, cfg.k)
+    want = _check_dispatch(cfg, idx, inp.dest_rank, inp.x)
+    say(f"    n_loc={int(want[2][cfg.local_rank])} of S={cfg.S}; max count={int(want[0].max())}")
+    if name == "finegrained":
+        # the four hottest non-home experts are the migrated ones (ids 8..11)
+        hot = np.argsort(-want[0][8:], kind="stable")[:4] + 8
+        assert sorted(hot.tolist()) == [8, 9, 10, 11]
+
+
+@pytest.mark.parametrize("T,E,k,R,d,case", [
+    (0, 8, 2, 2, 64, "empty"), (1, 8, 2, 2, 64, "one"), (1023, 16, 3, 4, 72, "ragged"),
+    (2049, 256, 16, 8, 64, "maxE"), (3000, 7, 1, 7, 136, "k1"), (1500, 8, 2, 2, 64, "allone"),
+    (700, 12, 2, 3, 64, "hole"), (5000, 64, 6, 256, 64, "manyranks"),
+])
+def test_dispatch_edge_cases(T, E, k, R, d, case):
+    from gpu_common import say
+    say(f"[dispatch-edge] {case}: T={T} E={E} k={k} R={R} d={d}")
+    cfg = wl.MoEConfig(case, 0, "f32", T=T, d=d, E=E, k=k, f=64, R=R)
+    rng = np.random.default_rng(T + E)
+    if case == "allone":
+        idx = np.tile(np.array([[3, 5]], np.int32), (T, 1))            # two experts get everything
+    elif case == "hole":
+        idx = wl.random_routing(T, 6, k, 3) * 2                         # odd experts get nothing
+    else:
+        idx = wl.random_routing(T, E, k, seed=T + k, skew=0.5) if T else np.zeros((0, k), np.int32)
+    dest = rng.integers(0, R, size=E).astype(np.int32) if R > 1 else np.zeros(E, np.int32)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    _check_dispatch(cfg, idx, dest, x)
+
+
+def test_dispatch_placement_only_relabels():
+    """The same routing under two placement maps: counts and per-expert token sequences are
+    identical, only offsets move; a fetched expert moves exactly its rows to the local chunk
+    (paper Sec. 3.2)."""
+    from gpu_common import DEV, moe, say, i32
+    say("[dispatch] placement relabel invariant")
+    cfg = wl.scaled(wl.CONFIGS["small"], T=2048)
+    idx_np = wl.random_routing(cfg.T, cfg.E, cfg.k, 77)
+    idx = torch.from_numpy(idx_np).to(DEV)
+    ctx = moe.moe_create(T_max=cfg.T, d=cfg.d, E=cfg.E, k=cfg.k, f=cfg.f, R=cfg.R)
+    res = []
+    for dest in (wl.home_rank(cfg), wl.expert_dest_rank(cfg)):
+        moe.moe_set_placement(ctx, dest)
+        o = moe.moe_dispatch(ctx, None, idx)
+        torch.cuda.synchronize()
+        res.append((i32(o.expert_counts), i32(o.expert_offsets), i32(o.rank_counts), i32(o.row_to_slot)))
+    a, b = res
+    assert np.array_equal(a[0], b[0])
+    for e in range(cfg.E):
+        assert np.array_equal(a[3][a[1][e]:a[1][e] + a[0][e]], b[3][b[1][e]:b[1][e] + b[0][e]])
+    moved = a[0][5] + a[0][9]
+    assert b[2][0] - a[2][0] == moved and a[2].sum() == b[2].sum() == cfg.S
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,T", [("tiny", None), ("small", None), ("finegrained", 2048),
+                                    ("train", 1024), ("mixtral", 512)])
+def test_combine_and_rowwise_backward(name, T):
+    from gpu_common import DEV, TOL, moe, say, nerr, vals, to_device, to_host_f32
+    cfg = wl.CONFIGS[name]
+    if T is not None:
+        cfg = wl.scaled(cfg, T=T)
+    say(f"[combine] config={name} T={cfg.T} d={cfg.d} k={cfg.k} dtype={cfg.dtype}")
+    rng = np.random.default_rng(cfg.seed)
+    inp = wl.make_inputs(cfg, experts="none")
+    idx_np = wl.random_routing(cfg.T, cfg.E, cfg.k, cfg.seed, skew=0.3)
+    w_np = rng.random((cfg.T, cfg.k)).astype(np.float32)
+    w_np /= w_np.sum(1, keepdims=True)
+    _, _, _, _, s2r, r2s = orc.dispatch_maps(idx_np, inp.dest_rank, cfg.R)
+    y_st = wl.store(rng.standard_normal((cfg.S, cfg.d), dtype=np.float32), cfg.dtype)
+    do_st = wl.store(rng.standard_normal((cfg.T, cfg.d), dtype=np.float32), cfg.dtype)
+    ctx = moe.moe_create(T_max=cfg.T, d=cfg.d, E=cfg.E, k=cfg.k, f=cfg.f, R=cfg.R,
+                         dtype=moe.MOE_BF16 if cfg.dtype == "bf16" else moe.MOE_F32)
+    y = to_device(y_st, cfg.dtype)
+    s2r_d = torch.from_numpy(s2r).to(DEV)
+    w = torch.from_numpy(w_np).to(DEV)
+    tol = TOL[cfg.dtype]
+    out = moe.moe_combine(ctx, y, s2r_d, w)
+    torch.cuda.synchronize()
+    assert nerr(to_host_f32(out), orc.combine(vals(y_st, cfg.dtype), s2r, w_np)) <= tol
+    # identity experts: y_packed := x_packed, normalised weights -> out = x (one rounding)
+    xp = to_device(orc.pack_rows(inp.x, r2s, cfg.k), cfg.dtype)
+    out_id = moe.moe_combine(ctx, xp, s2r_d, w)
+    torch.cuda.synchronize()
+    xv = vals(inp.x, cfg.dtype)
+    ulp = 2.0 ** -8 if cfg.dtype == "bf16" else 2.0 ** -22
+    assert np.max(np.abs(to_host_f32(out_id) - xv) / np.maximum(np.abs(xv), 1e-3)) <= ulp
+    # backward of combine
+    do = to_device(do_st, cfg.dtype)
+    dy, dw = moe.moe_combine_bwd(ctx, do, y, s2r_d, w)
+    torch.cuda.synchronize()
+    dy_o, dw_o = orc.combine_bwd(vals(do_st, cfg.dtype), vals(y_st, cfg.dtype), s2r, w_np)
+    assert nerr(to_host_f32(dy), dy_o) <= tol
+    assert nerr(dw.cpu().numpy(), dw_o) <= (1e-5 if cfg.dtype == "f32" else 1e-5)
+    # backward of dispatch
+    dx = moe.moe_dispatch_bwd(ctx, y, s2r_d)
+    torch.cuda.synchronize()
+    assert nerr(to_host_f32(dx), orc.dispatch_bwd(vals(y_st, cfg.dtype), s2r, cfg.T, cfg.k)) <= tol
+    ctx.close()

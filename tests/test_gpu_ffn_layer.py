@@ -1,0 +1,231 @@
+"""GPU parity: grouped SwiGLU expert FFN (MFMA and vector-ALU kernels), the whole layer in
+loopback, and the backward, against the float64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import moe_workloads as wl
+from oracle import moe_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+def _f64_list(ws, dtype):
+    return [None if w is None else wl.stored_to_f32(w, dtype).astype(np.float64) for w in ws]
+
+
+def _run_ffn_case(cfg, idx_np, path, experts_present=None, save=False):
+    """FFN alone on a given routing: every float output against the oracle."""
+    from gpu_common import DEV, TOL, moe, nerr, vals, to_device, to_host_f32, layer_from_inputs
+    inp = wl.make_inputs(cfg)
+    if experts_present is not None:
+        for e in range(cfg.E):
+            if e not in experts_present:
+                inp.W1[e] = inp.W3[e] = inp.W2[e] = None
+    lay = layer_from_inputs(inp)
+    moe.moe_set_ffn_path(lay.ctx, path)
+    cnt, off, _, _, s2r, r2s = orc.dispatch_maps(idx_np, inp.dest_rank, cfg.R)
+    xp_st = orc.pack_rows(inp.x, r2s, cfg.k)
+    xp = to_device(xp_st, cfg.dtype)
+    sentinel = 3.0
+    y0 = torch.full((cfg.S, cfg.d), sentinel, dtype=xp.dtype, device=DEV)
+    y, G, U = moe.moe_expert_ffn(lay.ctx, xp, torch.from_numpy(cnt).to(DEV),
+                                 torch.from_numpy(off).to(DEV), lay.W1, lay.W3, lay.W2,
+                                 y_packed=y0, save=save)
+    torch.cuda.synchronize()
+    yo, Go, Uo = orc.expert_ffn(vals(xp_st, cfg.dtype), cnt, off, _f64_list(inp.W1, cfg.dtype),
+                                _f64_list(inp.W3, cfg.dtype), _f64_list(inp.W2, cfg.dtype))
+    yg = to_host_f32(y).astype(np.float64)
+    tol = TOL[cfg.dtype]
+    done = np.zeros(cfg.S, bool)
+    for e in range(cfg.E):
+        if inp.W1[e] is not None:
+            done[off[e]:off[e] + cnt[e]] = True
+    assert nerr(yg[done], yo[done]) <= tol
+    assert np.all(yg[~done] == sentinel)          # rows of absent experts are left untouched
+    if save:
+        assert nerr(to_host_f32(G)[done], Go[done]) <= tol
+        assert nerr(to_host_f32(U)[done], Uo[done]) <= tol
+    lay.close()
+    return nerr(yg[done], yo[done])
+
+
+def test_ffn_tiny_fp32():
+    from gpu_common import moe, say
+    cfg = wl.CONFIGS["tiny"]
+    say(f"[ffn] tiny fp32 T={cfg.T}")
+    idx = wl.random_routing(cfg.T, cfg.E, cfg.k, 5)
+    err = _run_ffn_case(cfg, idx, moe.MOE_FFN_AUTO, save=True)
+    say(f"    normalised max error {err:.3e}")
+
+
+@pytest.mark.parametrize("path", ["mfma", "valu"])
+@pytest.mark.parametrize("T,d,E,k,f,skew,present", [
+    (700, 256, 4, 2, 128, 0.0, None),           # several row tiles, ragged tails
+    (1031, 512, 8, 2, 384, 1.5, None),          # skewed: one expert > 256 rows, some < 32
+    (300, 256, 16, 1, 256, 2.5, None),          # experts with zero tokens
+    (515, 768, 6, 3, 640, 0.5, (0, 2, 5)),      # only some experts resident
+])
+def test_ffn_bf16_reduced_shapes(path, T, d, E, k, f, skew, present):
+    from gpu_common import moe, say
+    say(f"[ffn] bf16 path={path} T={T} d={d} E={E} k={k} f={f} skew={skew} present={present}")
+    cfg = wl.MoEConfig("case", 4242 + T, "bf16", T=T, d=d, E=E, k=k, f=f, R=2)
+    idx = wl.random_routing(T, E, k, seed=T, skew=skew)
+    err = _run_ffn_case(cfg, idx, moe.MOE_FFN_AUTO if path == "mfma" else moe.MOE_FFN_VALU,
+                        experts_present=present, save=True)
+    say(f"    normalised max error {err:.3e}")
+
+
+@pytest.mark.parametrize("name,T", [("tiny", None), ("small", 1024), ("finegrained", 1024),
+                                    ("train", 1024)])
+def test_whole_layer_loopback_matches_dense_definition(name, T):
+    """All experts present (remote segments looped back): out equals the layer's definition,
+    and does not depend on the placement map."""
+    from gpu_common import DEV, TOL, moe, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
+    cfg = wl.CONFIGS[name]
+    if T is not None:
+        cfg = wl.scaled(cfg, T=T)
+    say(f"[layer] loopback config={name} T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} f={cfg.f}")
+    inp = wl.make_inputs(cfg)
+    lay = layer_from_inputs(inp)
+    x = to_device(inp.x, cfg.dtype)
+    fwd = lay.forward(x)
+    torch.cuda.synchronize()
+    idx = i32(fwd["topk_idx"])
+    w = fwd["topk_w"].cpu().numpy()
+    dense = orc.layer_dense(vals(inp.x, cfg.dtype), idx, w, _f64_list(inp.W1, cfg.dtype),
+                            _f64_list(inp.W3, cfg.dtype), _f64_list(inp.W2, cfg.dtype))
+    err = nerr(to_host_f32(fwd["out"]), dense)
+    say(f"    normalised max error vs dense definition {err:.3e}")
+    assert err <= TOL[cfg.dtype]
+    # integer outputs against the oracle on the GPU's own routing
+    want = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
+    d = fwd["disp"]
+    for g, wv in zip((d.expert_counts, d.expert_offsets, d.rank_counts, d.rank_offsets,
+                      d.slot_to_row, d.row_to_slot), want):
+        assert np.array_equal(i32(g), wv)
+    # another placement: same output up to rounding (here bitwise, rows are independent)
+    moe.moe_set_placement(lay.ctx, np.zeros(cfg.E, np.int32))
+    fwd2 = lay.forward(x)
+    torch.cuda.synchronize()
+    assert nerr(to_host_f32(fwd2["out"]), to_host_f32(fwd["out"])) <= 1e-6
+    lay.close()
+
+
+def test_small_config_full_size():
+    """Config 'small' at full size, resident experts only (the production launch shape):
+    every row of the compute region against the oracle."""
+    from gpu_common import DEV, TOL, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
+    cfg = wl.CONFIGS["small"]
+    say(f"[ffn] small full size T={cfg.T}")
+    inp = wl.make_inputs(cfg, experts="resident")
+    lay = layer_from_inputs(inp)
+    x = to_device(inp.x, cfg.dtype)
+    fwd = lay.forward(x)
+    torch.cuda.synchronize()
+    idx = i32(fwd["topk_idx"])
+    cnt, off, rcnt, roff, s2r, r2s = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
+    xp = orc.pack_rows(inp.x, r2s, cfg.k)
+    yo, _, _ = orc.expert_ffn(vals(xp, cfg.dtype), cnt, off, _f64_list(inp.W1, cfg.dtype),
+                              _f64_list(inp.W3, cfg.dtype), _f64_list(inp.W2, cfg.dtype))
+    lo, hi = int(roff[cfg.local_rank]), int(roff[cfg.local_rank + 1])
+    say(f"    compute region rows [{lo},{hi})")
+    err = nerr(to_host_f32(fwd["y_packed"])[lo:hi], yo[lo:hi])
+    say(f"    normalised max error {err:.3e}")
+    assert err <= TOL["bf16"]
+    lay.close()
+
+
+def _sampled_rows_check(cfg, n_per_expert=3):
+    """Full-size launch; the oracle recomputes a few packed rows per resident expert (first,
+    last and one inside -- the last row sits in a ragged tail tile)."""
+    from gpu_common import TOL, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
+    inp = wl.make_inputs(cfg, experts="resident")
+    lay = layer_from_inputs(inp)
+    x = to_device(inp.x, cfg.dtype)
+    fwd = lay.forward(x)
+    torch.cuda.synchronize()
+    idx = i32(fwd["topk_idx"])
+    cnt, off, rcnt, roff, s2r, r2s = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
+    d = fwd["disp"]
+    assert np.array_equal(i32(d.slot_to_row), s2r) and np.array_equal(i32(d.expert_counts), cnt)
+    yg = to_host_f32(fwd["y_packed"])
+    xv = wl.stored_to_f32(inp.x, cfg.dtype)
+    worst = 0.0
+    for e in wl.resident_experts(cfg):
+        n = int(cnt[e])
+        if n == 0:
+            continue
+        rows = sorted({int(off[e]), int(off[e]) + n // 2, int(off[e]) + n - 1})[:n_per_expert]
+        xe = xv[r2s[rows] // cfg.k].astype(np.float64)
+        w1 = vals(inp.W1[e], cfg.dtype)
+        w3 = vals(inp.W3[e], cfg.dtype)
+        h = orc.silu(xe @ w1.T) * (xe @ w3.T)
+        del w1, w3
+        yo = h @ vals(inp.W2[e], cfg.dtype).T
+        err = nerr(yg[rows], yo)
+        worst = max(worst, err)
+        assert err <= TOL["bf16"], (e, rows, err)
+    say(f"    worst normalised max error over sampled rows {worst:.3e}")
+    # the combined output of tokens whose experts are all resident, by the definition
+    res = set(wl.resident_experts(cfg))
+    tok = [t for t in range(cfg.T) if all(int(e) in res for e in idx[t])][:4]
+    if tok:
+        w = fwd["topk_w"].cpu().numpy()
+        W1 = [None if a is None else vals(a, cfg.dtype) if i in set(idx[tok].ravel()) else None
+              for i, a in enumerate(inp.W1)]
+        out_o = np.zeros((len(tok), cfg.d))
+        for n_, t in enumerate(tok):
+            for j in range(cfg.k):
+                e = int(idx[t, j])
+                xe = xv[t:t + 1].astype(np.float64)
+                h = orc.silu(xe @ vals(inp.W1[e], cfg.dtype).T) * (xe @ vals(inp.W3[e], cfg.dtype).T)
+                out_o[n_] += w[t, j] * (h @ vals(inp.W2[e], cfg.dtype).T)[0]
+        assert nerr(to_host_f32(fwd["out"])[tok], out_o) <= TOL["bf16"]
+    lay.close()
+
+
+@pytest.mark.parametrize("name", ["mixtral", "finegrained", "train"])
+def test_full_size_configs_sampled_rows(name):
+    from gpu_common import say
+    cfg = wl.CONFIGS[name]
+    say(f"[ffn] full size, sampled rows: config={name} T={cfg.T} d={cfg.d} E={cfg.E} f={cfg.f}")
+    _sampled_rows_check(cfg)
+
+
+@pytest.mark.parametrize("name,T", [("tiny", None), ("train", 512)])
+def test_backward_matches_oracle(name, T):
+    from gpu_common import DEV, TOL, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
+    cfg = wl.scaled(wl.CONFIGS[name], backward=True)
+    if T is not None:
+        cfg = wl.scaled(cfg, T=T)
+    say(f"[bwd] config={name} T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} f={cfg.f}")
+    inp = wl.make_inputs(cfg)
+    lay = layer_from_inputs(inp)
+    x = to_device(inp.x, cfg.dtype)
+    dout = to_device(inp.dOut, cfg.dtype)
+    fwd = lay.forward(x, save=True)
+    bwd = lay.backward(fwd, dout)
+    torch.cuda.synchronize()
+    tol = TOL[cfg.dtype]
+    idx = i32(fwd["topk_idx"])
+    w = fwd["topk_w"].cpu().numpy().astype(np.float64)
+    cnt, off, _, _, s2r, r2s = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
+    W1, W3, W2 = (_f64_list(a, cfg.dtype) for a in (inp.W1, inp.W3, inp.W2))
+    xp = vals(orc.pack_rows(inp.x, r2s, cfg.k), cfg.dtype)
+    yo, Go, Uo = orc.expert_ffn(xp, cnt, off, W1, W3, W2)
+    dy_o, dw_o = orc.combine_bwd(vals(inp.dOut, cfg.dtype), yo, s2r, w)
+    dxp_o, dW1_o, dW3_o, dW2_o = orc.expert_ffn_bwd(dy_o, xp, Go, Uo, cnt, off, W1, W3, W2)
+    dx_o = orc.dispatch_bwd(dxp_o, s2r, cfg.T, cfg.k)
+    errs = dict(dy=nerr(to_host_f32(bwd["dy_packed"]), dy_o),
+                dw=nerr(bwd["dtopk_w"].cpu().numpy(), dw_o),
+                dxp=nerr(to_host_f32(bwd["dx_packed"]), dxp_o),
+                dx=nerr(to_host_f32(bwd["dx"]), dx_o))
+    for e in range(cfg.E):
+        errs[f"dW1[{e}]"] = nerr(bwd["dW1"][e].cpu().numpy(), dW1_o[e])
+        errs[f"dW3[{e}]"] = nerr(bwd["dW3"][e].cpu().numpy(), dW3_o[e])
+        errs[f"dW2[{e}]"] = nerr(bwd["dW2"][e].cpu().numpy(), dW2_o[e])
+    say("    " + ", ".join(f"{k_}={v:.2e}" for k_, v in list(errs.items())[:7]))
+    bad = {k_: v for k_, v in errs.items() if not v <= tol}
+    assert not bad, bad
+    lay.close()
