@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the one-GPU MoE hot path.
+
+A step is one pass of the whole path over one batch of synthetic input:
+moe_route -> moe_dispatch -> moe_expert_ffn (resident experts only) -> moe_combine
+(the training configuration adds moe_combine_bwd -> moe_expert_ffn_bwd -> moe_dispatch_bwd).
+Inputs are resident in HBM before the timed region; rows of the packed output that belong
+to other ranks are pre-filled outside it.
+
+Prints ONE JSON line: tokens/s of the layer, per-call times, the roofline of the dominant
+kernel (the MFMA gate/up grouped GEMM, timed with HIP events on its own stream inside the
+timed steps), HBM-bandwidth fractions of dispatch and combine, and the CPU oracle timed on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3       # fp32 vector
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(cfg, inp, sample_tokens: int):
+    """The oracle as it stands on a bounded sample: the first `sample_tokens` tokens of the
+    same workload (same d, E, k, f, placement; resident experts only)."""
+    import moe_workloads as wl
+    from oracle import moe_oracle as orc
+    T = min(sample_tokens, cfg.T)
+    f32 = lambda a: None if a is None else wl.stored_to_f32(a, cfg.dtype)
+    x = f32(inp.x)[:T]
+    Wg = f32(inp.Wg)
+    W1 = [f32(w) for w in inp.W1]
+    W3 = [f32(w) for w in inp.W3]
+    W2 = [f32(w) for w in inp.W2]
+    t0 = time.perf_counter()
+    res = orc.layer_forward(x, Wg, inp.bias, cfg.k, inp.dest_rank, cfg.R, W1, W3, W2)
+    if cfg.backward:
+        dout = f32(inp.dOut)[:T]
+        dy, _ = orc.combine_bwd(dout, res["y_packed"], res["slot_to_row"], res["topk_w"])
+        dxp, _, _, _ = orc.expert_ffn_bwd(dy, res["x_packed"], res["G"], res["U"],
+                                          res["expert_counts"], res["expert_offsets"], W1, W3, W2)
+        orc.dispatch_bwd(dxp, res["slot_to_row"], T, cfg.k)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": T / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {T} of {cfg.T} tokens of '{cfg.name}', float64 NumPy oracle, "
+                      f"resident experts only, {dt:.2f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="mixtral",
+                    help="workload: tiny | small | mixtral | finegrained | train")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0,
+                    help="tokens of the oracle baseline sample (0 = sized for ~10-30 s)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import moe_workloads as wl
+    import paper_2510_19470_amd as moe
+    from paper_2510_19470_amd.layer import layer_from_inputs, to_device
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    cfg = wl.CONFIGS[args.config]
+    t_gen = time.perf_counter()
+    inp = wl.make_inputs(cfg, experts="resident")
+    t_gen = time.perf_counter() - t_gen
+    lay = layer_from_inputs(inp)
+    dev = lay.device
+    x = to_device(inp.x, cfg.dtype)
+    dout = to_device(inp.dOut, cfg.dtype) if cfg.backward else None
+    T, k, d, E, f, R = cfg.T, cfg.k, cfg.d, cfg.E, cfg.f, cfg.R
+    S = T * k
+    tdt = lay.ctx.torch_dtype
+    elem = 2 if cfg.dtype == "bf16" else 4
+
+    # caller-owned buffers, allocated once
+    i32 = dict(dtype=torch.int32, device=dev)
+    topk_idx = torch.empty((T, k), **i32)
+    topk_w = torch.empty((T, k), dtype=torch.float32, device=dev)
+    disp = moe.binding.DispatchOut()
+    disp.x_packed = torch.empty((S, d), dtype=tdt, device=dev)
+    disp.slot_to_row = torch.empty(S, **i32)
+    disp.row_to_slot = torch.empty(S, **i32)
+    disp.expert_counts = torch.empty(E, **i32)
+    disp.expert_offsets = torch.empty(E, **i32)
+    disp.rank_counts = torch.empty(R, **i32)
+    disp.rank_offsets = torch.empty(R + 1, **i32)
+    y_packed = torch.zeros((S, d), dtype=tdt, device=dev)      # remote rows: "received" zeros
+    out = torch.empty((T, d), dtype=tdt, device=dev)
+    G = U = dy = dw = dxp = dx = None
+    dW1 = dW3 = dW2 = None
+    if cfg.backward:
+        G = torch.zeros((S, f), dtype=tdt, device=dev)
+        U = torch.zeros((S, f), dtype=tdt, device=dev)
+        dy = torch.empty((S, d), dtype=tdt, device=dev)
+        dw = torch.empty((T, k), dtype=torch.float32, device=dev)
+        dxp = torch.zeros((S, d), dtype=tdt, device=dev)
+        dx = torch.empty((T, d), dtype=tdt, device=dev)
+        mk = lambda ws: [None if w is None else torch.empty(w.shape, dtype=torch.float32, device=dev)
+                         for w in ws]
+        dW1, dW3, dW2 = mk(lay.W1), mk(lay.W3), mk(lay.W2)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    names = ["route", "dispatch", "expert_ffn", "combine"] + \
+        (["combine_bwd", "expert_ffn_bwd", "dispatch_bwd"] if cfg.backward else [])
+
+    def step(marks=None):
+        def mark(i):
+            if marks is not None:
+                marks[i].record()
+        mark(0)
+        moe.moe_route(lay.ctx, x, lay.Wg, lay.bias, topk_idx=topk_idx, topk_w=topk_w)
+        mark(1)
+        moe.moe_dispatch(lay.ctx, x, topk_idx, out=disp)
+        mark(2)
+        moe.moe_expert_ffn(lay.ctx, disp.x_packed, disp.expert_counts, disp.expert_offsets,
+                           lay.W1, lay.W3, lay.W2, y_packed=y_packed, G_save=G, U_save=U)
+        mark(3)
+        moe.moe_combine(lay.ctx, y_packed, disp.slot_to_row, topk_w, out=out)
+        mark(4)
+        if cfg.backward:
+            moe.moe_combine_bwd(lay.ctx, dout, y_packed, disp.slot_to_row, topk_w, dy_packed=dy,
+                                dtopk_w=dw)
+            mark(5)
+            moe.moe_expert_ffn_bwd(lay.ctx, dy, disp.x_packed, G, U, disp.expert_counts,
+                                   disp.expert_offsets, lay.W1, lay.W3, lay.W2, dx_packed=dxp,
+                                   dW1=dW1, dW3=dW3, dW2=dW2)
+            mark(6)
+            moe.moe_dispatch_bwd(lay.ctx, dxp, disp.slot_to_row, dx=dx)
+            mark(7)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps, events on the launch stream ------------
+    marks = [[ev() for _ in range(len(names) + 1)] for _ in range(args.steps)]
+    moe.moe_profile_ffn(lay.ctx, args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(marks[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ffn_ms, n_rec = moe.moe_profile_ffn_read(lay.ctx)
+    moe.moe_profile_ffn(lay.ctx, 0)
+
+    ms_per_step = wall * 1e3 / args.steps
+    call_ms = {n: float(np.mean([marks[s][i].elapsed_time(marks[s][i + 1])
+                                 for s in range(args.steps)])) for i, n in enumerate(names)}
+    n_loc = int(disp.rank_counts[cfg.local_rank].item())
+    n_res = len(wl.resident_experts(cfg))
+
+    # ---- algorithmic work ------------------------------------------------------------
+    flops_up = 4.0 * n_loc * d * f            # gate and up projections of the compute region
+    flops_down = 2.0 * n_loc * d * f
+    bytes_dispatch = T * d * elem + S * d * elem + S * 4 + 2 * S * 4
+    bytes_combine = S * d * elem + T * d * elem + S * 8
+    mfma = cfg.dtype == "bf16"
+    peak = PEAK_BF16_TFLOPS if mfma else PEAK_F32_TFLOPS
+    ach_up = flops_up / (ffn_ms[1] * 1e-3) / 1e12 if ffn_ms[1] > 0 else 0.0
+    ach_down = flops_down / (ffn_ms[2] * 1e-3) / 1e12 if ffn_ms[2] > 0 else 0.0
+    ach_ffn = (flops_up + flops_down) / (call_ms["expert_ffn"] * 1e-3) / 1e12
+    gbs = lambda b, ms: b / (ms * 1e-3) / 1e9
+
+    rec = {
+        "metric": "MoE-layer tokens/s (1 GPU); grouped-GEMM % MFMA peak; dispatch % HBM BW",
+        "value": T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={T} d_model={d} E={E} top-{k} ffn_dim={f} "
+                               f"R={R} resident={n_res} experts, seed {cfg.seed}",
+                   "T": T, "d_model": d, "E": E, "k": k, "ffn_dim": f, "R": R,
+                   "resident_experts": n_res, "n_loc_rows": n_loc,
+                   "steps_in_path": names},
+        "roofline": {
+            "kernel": "ffn_mfma_kernel<true> (gate/up grouped GEMM + SwiGLU)" if mfma
+                      else "ffn_gate_up_kernel<float>",
+            "bound": "mfma" if mfma else "alu",
+            "achieved": ach_up, "peak": peak, "unit": "TFLOP/s", "frac": ach_up / peak,
+            "traffic": None,
+            "avg_launch_ms": ffn_ms[1], "flops_per_launch": flops_up, "launches": n_rec,
+        },
+        "grouped_gemm": {
+            "gate_up_tflops": ach_up, "down_tflops": ach_down, "down_ms": ffn_ms[2],
+            "schedule_ms": ffn_ms[0], "whole_call_tflops": ach_ffn,
+            "frac_of_peak_gate_up": ach_up / peak, "frac_of_peak_down": ach_down / peak,
+            "frac_of_peak_whole_call": ach_ffn / peak,
+        },
+        "hbm": {
+            "dispatch_gbs": gbs(bytes_dispatch, call_ms["dispatch"]),
+            "dispatch_frac": gbs(bytes_dispatch, call_ms["dispatch"]) / PEAK_HBM_GBS,
+            "combine_gbs": gbs(bytes_combine, call_ms["combine"]),
+            "combine_frac": gbs(bytes_combine, call_ms["combine"]) / PEAK_HBM_GBS,
+            "bytes_dispatch": bytes_dispatch, "bytes_combine": bytes_combine, "peak_gbs": PEAK_HBM_GBS,
+        },
+        "call_ms": call_ms,
+        "input_generation_s": t_gen,
+    }
+    if not args.no_cpu_baseline:
+        flops_tok = 6.0 * d * f * k * (3 if cfg.backward else 1) + 2.0 * d * E
+        sample = args.cpu_sample_tokens or int(max(16, min(cfg.T, 4e12 / flops_tok / 4)))
+        rec["cpu_baseline"] = cpu_baseline(cfg, inp, sample)
+    print(json.dumps(rec))
+    lay.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -175,6 +175,17 @@ int moe_expert_ffn_bwd(moe_ctx* ctx, const void* dy_packed, const void* x_packed
 int moe_dispatch_bwd(moe_ctx* ctx, const void* dx_packed, const int32_t* slot_to_row, int32_t T,
                      void* dx, void* stream);
 
+/* Measurement aid.  moe_profile_ffn(ctx, n_calls) makes the next n_calls calls of
+ * moe_expert_ffn record HIP events on their stream around each internal launch
+ * (n_calls = 0 switches it off and frees the events; creates events, so not for use
+ * under graph capture).  moe_profile_ffn_read synchronises with those events and returns
+ * the average duration in milliseconds of each launch over the recorded calls:
+ * ms[0] tile schedule, ms[1] gate/up GEMM (+SwiGLU), ms[2] down GEMM; *n_recorded = calls
+ * averaged.  ms [host][MOE_PROF_SLOTS]. */
+#define MOE_PROF_SLOTS 3
+int moe_profile_ffn(moe_ctx* ctx, int32_t n_calls);
+int moe_profile_ffn_read(moe_ctx* ctx, float* ms, int32_t* n_recorded);
+
 #ifdef __cplusplus
 }
 #endif

@@ -6,5 +6,6 @@ from .binding import (  # noqa: F401
     MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_VALU, MoEConfigC, MoEError, MoEContext,
     library_path, load_library, moe_combine, moe_combine_bwd, moe_create, moe_destroy,
     moe_dispatch, moe_dispatch_bwd, moe_expert_ffn, moe_expert_ffn_bwd, moe_route,
-    moe_route_logits, moe_set_ffn_path, moe_set_placement, moe_strerror,
+    moe_route_logits, moe_set_ffn_path, moe_set_placement, moe_strerror, moe_profile_ffn,
+    moe_profile_ffn_read,
 )

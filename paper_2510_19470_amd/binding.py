@@ -63,9 +63,12 @@ def load_library(build_if_missing: bool = True):
     lib.moe_combine_bwd.argtypes = [P, P, P, P, P, c_int32, P, P, P]
     lib.moe_expert_ffn_bwd.argtypes = [P, P, P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P]
     lib.moe_dispatch_bwd.argtypes = [P, P, P, c_int32, P, P]
+    lib.moe_profile_ffn.argtypes = [P, c_int32]
+    lib.moe_profile_ffn_read.argtypes = [P, POINTER(c_float), POINTER(c_int32)]
     for name in ("moe_create", "moe_destroy", "moe_set_placement", "moe_set_ffn_path", "moe_route",
                  "moe_route_logits", "moe_dispatch", "moe_expert_ffn", "moe_combine",
-                 "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd"):
+                 "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd", "moe_profile_ffn",
+                 "moe_profile_ffn_read"):
         getattr(lib, name).restype = c_int
     _lib = lib
     return lib
@@ -263,3 +266,19 @@ def moe_dispatch_bwd(ctx, dx_packed, slot_to_row, dx=None):
     _check(load_library().moe_dispatch_bwd(ctx.handle, _ptr(dx_packed), _ptr(slot_to_row), T,
                                            _ptr(dx), _stream()), "moe_dispatch_bwd")
     return dx
+
+
+MOE_PROF_SLOTS = 3
+
+
+def moe_profile_ffn(ctx, n_calls: int) -> None:
+    _check(load_library().moe_profile_ffn(ctx.handle, n_calls), "moe_profile_ffn")
+
+
+def moe_profile_ffn_read(ctx):
+    """Returns ([ms_schedule, ms_gate_up, ms_down] averaged, n_calls_recorded); synchronises."""
+    ms = (c_float * MOE_PROF_SLOTS)()
+    n = c_int32(0)
+    _check(load_library().moe_profile_ffn_read(ctx.handle, ms, ctypes.byref(n)),
+           "moe_profile_ffn_read")
+    return [float(v) for v in ms], int(n.value)

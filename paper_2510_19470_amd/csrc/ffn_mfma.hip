@@ -279,16 +279,20 @@ int launch_ffn_mfma(moe_ctx* c, const int32_t* counts, const int32_t* offsets, c
   const void* const* W3 = c->d_wtab + 1 * MOE_MAX_EXPERTS;
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
   const int max_mt = c->max_mtiles[1];
+  prof_mark(c, 0, s);
   hipLaunchKernelGGL(mfma_sched_kernel, dim3(32), dim3(256), 0, s, counts, offsets, W1, E,
                      c->S_max, max_mt, nt_up, nt_down, c->d_sched[1], c->d_mtiles[1], c->d_order_up, c->d_order_down);
   const int grid_up = ((max_mt * nt_up + 7) / 8) * 8;
   const int grid_down = ((max_mt * nt_down + 7) / 8) * 8;
+  prof_mark(c, 1, s);
   hipLaunchKernelGGL((ffn_mfma_kernel<true>), dim3(grid_up), dim3(NT), 0, s,
                      (const uint16_t*)x_packed, c->d_sched[1], c->d_mtiles[1], c->d_order_up, nt_up,
                      W1, W3, d, f, (uint16_t*)c->d_H, (uint16_t*)G, (uint16_t*)U);
+  prof_mark(c, 2, s);
   hipLaunchKernelGGL((ffn_mfma_kernel<false>), dim3(grid_down), dim3(NT), 0, s,
                      (const uint16_t*)c->d_H, c->d_sched[1], c->d_mtiles[1], c->d_order_down,
                      nt_down, W2, (const void* const*)nullptr, f, d, (uint16_t*)y_packed,
                      (uint16_t*)nullptr, (uint16_t*)nullptr);
+  prof_mark(c, 3, s);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }

@@ -296,8 +296,10 @@ int ffn_generic_t(moe_ctx* c, const void* xp, void* y, void* G, void* U, void* H
   hipLaunchKernelGGL((ffn_gate_up_kernel<T>), dim3((f + BN - 1) / BN, mtiles), dim3(256), 0, s,
                      (const T*)xp, c->d_sched[0], c->d_mtiles[0], W1, W3, d, f, (T*)H, (T*)G,
                      (T*)U);
+  prof_mark(c, 2, s);
   hipLaunchKernelGGL((ffn_down_kernel<T>), dim3((d + BN - 1) / BN, mtiles), dim3(256), 0, s,
                      (const T*)H, c->d_sched[0], c->d_mtiles[0], W2, d, f, (T*)y);
+  prof_mark(c, 3, s);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 

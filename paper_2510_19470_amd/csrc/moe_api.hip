@@ -156,9 +156,55 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
   return MOE_OK;
 }
 
+int moe_profile_ffn(moe_ctx* c, int32_t n_calls) {
+  if (c == nullptr || n_calls < 0 || n_calls > 4096) return MOE_EINVAL;
+  if (c->prof_ev != nullptr) {
+    (void)hipDeviceSynchronize();
+    for (size_t i = 0; i < (size_t)c->prof_calls * (MOE_PROF_SLOTS + 1); ++i)
+      (void)hipEventDestroy(c->prof_ev[i]);
+    delete[] c->prof_ev;
+    c->prof_ev = nullptr;
+  }
+  c->prof_calls = 0;
+  c->prof_n = 0;
+  if (n_calls == 0) return MOE_OK;
+  const size_t n = (size_t)n_calls * (MOE_PROF_SLOTS + 1);
+  c->prof_ev = new (std::nothrow) hipEvent_t[n];
+  if (c->prof_ev == nullptr) return MOE_ENOMEM;
+  for (size_t i = 0; i < n; ++i)
+    if (hipEventCreate(&c->prof_ev[i]) != hipSuccess) {
+      for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(c->prof_ev[j]);
+      delete[] c->prof_ev;
+      c->prof_ev = nullptr;
+      return MOE_EHIP;
+    }
+  c->prof_calls = n_calls;
+  return MOE_OK;
+}
+
+int moe_profile_ffn_read(moe_ctx* c, float* ms, int32_t* n_recorded) {
+  if (c == nullptr || ms == nullptr || n_recorded == nullptr) return MOE_EINVAL;
+  for (int i = 0; i < MOE_PROF_SLOTS; ++i) ms[i] = 0.f;
+  *n_recorded = c->prof_n;
+  if (c->prof_n == 0) return MOE_OK;
+  for (int call = 0; call < c->prof_n; ++call) {
+    hipEvent_t* ev = c->prof_ev + (size_t)call * (MOE_PROF_SLOTS + 1);
+    if (hipEventSynchronize(ev[MOE_PROF_SLOTS]) != hipSuccess) return MOE_EHIP;
+    for (int i = 0; i < MOE_PROF_SLOTS; ++i) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, ev[i], ev[i + 1]) != hipSuccess) return MOE_EHIP;
+      ms[i] += t;
+    }
+  }
+  for (int i = 0; i < MOE_PROF_SLOTS; ++i) ms[i] /= (float)c->prof_n;
+  c->prof_n = 0;
+  return MOE_OK;
+}
+
 int moe_destroy(moe_ctx* c) {
   if (c == nullptr) return MOE_OK;
   (void)hipDeviceSynchronize();
+  (void)moe_profile_ffn(c, 0);
   free_all(c);
   delete c;
   return MOE_OK;
@@ -250,11 +296,17 @@ int moe_expert_ffn(moe_ctx* c, const void* x_packed, const int32_t* expert_count
   const void* const* tabs[6] = {W1, W3, W2, nullptr, nullptr, nullptr};
   st = sync_tables(c, tabs, s);
   if (st != MOE_OK) return st;
-  if (c->ffn_path == MOE_FFN_AUTO && ffn_mfma_supported(c))
-    return launch_ffn_mfma(c, expert_counts, expert_offsets, x_packed, y_packed, G_save, U_save, s);
-  st = launch_build_sched(c, expert_counts, expert_offsets, 0, s);
-  if (st != MOE_OK) return st;
-  return launch_ffn_generic(c, x_packed, y_packed, G_save, U_save, c->d_H, s);
+  if (c->ffn_path == MOE_FFN_AUTO && ffn_mfma_supported(c)) {
+    st = launch_ffn_mfma(c, expert_counts, expert_offsets, x_packed, y_packed, G_save, U_save, s);
+  } else {
+    prof_mark(c, 0, s);
+    st = launch_build_sched(c, expert_counts, expert_offsets, 0, s);
+    if (st != MOE_OK) return st;
+    prof_mark(c, 1, s);
+    st = launch_ffn_generic(c, x_packed, y_packed, G_save, U_save, c->d_H, s);
+  }
+  if (c->prof_calls > 0 && c->prof_n < c->prof_calls) c->prof_n++;
+  return st;
 }
 
 int moe_combine(moe_ctx* c, const void* y_packed, const int32_t* slot_to_row, const float* topk_w,

@@ -51,7 +51,17 @@ struct moe_ctx {
   void* d_H;              // [T_max*k][f]
   void* d_dG;             // [T_max*k][f]
   void* d_dU;             // [T_max*k][f]
+  // optional HIP-event timing of the internal launches of moe_expert_ffn
+  int prof_calls;         // capacity in calls (0 = off)
+  int prof_n;             // calls recorded so far
+  hipEvent_t* prof_ev;    // [prof_calls][MOE_PROF_SLOTS + 1]
 };
+
+// Records event `slot` of the current profiled call (no-op when profiling is off).
+inline void prof_mark(moe_ctx* c, int slot, hipStream_t s) {
+  if (c->prof_calls > 0 && c->prof_n < c->prof_calls)
+    (void)hipEventRecord(c->prof_ev[(size_t)c->prof_n * (MOE_PROF_SLOTS + 1) + slot], s);
+}
 
 #define DISPATCH_CHUNK 1024      // slots per histogram / ranking block
 #define GENERIC_BM 64
