@@ -106,13 +106,64 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
   }
 }
 
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// One k-step of the wavefront tile: 4 k-slices of 16, each 6 fragment reads + 8 MFMAs.
+__device__ __forceinline__ void mma_stage(f32x16 (&acc)[2][4], const uint4* __restrict__ As,
+                                          const uint4* __restrict__ Bs, const int (&fr_a)[4],
+                                          const int (&fr_b)[2], int fr_half, int fr_swz) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const int ch = (kk * 2 + fr_half) ^ fr_swz;
+    bf16x8 xa[4], wb[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xa[i] = __builtin_bit_cast(bf16x8, As[fr_a[i] + ch]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) wb[j] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ch]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[j], xa[i], acc[j][i], 0, 0, 0);
+  }
+}
+
+// Asynchronous global -> LDS copy of one k-step (no registers in between): each wavefront
+// fills 4 blocks of 8 rows x 128 B per operand; a lane's 16 bytes land at lane*16 inside
+// the block, so the swizzle is applied by choosing which global chunk the lane fetches.
+__device__ __forceinline__ void issue_stage(const uint4* const (&a_src)[4],
+                                            const uint4* const (&b_src)[4], int kofs,
+                                            uint4* As, uint4* Bs, int wave) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + kofs), (lptr_t)(As + (wave * 4 + i) * 64),
+                                     16, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr_t)(b_src[i] + kofs), (lptr_t)(Bs + (wave * 4 + i) * 64),
+                                     16, 0, 0);
+  }
+  // keep the copies at the top of the step: the scheduler would otherwise sink them
+  // below the MFMAs and expose their whole latency at the barrier
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+__device__ __forceinline__ void wait_stage_and_sync() {
+  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): my copies landed, my reads are done
+  __syncthreads();
+}
+
 template <bool GATED>
 __global__ __launch_bounds__(NT) void ffn_mfma_kernel(
     const uint16_t* __restrict__ A, const TileSched* __restrict__ sched,
     const MTile* __restrict__ mt, const uint32_t* __restrict__ order, int n_tiles_n,
     const void* const* __restrict__ Bt0, const void* const* __restrict__ Bt1, int K, int N,
     uint16_t* __restrict__ C, uint16_t* __restrict__ Gs, uint16_t* __restrict__ Us) {
-  __shared__ uint4 lds[4 * STAGE_VEC];  // [stage][A|B][2048]
+  // two stages, each 256 token rows + 256 weight rows of 64 bf16 (separate arrays so that
+  // reads of one stage are known not to alias the copy in flight into the other)
+  __shared__ uint4 ldsA0[STAGE_VEC];
+  __shared__ uint4 ldsB0[STAGE_VEC];
+  __shared__ uint4 ldsA1[STAGE_VEC];
+  __shared__ uint4 ldsB1[STAGE_VEC];
 
   const int total = sched->n_mtiles * n_tiles_n;
   const int per_xcd = (total + 7) >> 3;
@@ -126,25 +177,25 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
 
-  // ---- global -> LDS assignment: 4 token chunks and 4 weight chunks (16 B) per thread
-  const int ld_row = tid >> 3, ld_ch = tid & 7;
+  // ---- global -> LDS assignment: lane (lane>>3, lane&7) of block b = wave*4+i fills LDS
+  // row 8b + (lane>>3), chunk slot (lane&7), which must hold global chunk slot ^ swz(row)
   const uint4* a_src[4];
   const uint4* b_src[4];
   const uint16_t* B0 = (const uint16_t*)Bt0[tl.expert];
   const uint16_t* B1 = GATED ? (const uint16_t*)Bt1[tl.expert] : nullptr;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int row = ld_row + i * 64;
+    const int row = (wave * 4 + i) * 8 + (lane >> 3);
+    const int ch = (lane & 7) ^ swz(row);
     const int arow = min(row, tl.rows - 1);
-    a_src[i] = (const uint4*)(A + (size_t)(tl.row0 + arow) * K) + ld_ch;
+    a_src[i] = (const uint4*)(A + (size_t)(tl.row0 + arow) * K) + ch;
     const uint16_t* bp;
     if (GATED)
       bp = (row < 128 ? B0 : B1) + (size_t)(nblk * 128 + (row & 127)) * K;
     else
       bp = B0 + (size_t)(nblk * 256 + row) * K;
-    b_src[i] = (const uint4*)bp + ld_ch;
+    b_src[i] = (const uint4*)bp + ch;
   }
-  const int st_off = ld_row * 8 + (ld_ch ^ swz(ld_row));  // + i*512 per chunk
 
   // ---- fragment read offsets (uint4 units inside one operand stage)
   const int fr_row = lane & 31, fr_half = lane >> 5;
@@ -163,55 +214,21 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
-  uint4 pa[4], pb[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    pa[i] = a_src[i][0];
-    pb[i] = b_src[i][0];
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    lds[st_off + i * 512] = pa[i];
-    lds[STAGE_VEC + st_off + i * 512] = pb[i];
-  }
-  __syncthreads();
-
+  // K is a multiple of 128, so the number of k-steps is even and the loop can alternate
+  // the two stages without a conditional exit (keeps the accumulators in registers).
   const int KT = K / BK;
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = (kt & 1) * 2 * STAGE_VEC;
-    const int nxt = ((kt + 1) & 1) * 2 * STAGE_VEC;
-    const bool more = kt + 1 < KT;
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        pa[i] = a_src[i][(kt + 1) * 8];
-        pb[i] = b_src[i][(kt + 1) * 8];
-      }
-    }
-    const uint4* As = lds + cur;
-    const uint4* Bs = lds + cur + STAGE_VEC;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int ch = (kk * 2 + fr_half) ^ fr_swz;
-      bf16x8 xa[4], wb[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) xa[i] = __builtin_bit_cast(bf16x8, As[fr_a[i] + ch]);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) wb[j] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ch]);
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[j], xa[i], acc[j][i], 0, 0, 0);
-    }
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        lds[nxt + st_off + i * 512] = pa[i];
-        lds[nxt + STAGE_VEC + st_off + i * 512] = pb[i];
-      }
-    }
-    __syncthreads();
+  issue_stage(a_src, b_src, 0, ldsA0, ldsB0, wave);
+  wait_stage_and_sync();
+  for (int kt = 0; kt < KT; kt += 2) {
+    issue_stage(a_src, b_src, (kt + 1) * 8, ldsA1, ldsB1, wave);
+    mma_stage(acc, ldsA0, ldsB0, fr_a, fr_b, fr_half, fr_swz);
+    wait_stage_and_sync();
+    // the copy after the last step re-reads that step into the idle stage: in bounds,
+    // unconditional, and nobody reads it
+    const int kn = kt + 2 < KT ? kt + 2 : kt;
+    issue_stage(a_src, b_src, kn * 8, ldsA0, ldsB0, wave);
+    mma_stage(acc, ldsA1, ldsB1, fr_a, fr_b, fr_half, fr_swz);
+    wait_stage_and_sync();
   }
 
   // ---- epilogue: lane holds, per 32x32 accumulator, token row (lane&31) and the weight
@@ -262,7 +279,8 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(
 
 bool ffn_mfma_supported(const moe_ctx* c) {
   const int d = c->cfg.d, f = c->cfg.f;
-  return c->cfg.dtype == MOE_BF16 && d % 256 == 0 && f % 128 == 0 && f / 128 < 4096 &&
+  return c->cfg.dtype == MOE_BF16 && d % 256 == 0 && f % 128 == 0 &&  // K % 128 == 0 too
+         f / 128 < 4096 &&
          d / 256 < 4096;
 }
 
