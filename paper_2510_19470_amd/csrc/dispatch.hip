@@ -3,15 +3,16 @@
 // activated experts; Sec. 3.2: one contiguous chunk per peer, and the chunk of an expert
 // that was fetched by all-gather stays local).
 //
-// Three launches, no host synchronisation:
-//   1. dispatch_hist_scan: per-chunk expert histograms in LDS; the last block to arrive
-//      (atomic ticket, no spinning) turns them into exclusive prefixes over chunks and
-//      writes counts / offsets / rank chunks.
-//   2. dispatch_rank: every chunk recomputes the stable rank of its slots (ballot + popcount
-//      per expert value inside a wavefront, LDS prefix over wavefronts) and writes both maps.
-//   3. dispatch_copy: one wavefront per token reads the row once (16 B per lane) and writes
-//      it to its k packed rows.
-// The permutation is deterministic: no atomics decide a row number.
+// Two launches, no host synchronisation:
+//   1. dispatch_count: every chunk of 1024 slots ranks its slots per expert (ballot +
+//      popcount per expert value inside a wavefront, LDS prefix over wavefronts), stores
+//      the in-chunk rank of each slot and the chunk's expert histogram; the last block to
+//      arrive (atomic ticket, no spinning) turns the histograms into exclusive prefixes
+//      over chunks and writes counts / offsets / rank chunks.
+//   2. dispatch_scatter: one wavefront per token turns the in-chunk ranks of its k slots
+//      into final rows (expert offset + chunk prefix + rank), writes both maps, reads the
+//      token row once (16 B per lane) and writes it to its k packed rows.
+// The permutation is deterministic: no atomic decides a row number.
 #include "moe_internal.h"
 
 namespace {
@@ -20,30 +21,73 @@ __device__ __forceinline__ int32_t load_agent(const int32_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__global__ __launch_bounds__(256) void dispatch_hist_scan_kernel(
+__global__ __launch_bounds__(256) void dispatch_count_kernel(
     const int32_t* __restrict__ topk_idx, int S, int E, int R, int n_chunks,
     const int32_t* __restrict__ dest_rank, const int32_t* __restrict__ seg_order,
     int32_t* __restrict__ chunk_hist, int32_t* __restrict__ ticket,
-    int32_t* __restrict__ expert_counts, int32_t* __restrict__ expert_offsets,
-    int32_t* __restrict__ rank_counts, int32_t* __restrict__ rank_offsets) {
-  __shared__ int32_t hist[MOE_MAX_EXPERTS];
+    int32_t* __restrict__ slot_rank, int32_t* __restrict__ expert_counts,
+    int32_t* __restrict__ expert_offsets, int32_t* __restrict__ rank_counts,
+    int32_t* __restrict__ rank_offsets) {
+  __shared__ int32_t wcnt[4][MOE_MAX_EXPERTS];
+  __shared__ int32_t tot[MOE_MAX_EXPERTS];
+  __shared__ int32_t s_order[MOE_MAX_EXPERTS];
+  __shared__ int32_t s_dest[MOE_MAX_EXPERTS];
   __shared__ int32_t rcnt[MOE_MAX_RANKS];
   __shared__ int is_last;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.x;
-  for (int e = tid; e < E; e += 256) hist[e] = 0;
+  for (int i = tid; i < 4 * MOE_MAX_EXPERTS; i += 256) (&wcnt[0][0])[i] = 0;
+  for (int e = tid; e < E; e += 256) {  // placement, needed only by the last block
+    s_order[e] = seg_order[e];
+    s_dest[e] = dest_rank[e];
+  }
   __syncthreads();
-  const int base = b * DISPATCH_CHUNK;
+  constexpr int ROUNDS = DISPATCH_CHUNK / 256;
+  int my_e[ROUNDS], my_rank[ROUNDS];
+  const int wbase = b * DISPATCH_CHUNK + wave * (DISPATCH_CHUNK / 4);
 #pragma unroll
-  for (int i = 0; i < DISPATCH_CHUNK / 256; ++i) {
-    const int s = base + i * 256 + tid;
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int s = wbase + r * 64 + lane;
+    int e = -1;
     if (s < S) {
-      const int e = topk_idx[s];
-      if ((unsigned)e < (unsigned)E) atomicAdd(&hist[e], 1);
+      e = topk_idx[s];
+      if ((unsigned)e >= (unsigned)E) e = -1;
+    }
+    my_e[r] = e;
+    my_rank[r] = 0;
+  }
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int e = my_e[r];
+    unsigned long long todo = __ballot(e >= 0);
+    while (todo) {
+      const int leader = __ffsll((long long)todo) - 1;
+      const int e0 = __shfl(e, leader, 64);
+      const unsigned long long m = __ballot(e == e0);
+      if (e == e0) {
+        const int before = wcnt[wave][e0];
+        my_rank[r] = before + __popcll(m & ((1ull << lane) - 1ull));
+        if (lane == leader) wcnt[wave][e0] = before + __popcll(m);
+      }
+      todo &= ~m;
     }
   }
   __syncthreads();
-  for (int e = tid; e < E; e += 256) chunk_hist[(size_t)b * E + e] = hist[e];
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int s = wbase + r * 64 + lane;
+    const int e = my_e[r];
+    if (s < S) {
+      int rank = -1;
+      if (e >= 0) {
+        rank = my_rank[r];
+        for (int w = 0; w < wave; ++w) rank += wcnt[w][e];
+      }
+      slot_rank[s] = rank;  // rank of the slot among its expert's slots of this chunk
+    }
+  }
+  for (int e = tid; e < E; e += 256)
+    chunk_hist[(size_t)b * E + e] = wcnt[0][e] + wcnt[1][e] + wcnt[2][e] + wcnt[3][e];
   __threadfence();
   __syncthreads();
   if (tid == 0) {
@@ -55,7 +99,6 @@ __global__ __launch_bounds__(256) void dispatch_hist_scan_kernel(
   __threadfence();
 
   // exclusive prefix over chunks, one wavefront per expert at a time
-  const int lane = tid & 63, wave = tid >> 6;
   for (int e = wave; e < E; e += 4) {
     int carry = 0;
     for (int c0 = 0; c0 < n_chunks; c0 += 64) {
@@ -70,18 +113,18 @@ __global__ __launch_bounds__(256) void dispatch_hist_scan_kernel(
       if (c < n_chunks) chunk_hist[(size_t)c * E + e] = carry + incl - v;
       carry += __shfl(incl, 63, 64);
     }
-    if (lane == 0) hist[e] = carry;  // total count of expert e
+    if (lane == 0) tot[e] = carry;  // total count of expert e
   }
   for (int r = tid; r < R; r += 256) rcnt[r] = 0;
   __syncthreads();
   if (tid == 0) {
     int run = 0;
     for (int i = 0; i < E; ++i) {
-      const int e = seg_order[i];
-      const int n = hist[e];
+      const int e = s_order[i];
+      const int n = tot[e];
       expert_offsets[e] = run;
       expert_counts[e] = n;
-      rcnt[dest_rank[e]] += n;
+      rcnt[s_dest[e]] += n;
       run += n;
     }
     int acc = 0;
@@ -108,89 +151,39 @@ __global__ void dispatch_empty_kernel(int E, int R, int32_t* expert_counts, int3
   }
 }
 
-__global__ __launch_bounds__(256) void dispatch_rank_kernel(
-    const int32_t* __restrict__ topk_idx, int S, int E, const int32_t* __restrict__ chunk_base,
-    const int32_t* __restrict__ expert_offsets, int32_t* __restrict__ slot_to_row,
-    int32_t* __restrict__ row_to_slot) {
-  __shared__ int32_t wcnt[4][MOE_MAX_EXPERTS];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int b = blockIdx.x;
-  for (int i = tid; i < 4 * MOE_MAX_EXPERTS; i += 256) (&wcnt[0][0])[i] = 0;
-  __syncthreads();
-  constexpr int ROUNDS = DISPATCH_CHUNK / 256;
-  int my_e[ROUNDS], my_rank[ROUNDS];
-  const int wbase = b * DISPATCH_CHUNK + wave * (DISPATCH_CHUNK / 4);
-#pragma unroll
-  for (int r = 0; r < ROUNDS; ++r) {
-    const int s = wbase + r * 64 + lane;
-    int e = -1;
-    if (s < S) {
-      e = topk_idx[s];
-      if ((unsigned)e >= (unsigned)E) e = -1;
-    }
-    my_e[r] = e;
-    my_rank[r] = 0;
-    unsigned long long todo = __ballot(e >= 0);
-    while (todo) {
-      const int leader = __ffsll((long long)todo) - 1;
-      const int e0 = __shfl(e, leader, 64);
-      const unsigned long long m = __ballot(e == e0);
-      if (e == e0) {
-        const int before = wcnt[wave][e0];
-        my_rank[r] = before + __popcll(m & ((1ull << lane) - 1ull));
-        if (lane == leader) wcnt[wave][e0] = before + __popcll(m);
-      }
-      todo &= ~m;
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int r = 0; r < ROUNDS; ++r) {
-    const int s = wbase + r * 64 + lane;
-    const int e = my_e[r];
-    if (s < S) {
-      int row = -1;
-      if (e >= 0) {
-        int before = 0;
-        for (int w = 0; w < wave; ++w) before += wcnt[w][e];
-        row = expert_offsets[e] + chunk_base[(size_t)b * E + e] + before + my_rank[r];
-        row_to_slot[row] = s;
-      }
-      slot_to_row[s] = row;
-    }
-  }
-}
-
-// One wavefront per token: read the row once, write it k times.
+// One wavefront per token: final rows of its k slots, both maps, and the row copy.
+// slot_to_row holds the in-chunk ranks on entry and the final rows on exit.
 template <int K_MAX>
-__global__ __launch_bounds__(256) void dispatch_copy_kernel(const uint4* __restrict__ x,
-                                                            const int32_t* __restrict__ slot_to_row,
-                                                            int T, int k, int S, int row_vec,
-                                                            uint4* __restrict__ x_packed) {
+__global__ __launch_bounds__(256) void dispatch_scatter_kernel(
+    const uint4* __restrict__ x, const int32_t* __restrict__ topk_idx,
+    const int32_t* __restrict__ chunk_base, const int32_t* __restrict__ expert_offsets, int T,
+    int k, int E, int row_vec, int32_t* __restrict__ slot_to_row,
+    int32_t* __restrict__ row_to_slot, uint4* __restrict__ x_packed) {
   const int lane = threadIdx.x & 63;
   const int t = (int)((blockIdx.x * (size_t)blockDim.x + threadIdx.x) >> 6);
   if (t >= T) return;
+  int row = -1;
+  if (lane < k) {
+    const int s = t * k + lane;
+    const int e = topk_idx[s];
+    const int rk = slot_to_row[s];
+    if ((unsigned)e < (unsigned)E && rk >= 0) {
+      row = expert_offsets[e] + chunk_base[(size_t)(s / DISPATCH_CHUNK) * E + e] + rk;
+      row_to_slot[row] = s;
+    }
+    slot_to_row[s] = row;
+  }
+  if (row_vec == 0) return;
   int rows[K_MAX];
 #pragma unroll
-  for (int j = 0; j < K_MAX; ++j) {
-    int r = j < k ? slot_to_row[(size_t)t * k + j] : -1;
-    rows[j] = ((unsigned)r < (unsigned)S) ? r : -1;
-  }
+  for (int j = 0; j < K_MAX; ++j) rows[j] = __shfl(row, j, 64);  // lanes >= k hold -1
   const uint4* src = x + (size_t)t * row_vec;
-  for (int c = lane; c < row_vec; c += 256) {
-    uint4 v[4];
+#pragma unroll 4
+  for (int c = lane; c < row_vec; c += 64) {
+    const uint4 v = src[c];
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (c + u * 64 < row_vec) v[u] = src[c + u * 64];
-#pragma unroll
-    for (int j = 0; j < K_MAX; ++j) {
-      if (rows[j] >= 0) {
-        uint4* dst = x_packed + (size_t)rows[j] * row_vec;
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (c + u * 64 < row_vec) dst[c + u * 64] = v[u];
-      }
-    }
+    for (int j = 0; j < K_MAX; ++j)
+      if (rows[j] >= 0) x_packed[(size_t)rows[j] * row_vec + c] = v;
   }
 }
 
@@ -209,27 +202,20 @@ int launch_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int T, v
   }
   const int n_chunks = (S + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK;
   if (n_chunks > c->n_chunks_max) return MOE_EINVAL;
-  hipLaunchKernelGGL(dispatch_hist_scan_kernel, dim3(n_chunks), dim3(256), 0, s, topk_idx, S, E, R,
+  hipLaunchKernelGGL(dispatch_count_kernel, dim3(n_chunks), dim3(256), 0, s, topk_idx, S, E, R,
                      n_chunks, c->d_dest_rank, c->d_seg_order, c->d_chunk_hist, c->d_ticket,
-                     expert_counts, expert_offsets, rank_counts, rank_offsets);
-  hipLaunchKernelGGL(dispatch_rank_kernel, dim3(n_chunks), dim3(256), 0, s, topk_idx, S, E,
-                     c->d_chunk_hist, expert_offsets, slot_to_row, row_to_slot);
-  if (x != nullptr) {
-    const int elem = c->cfg.dtype == MOE_BF16 ? 2 : 4;
-    const int row_vec = c->cfg.d * elem / 16;
-    const int grid = (T + 3) / 4;
-    if (k <= 2)
-      hipLaunchKernelGGL((dispatch_copy_kernel<2>), dim3(grid), dim3(256), 0, s, (const uint4*)x,
-                         slot_to_row, T, k, S, row_vec, (uint4*)x_packed);
-    else if (k <= 4)
-      hipLaunchKernelGGL((dispatch_copy_kernel<4>), dim3(grid), dim3(256), 0, s, (const uint4*)x,
-                         slot_to_row, T, k, S, row_vec, (uint4*)x_packed);
-    else if (k <= 8)
-      hipLaunchKernelGGL((dispatch_copy_kernel<8>), dim3(grid), dim3(256), 0, s, (const uint4*)x,
-                         slot_to_row, T, k, S, row_vec, (uint4*)x_packed);
-    else
-      hipLaunchKernelGGL((dispatch_copy_kernel<MOE_MAX_TOPK>), dim3(grid), dim3(256), 0, s,
-                         (const uint4*)x, slot_to_row, T, k, S, row_vec, (uint4*)x_packed);
-  }
+                     slot_to_row, expert_counts, expert_offsets, rank_counts, rank_offsets);
+  const int elem = c->cfg.dtype == MOE_BF16 ? 2 : 4;
+  const int row_vec = x != nullptr ? c->cfg.d * elem / 16 : 0;
+  const int grid = (T + 3) / 4;
+#define LAUNCH_SCATTER(KM)                                                                      \
+  hipLaunchKernelGGL((dispatch_scatter_kernel<KM>), dim3(grid), dim3(256), 0, s, (const uint4*)x, \
+                     topk_idx, c->d_chunk_hist, expert_offsets, T, k, E, row_vec, slot_to_row,  \
+                     row_to_slot, (uint4*)x_packed)
+  if (k <= 2) LAUNCH_SCATTER(2);
+  else if (k <= 4) LAUNCH_SCATTER(4);
+  else if (k <= 8) LAUNCH_SCATTER(8);
+  else LAUNCH_SCATTER(MOE_MAX_TOPK);
+#undef LAUNCH_SCATTER
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }

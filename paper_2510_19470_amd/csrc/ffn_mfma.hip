@@ -110,22 +110,41 @@ typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 // One k-step of the wavefront tile: 4 k-slices of 16, each 6 fragment reads + 8 MFMAs.
+// The reads of slice kk+1 are issued before the MFMAs of slice kk (two fragment sets in
+// registers), and the wavefront raises its priority while it feeds the matrix core so
+// that the other wavefront of the SIMD does its LDS reads in the shadow.
 __device__ __forceinline__ void mma_stage(f32x16 (&acc)[2][4], const uint4* __restrict__ As,
                                           const uint4* __restrict__ Bs, const int (&fr_a)[4],
                                           const int (&fr_b)[2], int fr_half, int fr_swz) {
+  bf16x8 xa[2][4], wb[2][2];
+  {
+    const int ch = fr_half ^ fr_swz;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xa[0][i] = __builtin_bit_cast(bf16x8, As[fr_a[i] + ch]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) wb[0][j] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ch]);
+  }
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
-    const int ch = (kk * 2 + fr_half) ^ fr_swz;
-    bf16x8 xa[4], wb[2];
+    if (kk < 3) {
+      const int ch = ((kk + 1) * 2 + fr_half) ^ fr_swz;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) xa[i] = __builtin_bit_cast(bf16x8, As[fr_a[i] + ch]);
+      for (int i = 0; i < 4; ++i)
+        xa[(kk + 1) & 1][i] = __builtin_bit_cast(bf16x8, As[fr_a[i] + ch]);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) wb[j] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ch]);
+      for (int j = 0; j < 2; ++j)
+        wb[(kk + 1) & 1][j] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ch]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[j], xa[i], acc[j][i], 0, 0, 0);
+        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[kk & 1][j], xa[kk & 1][i],
+                                                            acc[j][i], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 

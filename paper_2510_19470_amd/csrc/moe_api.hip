@@ -252,6 +252,9 @@ int moe_route(moe_ctx* c, const void* x, const void* Wg, const float* bias, int3
   if (!aligned16(x) || !aligned16(Wg) || !aligned16(bias) || !aligned16(logits) ||
       !aligned16(topk_idx) || !aligned16(topk_w))
     return MOE_EINVAL;
+  if (gate_route_fused_supported(c))  // one launch, logits only written when asked for
+    return launch_gate_route_fused(c, x, Wg, bias, T, logits, topk_idx, topk_w,
+                                   (hipStream_t)stream);
   float* L = logits != nullptr ? logits : c->d_logits;
   st = launch_gate_logits(c, x, Wg, bias, T, L, (hipStream_t)stream);
   if (st != MOE_OK) return st;

@@ -70,6 +70,9 @@ inline void prof_mark(moe_ctx* c, int slot, hipStream_t s) {
 // ---- launchers (defined in the .hip files); all return a moe_status ----
 int launch_route_select(const moe_ctx* c, const float* logits, int T, int32_t* idx, float* w,
                         hipStream_t s);
+bool gate_route_fused_supported(const moe_ctx* c);
+int launch_gate_route_fused(const moe_ctx* c, const void* x, const void* Wg, const float* bias,
+                            int T, float* logits, int32_t* idx, float* w, hipStream_t s);
 int launch_gate_logits(const moe_ctx* c, const void* x, const void* Wg, const float* bias, int T,
                        float* logits, hipStream_t s);
 int launch_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int T, void* x_packed,
