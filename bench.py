@@ -29,6 +29,10 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3       # fp32 vector
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes per launch of the dominant kernel (read + written), from the two rocprofv3
+# --pmc passes (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0, factors from the plain 512 MiB copy of
+# --copy-calibration) summarised in profiles/hotpath_mixtral_kernel_trace_and_traffic.md.
+MEASURED_TRAFFIC_BYTES = {"mixtral": 6132.5e6 + 469.8e6}
 
 
 def cpu_baseline(cfg, inp, sample_tokens: int):
@@ -72,6 +76,9 @@ def main() -> int:
     ap.add_argument("--cpu-sample-tokens", type=int, default=0,
                     help="tokens of the oracle baseline sample (0 = sized for ~10-30 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 512 MiB device copy (a kernel of known traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -171,6 +178,15 @@ def main() -> int:
     ffn_ms, n_rec = moe.moe_profile_ffn_read(lay.ctx)
     moe.moe_profile_ffn(lay.ctx, 0)
 
+    if args.copy_calibration:
+        src = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 512 MiB, writes 512 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     ms_per_step = wall * 1e3 / args.steps
     call_ms = {n: float(np.mean([marks[s][i].elapsed_time(marks[s][i + 1])
                                  for s in range(args.steps)])) for i, n in enumerate(names)}
@@ -207,7 +223,8 @@ def main() -> int:
                       else "ffn_gate_up_kernel<float>",
             "bound": "mfma" if mfma else "alu",
             "achieved": ach_up, "peak": peak, "unit": "TFLOP/s", "frac": ach_up / peak,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if mfma else None,
+            "algorithmic_bytes": (2 * n_res * d * f + n_loc * d + n_loc * f) * elem,
             "avg_launch_ms": ffn_ms[1], "flops_per_launch": flops_up, "launches": n_rec,
         },
         "grouped_gemm": {
