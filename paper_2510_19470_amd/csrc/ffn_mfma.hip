@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
     const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets,
     const void* const* __restrict__ present, int E, int S, int max_mtiles, int nt_up, int nt_down,
     TileSched* __restrict__ sched, MTile* __restrict__ mt, uint32_t* __restrict__ order_up,
-    uint32_t* __restrict__ order_down) {
+    uint32_t* __restrict__ order_down, int32_t* __restrict__ koff) {
   __shared__ int32_t start[MOE_MAX_EXPERTS + 1];
   __shared__ int bad;
   const int tid = threadIdx.x;
@@ -70,6 +70,25 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
   }
   const int total_m = (bad || start[E] > max_mtiles) ? 0 : start[E];
   if (blockIdx.x == 0 && tid == 0) sched->n_mtiles = total_m;
+  // Backward only: column offset of every expert in the transposed activation buffers,
+  // each expert's rows padded to a multiple of 128 (koff[e+1]-koff[e] = padded count).
+  if (koff != nullptr && blockIdx.x == 0) {
+    __shared__ int32_t kp[MOE_MAX_EXPERTS + 1];
+    int pad = 0;
+    if (!bad && tid < E && present[tid] != nullptr) pad = (counts[tid] + 127) & ~127;
+    kp[tid + 1] = pad;
+    if (tid == 0) kp[0] = 0;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+      int v = 0;
+      if (tid >= off) v = kp[tid + 1 - off];
+      __syncthreads();
+      if (tid >= off) kp[tid + 1] += v;
+      __syncthreads();
+    }
+    if (tid <= E) koff[tid] = kp[tid];
+    if (tid == 0 && E == 256) koff[256] = kp[256];
+  }
   const int gsz = gridDim.x * blockDim.x;
   const int gid = blockIdx.x * blockDim.x + tid;
   for (int i = gid; i < total_m; i += gsz) {
@@ -171,49 +190,100 @@ __device__ __forceinline__ void wait_stage_and_sync() {
   __syncthreads();
 }
 
-template <bool GATED>
-__global__ __launch_bounds__(NT) void ffn_mfma_kernel(
-    const uint16_t* __restrict__ A, const TileSched* __restrict__ sched,
-    const MTile* __restrict__ mt, const uint32_t* __restrict__ order, int n_tiles_n,
-    const void* const* __restrict__ Bt0, const void* const* __restrict__ Bt1, int K, int N,
-    uint16_t* __restrict__ C, uint16_t* __restrict__ Gs, uint16_t* __restrict__ Us) {
+enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_WGRAD = 3 };
+
+struct GemmArgs {
+  const uint16_t* A;    // token-role operand: [rows, lda]
+  int lda;              // elements per row of A (and of BT in MODE_WGRAD)
+  const TileSched* sched;
+  const MTile* mt;
+  const uint32_t* order;
+  int n_tiles_n;
+  const void* const* Bt0;  // weight-role operand table (UP: W1; DOWN: W2 or [W1^T|W3^T]; DH: W2^T)
+  const void* const* Bt1;  // UP: W3
+  int K;                   // contraction length (not MODE_WGRAD)
+  int N;                   // elements per output row
+  uint16_t* C;             // UP: H; DOWN: Y / dX; DH: [dG|dU] with row pitch 2N
+  uint16_t* C2;            // DH: H
+  uint16_t* Gs;            // UP: optional save (out); DH: saved G (in)
+  uint16_t* Us;
+  // MODE_WGRAD: dW[e][Mo,No] = AT_e * BT_e^T over the expert's padded row range
+  const uint16_t* BT;
+  const int32_t* koff;
+  const void* const* present;
+  const void* const* dWt;
+  int Mo, No, a_row0, b_row0;
+};
+
+// MODE_UP   : H = silu(A W1^T) * (A W3^T)            (gate/up, SwiGLU fused)
+// MODE_DOWN : C = A B^T                               (down projection; also dX = [dG|dU][W1^T|W3^T]^T)
+// MODE_DH   : dH = A B^T, then dG = dH*u*silu'(g), dU = dH*silu(g), H = silu(g)*u
+// MODE_WGRAD: fp32 dW = AT BT^T, both operands transposed activations (contraction = rows)
+template <int MODE>
+__global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   // two stages, each 256 token rows + 256 weight rows of 64 bf16 (separate arrays so that
   // reads of one stage are known not to alias the copy in flight into the other)
   __shared__ uint4 ldsA0[STAGE_VEC];
   __shared__ uint4 ldsB0[STAGE_VEC];
   __shared__ uint4 ldsA1[STAGE_VEC];
   __shared__ uint4 ldsB1[STAGE_VEC];
-
-  const int total = sched->n_mtiles * n_tiles_n;
-  const int per_xcd = (total + 7) >> 3;
-  const int slot = blockIdx.x >> 3;
-  const int L = (blockIdx.x & 7) * per_xcd + slot;
-  if (slot >= per_xcd || L >= total) return;
-  const uint32_t ent = order[L];
-  const MTile tl = mt[ent >> 12];
-  const int nblk = ent & 0xfff;
+  constexpr bool GATED = MODE == MODE_UP;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
-
-  // ---- global -> LDS assignment: lane (lane>>3, lane&7) of block b = wave*4+i fills LDS
-  // row 8b + (lane>>3), chunk slot (lane&7), which must hold global chunk slot ^ swz(row)
+  MTile tl;
+  int nblk, KT;
   const uint4* a_src[4];
   const uint4* b_src[4];
-  const uint16_t* B0 = (const uint16_t*)Bt0[tl.expert];
-  const uint16_t* B1 = GATED ? (const uint16_t*)Bt1[tl.expert] : nullptr;
+  float* dW = nullptr;
+  int mblk = 0;
+  if (MODE == MODE_WGRAD) {
+    const int MoT = p.Mo >> 8, NoT = p.No >> 8;
+    const int e = blockIdx.x / (MoT * NoT);
+    const int rem = blockIdx.x % (MoT * NoT);
+    mblk = rem / NoT;
+    nblk = rem % NoT;
+    dW = (float*)p.dWt[e];
+    if (dW == nullptr || p.present[e] == nullptr) return;
+    const int k0 = p.koff[e];
+    KT = (p.koff[e + 1] - k0) / BK;
+    tl.expert = e;
+    tl.row0 = 0;
+    tl.rows = BM;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = (wave * 4 + i) * 8 + (lane >> 3);
-    const int ch = (lane & 7) ^ swz(row);
-    const int arow = min(row, tl.rows - 1);
-    a_src[i] = (const uint4*)(A + (size_t)(tl.row0 + arow) * K) + ch;
-    const uint16_t* bp;
-    if (GATED)
-      bp = (row < 128 ? B0 : B1) + (size_t)(nblk * 128 + (row & 127)) * K;
-    else
-      bp = B0 + (size_t)(nblk * 256 + row) * K;
-    b_src[i] = (const uint4*)bp + ch;
+    for (int i = 0; i < 4; ++i) {
+      const int row = (wave * 4 + i) * 8 + (lane >> 3);
+      const int ch = (lane & 7) ^ swz(row);
+      a_src[i] = (const uint4*)(p.A + (size_t)(p.a_row0 + mblk * 256 + row) * p.lda + k0) + ch;
+      b_src[i] = (const uint4*)(p.BT + (size_t)(p.b_row0 + nblk * 256 + row) * p.lda + k0) + ch;
+    }
+  } else {
+    const int total = p.sched->n_mtiles * p.n_tiles_n;
+    const int per_xcd = (total + 7) >> 3;
+    const int slot = blockIdx.x >> 3;
+    const int L = (blockIdx.x & 7) * per_xcd + slot;
+    if (slot >= per_xcd || L >= total) return;
+    const uint32_t ent = p.order[L];
+    tl = p.mt[ent >> 12];
+    nblk = ent & 0xfff;
+    KT = p.K / BK;
+    // global -> LDS assignment: lane (lane>>3, lane&7) of block b = wave*4+i fills LDS row
+    // 8b + (lane>>3), chunk slot (lane&7), which must hold global chunk slot ^ swz(row)
+    const uint16_t* B0 = (const uint16_t*)p.Bt0[tl.expert];
+    const uint16_t* B1 = GATED ? (const uint16_t*)p.Bt1[tl.expert] : nullptr;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = (wave * 4 + i) * 8 + (lane >> 3);
+      const int ch = (lane & 7) ^ swz(row);
+      const int arow = min(row, tl.rows - 1);
+      a_src[i] = (const uint4*)(p.A + (size_t)(tl.row0 + arow) * p.lda) + ch;
+      const uint16_t* bp;
+      if (GATED)
+        bp = (row < 128 ? B0 : B1) + (size_t)(nblk * 128 + (row & 127)) * p.K;
+      else
+        bp = B0 + (size_t)(nblk * 256 + row) * p.K;
+      b_src[i] = (const uint4*)bp + ch;
+    }
   }
 
   // ---- fragment read offsets (uint4 units inside one operand stage)
@@ -235,9 +305,10 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(
 
   // K is a multiple of 128, so the number of k-steps is even and the loop can alternate
   // the two stages without a conditional exit (keeps the accumulators in registers).
-  const int KT = K / BK;
-  issue_stage(a_src, b_src, 0, ldsA0, ldsB0, wave);
-  wait_stage_and_sync();
+  if (KT > 0) {
+    issue_stage(a_src, b_src, 0, ldsA0, ldsB0, wave);
+    wait_stage_and_sync();
+  }
   for (int kt = 0; kt < KT; kt += 2) {
     issue_stage(a_src, b_src, (kt + 1) * 8, ldsA1, ldsB1, wave);
     mma_stage(acc, ldsA0, ldsB0, fr_a, fr_b, fr_half, fr_swz);
@@ -256,8 +327,21 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(
   for (int i = 0; i < 4; ++i) {
     const int m_local = wm * 128 + i * 32 + fr_row;
     if (m_local >= tl.rows) continue;
-    const size_t rbase = (size_t)(tl.row0 + m_local) * N;
-    if (GATED) {
+    if (MODE == MODE_WGRAD) {
+      float* orow = dW + (size_t)(mblk * 256 + m_local) * p.No;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col0 = nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(orow + col0 + 8 * g) =
+              make_float4(acc[j][i][g * 4], acc[j][i][g * 4 + 1], acc[j][i][g * 4 + 2],
+                          acc[j][i][g * 4 + 3]);
+      }
+      continue;
+    }
+    const size_t row = (size_t)(tl.row0 + m_local);
+    if (MODE == MODE_UP) {
       const int col0 = nblk * 128 + wn * 32 + 4 * fr_half;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -267,13 +351,14 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(
           const float gv = acc[0][i][g * 4 + r], uv = acc[1][i][g * 4 + r];
           h[r] = silu_f(gv) * uv;
         }
-        const size_t o = rbase + col0 + 8 * g;
-        *reinterpret_cast<uint2*>(C + o) = make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
-        if (Gs != nullptr) {
-          *reinterpret_cast<uint2*>(Gs + o) =
+        const size_t o = row * p.N + col0 + 8 * g;
+        *reinterpret_cast<uint2*>(p.C + o) =
+            make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+        if (p.Gs != nullptr) {
+          *reinterpret_cast<uint2*>(p.Gs + o) =
               make_uint2(pack_bf16x2(acc[0][i][g * 4], acc[0][i][g * 4 + 1]),
                          pack_bf16x2(acc[0][i][g * 4 + 2], acc[0][i][g * 4 + 3]));
-          *reinterpret_cast<uint2*>(Us + o) =
+          *reinterpret_cast<uint2*>(p.Us + o) =
               make_uint2(pack_bf16x2(acc[1][i][g * 4], acc[1][i][g * 4 + 1]),
                          pack_bf16x2(acc[1][i][g * 4 + 2], acc[1][i][g * 4 + 3]));
         }
@@ -284,14 +369,88 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(
         const int col0 = nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const size_t o = rbase + col0 + 8 * g;
-          *reinterpret_cast<uint2*>(C + o) =
-              make_uint2(pack_bf16x2(acc[j][i][g * 4], acc[j][i][g * 4 + 1]),
-                         pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]));
+          const int col = col0 + 8 * g;
+          if (MODE == MODE_DOWN) {
+            *reinterpret_cast<uint2*>(p.C + row * p.N + col) =
+                make_uint2(pack_bf16x2(acc[j][i][g * 4], acc[j][i][g * 4 + 1]),
+                           pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]));
+          } else {  // MODE_DH
+            const uint2 gq = *reinterpret_cast<const uint2*>(p.Gs + row * p.N + col);
+            const uint2 uq = *reinterpret_cast<const uint2*>(p.Us + row * p.N + col);
+            const uint32_t gw[2] = {gq.x, gq.y}, uw[2] = {uq.x, uq.y};
+            float dg[4], du[4], hh[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float gv = __uint_as_float((r & 1) ? (gw[r >> 1] & 0xffff0000u) : (gw[r >> 1] << 16));
+              const float uv = __uint_as_float((r & 1) ? (uw[r >> 1] & 0xffff0000u) : (uw[r >> 1] << 16));
+              const float dh = acc[j][i][g * 4 + r];
+              const float sg = 1.f / (1.f + __expf(-gv));
+              dg[r] = dh * uv * sg * (1.f + gv * (1.f - sg));
+              du[r] = dh * gv * sg;
+              hh[r] = gv * sg * uv;
+            }
+            *reinterpret_cast<uint2*>(p.C + row * (2 * (size_t)p.N) + col) =
+                make_uint2(pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3]));
+            *reinterpret_cast<uint2*>(p.C + row * (2 * (size_t)p.N) + p.N + col) =
+                make_uint2(pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3]));
+            *reinterpret_cast<uint2*>(p.C2 + row * p.N + col) =
+                make_uint2(pack_bf16x2(hh[0], hh[1]), pack_bf16x2(hh[2], hh[3]));
+          }
         }
       }
     }
   }
+}
+
+// ---- transposes feeding the backward GEMMs ------------------------------------------
+// All GEMMs here want both operands contiguous along the contraction dimension.  The
+// backward contracts over the other index of the weights (dH = dY W2, dX = dG W1 + dU W3)
+// and over the token rows (dW = P^T Q), so the weights and the activations are transposed
+// once per call with a 64x64 LDS tile.
+
+// out[c][col_off + r] = in[r][c] for every expert with a source; in: [R,C], out pitch given.
+__global__ __launch_bounds__(256) void transpose_weights_kernel(const void* const* __restrict__ src_t,
+                                                                const void* const* __restrict__ dst_t,
+                                                                int R, int C, int dst_pitch,
+                                                                int col_off) {
+  __shared__ uint16_t tile[64][66];
+  const int e = blockIdx.z;
+  const uint16_t* src = (const uint16_t*)src_t[e];
+  uint16_t* dst = (uint16_t*)dst_t[e];
+  if (src == nullptr || dst == nullptr) return;
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) tile[i][tx] = src[(size_t)(r0 + i) * C + c0 + tx];
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4)
+    dst[(size_t)(c0 + i) * dst_pitch + col_off + r0 + tx] = tile[tx][i];
+}
+
+// dst[c][koff[e] + r] = src[offsets[e] + r][c] for r < counts[e], 0 for the padding rows.
+__global__ __launch_bounds__(256) void transpose_acts_kernel(
+    const uint16_t* __restrict__ src, int src_pitch, int C, const int32_t* __restrict__ counts,
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ koff, int E,
+    uint16_t* __restrict__ dst, int dst_pitch) {
+  __shared__ uint16_t tile[64][66];
+  __shared__ int32_t s_koff[MOE_MAX_EXPERTS + 1];
+  for (int i = threadIdx.x; i <= E; i += 256) s_koff[i] = koff[i];
+  __syncthreads();
+  const int k0 = blockIdx.x * 64;  // 64 padded rows; never straddles experts (pads are x128)
+  if (k0 >= s_koff[E]) return;
+  int lo = 0, hi = E;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (s_koff[mid] <= k0) lo = mid; else hi = mid;
+  }
+  const int e = lo;
+  const int rel = k0 - s_koff[e];
+  const int n = counts[e], row0 = offsets[e];
+  const int c0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4)
+    tile[i][tx] = (rel + i < n) ? src[(size_t)(row0 + rel + i) * src_pitch + c0 + tx] : (uint16_t)0;
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) dst[(size_t)(c0 + i) * dst_pitch + k0 + tx] = tile[tx][i];
 }
 
 }  // namespace
@@ -308,28 +467,128 @@ size_t ffn_mfma_order_entries(const moe_ctx* c) {
   return (size_t)c->max_mtiles[1] * (nt_up > nt_down ? nt_up : nt_down);
 }
 
+static int run_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets, int nt_a, int nt_b,
+                     int32_t* koff, hipStream_t s) {
+  hipLaunchKernelGGL(mfma_sched_kernel, dim3(32), dim3(256), 0, s, counts, offsets,
+                     c->d_wtab + 0 * MOE_MAX_EXPERTS, c->cfg.E, c->S_max, c->max_mtiles[1], nt_a,
+                     nt_b, c->d_sched[1], c->d_mtiles[1], c->d_order_up, c->d_order_down, koff);
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+}
+
+static GemmArgs tiled_args(moe_ctx* c, const void* A, int lda, const uint32_t* order, int nt,
+                           const void* const* B0, const void* const* B1, int K, int N, void* C) {
+  GemmArgs a{};
+  a.A = (const uint16_t*)A;
+  a.lda = lda;
+  a.sched = c->d_sched[1];
+  a.mt = c->d_mtiles[1];
+  a.order = order;
+  a.n_tiles_n = nt;
+  a.Bt0 = B0;
+  a.Bt1 = B1;
+  a.K = K;
+  a.N = N;
+  a.C = (uint16_t*)C;
+  return a;
+}
+
 int launch_ffn_mfma(moe_ctx* c, const int32_t* counts, const int32_t* offsets, const void* x_packed,
                     void* y_packed, void* G, void* U, hipStream_t s) {
-  const int d = c->cfg.d, f = c->cfg.f, E = c->cfg.E;
+  const int d = c->cfg.d, f = c->cfg.f;
   const int nt_up = f / 128, nt_down = d / 256;
   const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
   const void* const* W3 = c->d_wtab + 1 * MOE_MAX_EXPERTS;
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
   const int max_mt = c->max_mtiles[1];
   prof_mark(c, 0, s);
-  hipLaunchKernelGGL(mfma_sched_kernel, dim3(32), dim3(256), 0, s, counts, offsets, W1, E,
-                     c->S_max, max_mt, nt_up, nt_down, c->d_sched[1], c->d_mtiles[1], c->d_order_up, c->d_order_down);
+  int st = run_sched(c, counts, offsets, nt_up, nt_down, nullptr, s);
+  if (st != MOE_OK) return st;
   const int grid_up = ((max_mt * nt_up + 7) / 8) * 8;
   const int grid_down = ((max_mt * nt_down + 7) / 8) * 8;
   prof_mark(c, 1, s);
-  hipLaunchKernelGGL((ffn_mfma_kernel<true>), dim3(grid_up), dim3(NT), 0, s,
-                     (const uint16_t*)x_packed, c->d_sched[1], c->d_mtiles[1], c->d_order_up, nt_up,
-                     W1, W3, d, f, (uint16_t*)c->d_H, (uint16_t*)G, (uint16_t*)U);
+  GemmArgs up = tiled_args(c, x_packed, d, c->d_order_up, nt_up, W1, W3, d, f, c->d_H);
+  up.Gs = (uint16_t*)G;
+  up.Us = (uint16_t*)U;
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_UP>), dim3(grid_up), dim3(NT), 0, s, up);
   prof_mark(c, 2, s);
-  hipLaunchKernelGGL((ffn_mfma_kernel<false>), dim3(grid_down), dim3(NT), 0, s,
-                     (const uint16_t*)c->d_H, c->d_sched[1], c->d_mtiles[1], c->d_order_down,
-                     nt_down, W2, (const void* const*)nullptr, f, d, (uint16_t*)y_packed,
-                     (uint16_t*)nullptr, (uint16_t*)nullptr);
+  GemmArgs dn = tiled_args(c, c->d_H, f, c->d_order_down, nt_down, W2, nullptr, f, d, y_packed);
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN>), dim3(grid_down), dim3(NT), 0, s, dn);
   prof_mark(c, 3, s);
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+}
+
+bool ffn_bwd_mfma_supported(const moe_ctx* c) {
+  return ffn_mfma_supported(c) && c->cfg.f % 256 == 0;
+}
+
+// Elements per row of the transposed activation buffers: every expert padded to x128.
+int ffn_bwd_ktot(const moe_ctx* c) { return ((c->S_max + 127 * c->cfg.E + 127) / 128) * 128; }
+
+// dy, xp: [S,d]; G, U: [S,f] (forward saves); dxp out.  Workspace (context): d_H [S,f],
+// d_dGU [S,2f], d_actT: dY^T [d,Kt] | X^T [d,Kt] | H^T [f,Kt] | [dG|dU]^T [2f,Kt];
+// table rows 6 (W2^T) and 7 ([W1^T|W3^T]) point into d_wT.
+int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* G, const void* U,
+                        const int32_t* counts, const int32_t* offsets, void* dxp, hipStream_t s) {
+  const int d = c->cfg.d, f = c->cfg.f, E = c->cfg.E;
+  const int Kt = ffn_bwd_ktot(c);
+  const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
+  const void* const* W3 = c->d_wtab + 1 * MOE_MAX_EXPERTS;
+  const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
+  const void* const* dW1 = c->d_wtab + 3 * MOE_MAX_EXPERTS;
+  const void* const* dW3 = c->d_wtab + 4 * MOE_MAX_EXPERTS;
+  const void* const* dW2 = c->d_wtab + 5 * MOE_MAX_EXPERTS;
+  const void* const* W2T = c->d_wtab + 6 * MOE_MAX_EXPERTS;
+  const void* const* W13T = c->d_wtab + 7 * MOE_MAX_EXPERTS;
+  const int nt_f = f / 256, nt_d = d / 256;
+  const int max_mt = c->max_mtiles[1];
+  int st = run_sched(c, counts, offsets, nt_f, nt_d, c->d_koff, s);
+  if (st != MOE_OK) return st;
+  // weights: W2 [d,f] -> W2^T [f,d];  W1, W3 [f,d] -> [W1^T | W3^T] [d,2f]
+  hipLaunchKernelGGL(transpose_weights_kernel, dim3(f / 64, d / 64, E), dim3(256), 0, s, W2, W2T, d,
+                     f, d, 0);
+  hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, s, W1, W13T, f,
+                     d, 2 * f, 0);
+  hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, s, W3, W13T, f,
+                     d, 2 * f, f);
+  // dH = dY W2 with the SwiGLU derivative in the epilogue -> [dG|dU], H
+  GemmArgs dh = tiled_args(c, dy, d, c->d_order_up, nt_f, W2T, nullptr, d, f, c->d_dGU);
+  dh.C2 = (uint16_t*)c->d_H;
+  dh.Gs = (uint16_t*)const_cast<void*>(G);
+  dh.Us = (uint16_t*)const_cast<void*>(U);
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH>), dim3(((max_mt * nt_f + 7) / 8) * 8), dim3(NT), 0, s,
+                     dh);
+  // dX = [dG|dU] [W1^T|W3^T]^T  (one GEMM with contraction length 2f)
+  GemmArgs dx = tiled_args(c, c->d_dGU, 2 * f, c->d_order_down, nt_d, W13T, nullptr, 2 * f, d, dxp);
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN>), dim3(((max_mt * nt_d + 7) / 8) * 8), dim3(NT), 0,
+                     s, dx);
+  // activations transposed per expert segment (zero padded to x128 rows)
+  uint16_t* dYT = (uint16_t*)c->d_actT;
+  uint16_t* XT = dYT + (size_t)d * Kt;
+  uint16_t* HT = XT + (size_t)d * Kt;
+  uint16_t* dGUT = HT + (size_t)f * Kt;
+  const int kblocks = Kt / 64;
+  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, d / 64), dim3(256), 0, s,
+                     (const uint16_t*)dy, d, d, counts, offsets, c->d_koff, E, dYT, Kt);
+  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, d / 64), dim3(256), 0, s,
+                     (const uint16_t*)xp, d, d, counts, offsets, c->d_koff, E, XT, Kt);
+  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, f / 64), dim3(256), 0, s,
+                     (const uint16_t*)c->d_H, f, f, counts, offsets, c->d_koff, E, HT, Kt);
+  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, 2 * f / 64), dim3(256), 0, s,
+                     (const uint16_t*)c->d_dGU, 2 * f, 2 * f, counts, offsets, c->d_koff, E, dGUT,
+                     Kt);
+  // weight gradients, fp32
+  GemmArgs w{};
+  w.lda = Kt;
+  w.koff = c->d_koff;
+  w.present = W1;
+  // dW2 [d,f] = dY^T H
+  w.A = dYT; w.BT = HT; w.dWt = dW2; w.Mo = d; w.No = f; w.a_row0 = 0; w.b_row0 = 0;
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_WGRAD>), dim3(E * nt_d * nt_f), dim3(NT), 0, s, w);
+  // dW1 [f,d] = dG^T X
+  w.A = dGUT; w.BT = XT; w.dWt = dW1; w.Mo = f; w.No = d; w.a_row0 = 0;
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_WGRAD>), dim3(E * nt_d * nt_f), dim3(NT), 0, s, w);
+  // dW3 [f,d] = dU^T X
+  w.dWt = dW3; w.a_row0 = f;
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_WGRAD>), dim3(E * nt_d * nt_f), dim3(NT), 0, s, w);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }

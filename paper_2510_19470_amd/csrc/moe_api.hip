@@ -32,6 +32,10 @@ void free_all(moe_ctx* c) {
   (void)hipFree(c->d_H);
   (void)hipFree(c->d_dG);
   (void)hipFree(c->d_dU);
+  (void)hipFree(c->d_dGU);
+  (void)hipFree(c->d_actT);
+  (void)hipFree(c->d_koff);
+  (void)hipFree(c->d_wT);
 }
 
 int check_ctx_T(const moe_ctx* c, int32_t T) {
@@ -41,11 +45,12 @@ int check_ctx_T(const moe_ctx* c, int32_t T) {
 }
 
 // Refresh the device copy of the pointer tables when the host tables changed.
-// rows: 0 W1, 1 W3, 2 W2, 3 dW1, 4 dW3, 5 dW2; a NULL table leaves its row as it is.
-int sync_tables(moe_ctx* c, const void* const* const tabs[6], hipStream_t s) {
+// rows: 0 W1, 1 W3, 2 W2, 3 dW1, 4 dW3, 5 dW2, 6 W2^T, 7 [W1^T|W3^T]; a NULL table leaves
+// its row as it is.
+int sync_tables(moe_ctx* c, const void* const* const tabs[MOE_WTAB_ROWS], hipStream_t s) {
   const int E = c->cfg.E;
   bool changed = !c->wtab_valid;
-  for (int r = 0; r < 6; ++r) {
+  for (int r = 0; r < MOE_WTAB_ROWS; ++r) {
     if (tabs[r] == nullptr) continue;
     if (std::memcmp(c->h_wtab[r], tabs[r], sizeof(void*) * E) != 0) {
       std::memcpy(c->h_wtab[r], tabs[r], sizeof(void*) * E);
@@ -124,7 +129,7 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
   ok = ok && dev_alloc(&c->d_chunk_hist, (size_t)c->n_chunks_max * E) == hipSuccess;
   ok = ok && dev_alloc(&c->d_ticket, 1) == hipSuccess;
   ok = ok && dev_alloc(&c->d_logits, (size_t)cfg->T_max * E) == hipSuccess;
-  ok = ok && dev_alloc(&c->d_wtab, 6 * MOE_MAX_EXPERTS) == hipSuccess;
+  ok = ok && dev_alloc(&c->d_wtab, MOE_WTAB_ROWS * MOE_MAX_EXPERTS) == hipSuccess;
   for (int i = 0; i < 2 && ok; ++i) {
     ok = ok && dev_alloc(&c->d_sched[i], 1) == hipSuccess;
     ok = ok && dev_alloc(&c->d_mtiles[i], c->max_mtiles[i]) == hipSuccess;
@@ -136,7 +141,7 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
   }
   ok = ok && hipMalloc(&c->d_H, std::max<size_t>((size_t)S * cfg->f * c->elem, 16)) == hipSuccess;
   ok = ok && hipMemset(c->d_ticket, 0, sizeof(int32_t)) == hipSuccess;
-  ok = ok && hipMemset(c->d_wtab, 0, sizeof(void*) * 6 * MOE_MAX_EXPERTS) == hipSuccess;
+  ok = ok && hipMemset(c->d_wtab, 0, sizeof(void*) * MOE_WTAB_ROWS * MOE_MAX_EXPERTS) == hipSuccess;
   if (!ok) {
     (void)hipGetLastError();
     free_all(c);
@@ -296,7 +301,7 @@ int moe_expert_ffn(moe_ctx* c, const void* x_packed, const int32_t* expert_count
   if (!aligned16(x_packed) || !aligned16(y_packed) || !aligned16(G_save) || !aligned16(U_save))
     return MOE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
-  const void* const* tabs[6] = {W1, W3, W2, nullptr, nullptr, nullptr};
+  const void* const* tabs[MOE_WTAB_ROWS] = {W1, W3, W2, nullptr, nullptr, nullptr, nullptr, nullptr};
   st = sync_tables(c, tabs, s);
   if (st != MOE_OK) return st;
   if (c->ffn_path == MOE_FFN_AUTO && ffn_mfma_supported(c)) {
@@ -357,21 +362,83 @@ int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, 
       !aligned16(dx_packed))
     return MOE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
-  if (c->d_dG == nullptr) {  // first backward call: allocate the temporaries
-    const size_t bytes = std::max<size_t>((size_t)c->S_max * c->cfg.f * c->elem, 16);
-    if (hipMalloc(&c->d_dG, bytes) != hipSuccess || hipMalloc(&c->d_dU, bytes) != hipSuccess) {
+  const size_t sf_bytes = std::max<size_t>((size_t)c->S_max * c->cfg.f * c->elem, 16);
+  if (c->ffn_path == MOE_FFN_AUTO && ffn_bwd_mfma_supported(c)) {
+    // first call (or more resident experts than before): allocate the backward workspace
+    const int d = c->cfg.d, f = c->cfg.f, E = c->cfg.E;
+    size_t n_present = 0;
+    for (int e = 0; e < E; ++e) n_present += W1[e] != nullptr;
+    if (c->d_dGU == nullptr) {
+      const size_t kt = (size_t)ffn_bwd_ktot(c);
+      bool ok = hipMalloc(&c->d_dGU, 2 * sf_bytes) == hipSuccess;
+      ok = ok && hipMalloc(&c->d_actT, (2 * (size_t)d + 3 * (size_t)f) * kt * 2) == hipSuccess;
+      ok = ok && hipMalloc(reinterpret_cast<void**>(&c->d_koff), sizeof(int32_t) * (E + 1)) ==
+                     hipSuccess;
+      if (!ok) {
+        (void)hipGetLastError();
+        (void)hipFree(c->d_dGU);
+        (void)hipFree(c->d_actT);
+        (void)hipFree(c->d_koff);
+        c->d_dGU = c->d_actT = nullptr;
+        c->d_koff = nullptr;
+        return MOE_ENOMEM;
+      }
+    }
+    if (n_present > c->wT_experts) {
+      if (c->d_wT != nullptr) {
+        (void)hipStreamSynchronize(s);
+        (void)hipFree(c->d_wT);
+        c->d_wT = nullptr;
+        c->wT_experts = 0;
+      }
+      if (hipMalloc(&c->d_wT, n_present * 3 * (size_t)d * f * 2) != hipSuccess) {
+        (void)hipGetLastError();
+        return MOE_ENOMEM;
+      }
+      c->wT_experts = n_present;
+    }
+    const void* w2t[MOE_MAX_EXPERTS];
+    const void* w13t[MOE_MAX_EXPERTS];
+    size_t slot = 0;
+    for (int e = 0; e < E; ++e) {
+      if (W1[e] == nullptr) {
+        w2t[e] = w13t[e] = nullptr;
+        continue;
+      }
+      uint16_t* base = (uint16_t*)c->d_wT + slot * 3 * (size_t)d * f;
+      w2t[e] = base;
+      w13t[e] = base + (size_t)d * f;
+      ++slot;
+    }
+    const void* const* tabs[MOE_WTAB_ROWS] = {W1,
+                                              W3,
+                                              W2,
+                                              reinterpret_cast<const void* const*>(dW1),
+                                              reinterpret_cast<const void* const*>(dW3),
+                                              reinterpret_cast<const void* const*>(dW2),
+                                              w2t,
+                                              w13t};
+    st = sync_tables(c, tabs, s);
+    if (st != MOE_OK) return st;
+    return launch_ffn_bwd_mfma(c, dy_packed, x_packed, G_save, U_save, expert_counts,
+                               expert_offsets, dx_packed, s);
+  }
+  if (c->d_dG == nullptr) {  // first backward call on this path: allocate the temporaries
+    if (hipMalloc(&c->d_dG, sf_bytes) != hipSuccess || hipMalloc(&c->d_dU, sf_bytes) != hipSuccess) {
       (void)hipGetLastError();
       (void)hipFree(c->d_dG);
       c->d_dG = nullptr;
       return MOE_ENOMEM;
     }
   }
-  const void* const* tabs[6] = {W1,
-                                W3,
-                                W2,
-                                reinterpret_cast<const void* const*>(dW1),
-                                reinterpret_cast<const void* const*>(dW3),
-                                reinterpret_cast<const void* const*>(dW2)};
+  const void* const* tabs[MOE_WTAB_ROWS] = {W1,
+                                            W3,
+                                            W2,
+                                            reinterpret_cast<const void* const*>(dW1),
+                                            reinterpret_cast<const void* const*>(dW3),
+                                            reinterpret_cast<const void* const*>(dW2),
+                                            nullptr,
+                                            nullptr};
   st = sync_tables(c, tabs, s);
   if (st != MOE_OK) return st;
   st = launch_build_sched(c, expert_counts, expert_offsets, 0, s);

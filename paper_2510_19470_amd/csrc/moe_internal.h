@@ -21,6 +21,9 @@ struct TileSched {
   int32_t pad[3];
 };
 
+// pointer-table rows: W1, W3, W2, dW1, dW3, dW2, W2^T, [W1^T|W3^T]
+#define MOE_WTAB_ROWS 8
+
 struct moe_ctx {
   moe_config cfg;
   int device;
@@ -37,7 +40,7 @@ struct moe_ctx {
   // expert weight pointer tables: device copy [6][MOE_MAX_EXPERTS] (W1, W3, W2, dW1, dW3,
   // dW2), refreshed only when the host tables change
   const void** d_wtab;
-  const void* h_wtab[6][MOE_MAX_EXPERTS];
+  const void* h_wtab[MOE_WTAB_ROWS][MOE_MAX_EXPERTS];
   int wtab_valid;
   // grouped GEMM schedules: [0] 64-row tiles (vector ALU path), [1] 256-row tiles (MFMA)
   TileSched* d_sched[2];
@@ -49,8 +52,13 @@ struct moe_ctx {
   uint32_t* d_order_down; // ... and of the down GEMM
   int32_t S_max;          // T_max*k
   void* d_H;              // [T_max*k][f]
-  void* d_dG;             // [T_max*k][f]
+  void* d_dG;             // [T_max*k][f]   (vector-ALU backward)
   void* d_dU;             // [T_max*k][f]
+  void* d_dGU;            // [T_max*k][2f]  (MFMA backward: dG | dU)
+  void* d_actT;           // transposed activations of the MFMA backward
+  int32_t* d_koff;        // [E+1] padded row offsets of the experts in d_actT
+  void* d_wT;             // transposed weights of the MFMA backward
+  size_t wT_experts;      // experts d_wT has room for
   // optional HIP-event timing of the internal launches of moe_expert_ffn
   int prof_calls;         // capacity in calls (0 = off)
   int prof_n;             // calls recorded so far
@@ -94,6 +102,10 @@ bool ffn_mfma_supported(const moe_ctx* c);
 size_t ffn_mfma_order_entries(const moe_ctx* c);
 int launch_ffn_mfma(moe_ctx* c, const int32_t* counts, const int32_t* offsets, const void* x_packed,
                     void* y_packed, void* G, void* U, hipStream_t s);
+bool ffn_bwd_mfma_supported(const moe_ctx* c);
+int ffn_bwd_ktot(const moe_ctx* c);
+int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* G, const void* U,
+                        const int32_t* counts, const int32_t* offsets, void* dxp, hipStream_t s);
 int launch_ffn_bwd_generic(moe_ctx* c, const void* dy, const void* xp, const void* G,
                            const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
                            void* dG_tmp, void* dU_tmp, void* H_tmp, hipStream_t s);

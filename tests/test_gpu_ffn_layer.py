@@ -193,15 +193,25 @@ def test_full_size_configs_sampled_rows(name):
     _sampled_rows_check(cfg)
 
 
-@pytest.mark.parametrize("name,T", [("tiny", None), ("train", 512)])
-def test_backward_matches_oracle(name, T):
-    from gpu_common import DEV, TOL, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
+@pytest.mark.parametrize("name,T,path,shape", [
+    ("tiny", None, "auto", None), ("train", 512, "auto", None), ("train", 512, "valu", None),
+    ("train", 700, "auto", dict(d=256, f=512, E=8, k=2, R=4, migrated=(5,))),      # ragged, small
+    ("train", 300, "auto", dict(d=512, f=256, E=16, k=1, R=4, migrated=())),       # empty experts
+])
+def test_backward_matches_oracle(name, T, path, shape):
+    from gpu_common import DEV, TOL, moe, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
     cfg = wl.scaled(wl.CONFIGS[name], backward=True)
     if T is not None:
         cfg = wl.scaled(cfg, T=T)
-    say(f"[bwd] config={name} T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} f={cfg.f}")
+    if shape is not None:
+        cfg = wl.scaled(cfg, **shape)
+    say(f"[bwd] config={name} path={path} T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} f={cfg.f}")
     inp = wl.make_inputs(cfg)
+    if shape is not None and cfg.k == 1:
+        inp.bias = (-2.0 * np.log(np.arange(cfg.E) + 1.0)).astype(np.float32)   # starve the tail experts
     lay = layer_from_inputs(inp)
+    if path == "valu":
+        moe.moe_set_ffn_path(lay.ctx, moe.MOE_FFN_VALU)
     x = to_device(inp.x, cfg.dtype)
     dout = to_device(inp.dOut, cfg.dtype)
     fwd = lay.forward(x, save=True)
@@ -221,10 +231,15 @@ def test_backward_matches_oracle(name, T):
                 dw=nerr(bwd["dtopk_w"].cpu().numpy(), dw_o),
                 dxp=nerr(to_host_f32(bwd["dx_packed"]), dxp_o),
                 dx=nerr(to_host_f32(bwd["dx"]), dx_o))
+    scale = max(np.max(np.abs(dW2_o[e])) for e in range(cfg.E))
     for e in range(cfg.E):
-        errs[f"dW1[{e}]"] = nerr(bwd["dW1"][e].cpu().numpy(), dW1_o[e])
-        errs[f"dW3[{e}]"] = nerr(bwd["dW3"][e].cpu().numpy(), dW3_o[e])
-        errs[f"dW2[{e}]"] = nerr(bwd["dW2"][e].cpu().numpy(), dW2_o[e])
+        # experts with few or no tokens have tiny gradients: normalise by the layer's largest
+        for nm, got, want in (("dW1", bwd["dW1"][e], dW1_o[e]), ("dW3", bwd["dW3"][e], dW3_o[e]),
+                              ("dW2", bwd["dW2"][e], dW2_o[e])):
+            g = got.cpu().numpy().astype(np.float64)
+            if cnt[e] == 0:
+                assert np.all(g == 0), (nm, e)
+            errs[f"{nm}[{e}]"] = float(np.max(np.abs(g - want)) / max(np.max(np.abs(want)), 1e-3 * scale))
     say("    " + ", ".join(f"{k_}={v:.2e}" for k_, v in list(errs.items())[:7]))
     bad = {k_: v for k_, v in errs.items() if not v <= tol}
     assert not bad, bad
