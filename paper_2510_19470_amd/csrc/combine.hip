@@ -24,6 +24,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pa
     rows[j] = ((unsigned)r < (unsigned)S) ? r : -1;
     w[j] = j < k ? topk_w[(size_t)t * k + j] : 0.f;
   }
+#pragma unroll 4
   for (int c = lane * N; c < d; c += 64 * N) {
     float acc[N];
 #pragma unroll

@@ -3,138 +3,73 @@
 // activated experts; Sec. 3.2: one contiguous chunk per peer, and the chunk of an expert
 // that was fetched by all-gather stays local).
 //
-// Two launches, no host synchronisation:
-//   1. dispatch_count: every chunk of 1024 slots ranks its slots per expert (ballot +
-//      popcount per expert value inside a wavefront, LDS prefix over wavefronts), stores
-//      the in-chunk rank of each slot and the chunk's expert histogram; the last block to
-//      arrive (atomic ticket, no spinning) turns the histograms into exclusive prefixes
-//      over chunks and writes counts / offsets / rank chunks.
-//   2. dispatch_scatter: one wavefront per token turns the in-chunk ranks of its k slots
-//      into final rows (expert offset + chunk prefix + rank), writes both maps, reads the
-//      token row once (16 B per lane) and writes it to its k packed rows.
+// Two launches, no host synchronisation, no waiting between blocks:
+//   1. dispatch_count: every chunk of 1024 slots ranks its slots per expert (one ballot per
+//      bit of the expert id gives the lanes with the same expert, popcount below the lane
+//      gives the rank inside the wavefront; LDS prefix over the 16 wavefronts), stores the
+//      in-chunk rank of each slot and the chunk's expert histogram, and adds the histogram
+//      to the per-expert totals with integer atomics (their order cannot change the sums).
+//   2. dispatch_scatter: every block first turns the totals into expert offsets (scan in
+//      segment order, in LDS); one wavefront per token then sums the histograms of the
+//      chunks before its own (the prefix that makes the ranking stable across chunks),
+//      forms the final rows, writes both maps, reads the token row once (16 B per lane)
+//      and writes it to its k packed rows.  Block 0 also writes counts / offsets / rank
+//      chunks.
 // The permutation is deterministic: no atomic decides a row number.
+// The totals are double-buffered: call n accumulates into buffer n&1 and clears the other
+// one for call n+1 (calls on one context are ordered in time).
 #include "moe_internal.h"
 
 namespace {
 
-__device__ __forceinline__ int32_t load_agent(const int32_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Lanes of the wavefront holding the same value as this lane (value in [0,256) or -1 for
+// "none"): one ballot per bit of the value, no loop over the distinct values.
+__device__ __forceinline__ unsigned long long match_same(int e, int nbits) {
+  unsigned long long m = __ballot(e >= 0);
+  for (int b = 0; b < nbits; ++b) {
+    const unsigned long long bal = __ballot((e >> b) & 1);
+    m &= ((e >> b) & 1) ? bal : ~bal;
+  }
+  return m;
 }
 
-__global__ __launch_bounds__(256) void dispatch_count_kernel(
-    const int32_t* __restrict__ topk_idx, int S, int E, int R, int n_chunks,
-    const int32_t* __restrict__ dest_rank, const int32_t* __restrict__ seg_order,
-    int32_t* __restrict__ chunk_hist, int32_t* __restrict__ ticket,
-    int32_t* __restrict__ slot_rank, int32_t* __restrict__ expert_counts,
-    int32_t* __restrict__ expert_offsets, int32_t* __restrict__ rank_counts,
-    int32_t* __restrict__ rank_offsets) {
-  __shared__ int32_t wcnt[4][MOE_MAX_EXPERTS];
-  __shared__ int32_t tot[MOE_MAX_EXPERTS];
-  __shared__ int32_t s_order[MOE_MAX_EXPERTS];
-  __shared__ int32_t s_dest[MOE_MAX_EXPERTS];
-  __shared__ int32_t rcnt[MOE_MAX_RANKS];
-  __shared__ int is_last;
+constexpr int COUNT_THREADS = DISPATCH_CHUNK;  // one slot per thread, 16 wavefronts
+constexpr int COUNT_WAVES = COUNT_THREADS / 64;
+
+__global__ __launch_bounds__(COUNT_THREADS) void dispatch_count_kernel(
+    const int32_t* __restrict__ topk_idx, int S, int E, int ebits,
+    int32_t* __restrict__ chunk_hist, int32_t* __restrict__ totals,
+    int32_t* __restrict__ totals_next, int32_t* __restrict__ slot_rank) {
+  __shared__ int32_t wcnt[COUNT_WAVES][MOE_MAX_EXPERTS];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.x;
-  for (int i = tid; i < 4 * MOE_MAX_EXPERTS; i += 256) (&wcnt[0][0])[i] = 0;
-  for (int e = tid; e < E; e += 256) {  // placement, needed only by the last block
-    s_order[e] = seg_order[e];
-    s_dest[e] = dest_rank[e];
+  const int s = b * DISPATCH_CHUNK + tid;
+  int e = -1;
+  if (s < S) {
+    e = topk_idx[s];
+    if ((unsigned)e >= (unsigned)E) e = -1;
   }
+  for (int i = tid; i < COUNT_WAVES * MOE_MAX_EXPERTS; i += COUNT_THREADS) (&wcnt[0][0])[i] = 0;
+  if (b == 0 && tid < MOE_MAX_EXPERTS) totals_next[tid] = 0;
   __syncthreads();
-  constexpr int ROUNDS = DISPATCH_CHUNK / 256;
-  int my_e[ROUNDS], my_rank[ROUNDS];
-  const int wbase = b * DISPATCH_CHUNK + wave * (DISPATCH_CHUNK / 4);
+  const unsigned long long same = match_same(e, ebits);
+  const int in_wave = __popcll(same & ((1ull << lane) - 1ull));
+  if (e >= 0 && in_wave == 0) wcnt[wave][e] = __popcll(same);  // the lowest lane of each value
+  __syncthreads();
+  if (s < S) {
+    int rank = -1;
+    if (e >= 0) {
+      rank = in_wave;
+      for (int w = 0; w < wave; ++w) rank += wcnt[w][e];
+    }
+    slot_rank[s] = rank;  // rank of the slot among its expert's slots of this chunk
+  }
+  if (tid < E) {
+    int n = 0;
 #pragma unroll
-  for (int r = 0; r < ROUNDS; ++r) {
-    const int s = wbase + r * 64 + lane;
-    int e = -1;
-    if (s < S) {
-      e = topk_idx[s];
-      if ((unsigned)e >= (unsigned)E) e = -1;
-    }
-    my_e[r] = e;
-    my_rank[r] = 0;
-  }
-#pragma unroll
-  for (int r = 0; r < ROUNDS; ++r) {
-    const int e = my_e[r];
-    unsigned long long todo = __ballot(e >= 0);
-    while (todo) {
-      const int leader = __ffsll((long long)todo) - 1;
-      const int e0 = __shfl(e, leader, 64);
-      const unsigned long long m = __ballot(e == e0);
-      if (e == e0) {
-        const int before = wcnt[wave][e0];
-        my_rank[r] = before + __popcll(m & ((1ull << lane) - 1ull));
-        if (lane == leader) wcnt[wave][e0] = before + __popcll(m);
-      }
-      todo &= ~m;
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int r = 0; r < ROUNDS; ++r) {
-    const int s = wbase + r * 64 + lane;
-    const int e = my_e[r];
-    if (s < S) {
-      int rank = -1;
-      if (e >= 0) {
-        rank = my_rank[r];
-        for (int w = 0; w < wave; ++w) rank += wcnt[w][e];
-      }
-      slot_rank[s] = rank;  // rank of the slot among its expert's slots of this chunk
-    }
-  }
-  for (int e = tid; e < E; e += 256)
-    chunk_hist[(size_t)b * E + e] = wcnt[0][e] + wcnt[1][e] + wcnt[2][e] + wcnt[3][e];
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const int prev = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    is_last = (prev == n_chunks - 1);
-  }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-
-  // exclusive prefix over chunks, one wavefront per expert at a time
-  for (int e = wave; e < E; e += 4) {
-    int carry = 0;
-    for (int c0 = 0; c0 < n_chunks; c0 += 64) {
-      const int c = c0 + lane;
-      const int v = c < n_chunks ? load_agent(&chunk_hist[(size_t)c * E + e]) : 0;
-      int incl = v;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(incl, off, 64);
-        if (lane >= off) incl += o;
-      }
-      if (c < n_chunks) chunk_hist[(size_t)c * E + e] = carry + incl - v;
-      carry += __shfl(incl, 63, 64);
-    }
-    if (lane == 0) tot[e] = carry;  // total count of expert e
-  }
-  for (int r = tid; r < R; r += 256) rcnt[r] = 0;
-  __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int i = 0; i < E; ++i) {
-      const int e = s_order[i];
-      const int n = tot[e];
-      expert_offsets[e] = run;
-      expert_counts[e] = n;
-      rcnt[s_dest[e]] += n;
-      run += n;
-    }
-    int acc = 0;
-    for (int r = 0; r < R; ++r) {
-      rank_counts[r] = rcnt[r];
-      rank_offsets[r] = acc;
-      acc += rcnt[r];
-    }
-    rank_offsets[R] = acc;
-    __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int w = 0; w < COUNT_WAVES; ++w) n += wcnt[w][tid];
+    chunk_hist[(size_t)b * E + tid] = n;
+    if (n != 0) atomicAdd(&totals[tid], n);
   }
 }
 
@@ -156,19 +91,80 @@ __global__ void dispatch_empty_kernel(int E, int R, int32_t* expert_counts, int3
 template <int K_MAX>
 __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     const uint4* __restrict__ x, const int32_t* __restrict__ topk_idx,
-    const int32_t* __restrict__ chunk_base, const int32_t* __restrict__ expert_offsets, int T,
-    int k, int E, int row_vec, int32_t* __restrict__ slot_to_row,
-    int32_t* __restrict__ row_to_slot, uint4* __restrict__ x_packed) {
-  const int lane = threadIdx.x & 63;
-  const int t = (int)((blockIdx.x * (size_t)blockDim.x + threadIdx.x) >> 6);
+    const int32_t* __restrict__ chunk_hist, const int32_t* __restrict__ totals,
+    const int32_t* __restrict__ seg_order, const int32_t* __restrict__ dest_rank, int T, int k,
+    int E, int R, int row_vec, int32_t* __restrict__ slot_to_row,
+    int32_t* __restrict__ row_to_slot, uint4* __restrict__ x_packed,
+    int32_t* __restrict__ expert_counts, int32_t* __restrict__ expert_offsets,
+    int32_t* __restrict__ rank_counts, int32_t* __restrict__ rank_offsets) {
+  __shared__ int32_t scan[MOE_MAX_EXPERTS + 1];
+  __shared__ int32_t offs[MOE_MAX_EXPERTS];   // expert id -> first row of its segment
+  __shared__ int32_t rcnt[MOE_MAX_RANKS + 1];
+  const int tid = threadIdx.x, lane = tid & 63;
+  // ---- expert offsets: inclusive scan of the totals taken in segment order
+  int ex = 0, mine = 0;
+  if (tid < E) {
+    ex = seg_order[tid];
+    mine = totals[ex];
+  }
+  scan[tid + 1] = mine;
+  if (tid == 0) scan[0] = 0;
+  if (blockIdx.x == 0)
+    for (int r = tid; r <= R; r += 256) rcnt[r] = 0;
+  __syncthreads();
+  for (int off = 1; off < MOE_MAX_EXPERTS; off <<= 1) {
+    int v = 0;
+    if (tid >= off) v = scan[tid + 1 - off];
+    __syncthreads();
+    if (tid >= off) scan[tid + 1] += v;
+    __syncthreads();
+  }
+  if (tid < E) offs[ex] = scan[tid];
+  if (blockIdx.x == 0) {  // the integer outputs of the call
+    if (tid < E) {
+      expert_offsets[ex] = scan[tid];
+      expert_counts[ex] = mine;
+      atomicAdd(&rcnt[dest_rank[ex] + 1], mine);  // integer adds: order does not matter
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int acc = 0;
+      for (int r = 0; r < R; ++r) {
+        rank_counts[r] = rcnt[r + 1];
+        rank_offsets[r] = acc;
+        acc += rcnt[r + 1];
+      }
+      rank_offsets[R] = acc;
+    }
+  }
+  __syncthreads();
+
+  const int t = (int)((blockIdx.x * (size_t)blockDim.x + tid) >> 6);
   if (t >= T) return;
+  // ---- rows of this token's k slots (lane j < k owns slot t*k + j)
+  int e = -1, rk = -1, chunk = 0;
+  if (lane < k) {
+    const int s = t * k + lane;
+    e = topk_idx[s];
+    rk = slot_to_row[s];
+    chunk = s / DISPATCH_CHUNK;
+    if ((unsigned)e >= (unsigned)E || rk < 0) e = -1;
+  }
+  int base = 0;
+  for (int j = 0; j < k; ++j) {  // the whole wavefront sums the earlier chunks of slot j's expert
+    const int ej = __shfl(e, j, 64), cj = __shfl(chunk, j, 64);
+    int part = 0;
+    if (ej >= 0)
+      for (int c = lane; c < cj; c += 64) part += chunk_hist[(size_t)c * E + ej];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
+    if (lane == j) base = part;
+  }
   int row = -1;
   if (lane < k) {
     const int s = t * k + lane;
-    const int e = topk_idx[s];
-    const int rk = slot_to_row[s];
-    if ((unsigned)e < (unsigned)E && rk >= 0) {
-      row = expert_offsets[e] + chunk_base[(size_t)(s / DISPATCH_CHUNK) * E + e] + rk;
+    if (e >= 0) {
+      row = offs[e] + base + rk;
       row_to_slot[row] = s;
     }
     slot_to_row[s] = row;
@@ -202,16 +198,21 @@ int launch_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int T, v
   }
   const int n_chunks = (S + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK;
   if (n_chunks > c->n_chunks_max) return MOE_EINVAL;
-  hipLaunchKernelGGL(dispatch_count_kernel, dim3(n_chunks), dim3(256), 0, s, topk_idx, S, E, R,
-                     n_chunks, c->d_dest_rank, c->d_seg_order, c->d_chunk_hist, c->d_ticket,
-                     slot_to_row, expert_counts, expert_offsets, rank_counts, rank_offsets);
+  int ebits = 0;
+  while ((1 << ebits) < E) ++ebits;
+  int32_t* totals = c->d_totals + (c->dispatch_calls & 1) * MOE_MAX_EXPERTS;
+  int32_t* totals_next = c->d_totals + ((c->dispatch_calls + 1) & 1) * MOE_MAX_EXPERTS;
+  c->dispatch_calls++;
+  hipLaunchKernelGGL(dispatch_count_kernel, dim3(n_chunks), dim3(COUNT_THREADS), 0, s, topk_idx, S,
+                     E, ebits, c->d_chunk_hist, totals, totals_next, slot_to_row);
   const int elem = c->cfg.dtype == MOE_BF16 ? 2 : 4;
   const int row_vec = x != nullptr ? c->cfg.d * elem / 16 : 0;
   const int grid = (T + 3) / 4;
-#define LAUNCH_SCATTER(KM)                                                                      \
+#define LAUNCH_SCATTER(KM)                                                                       \
   hipLaunchKernelGGL((dispatch_scatter_kernel<KM>), dim3(grid), dim3(256), 0, s, (const uint4*)x, \
-                     topk_idx, c->d_chunk_hist, expert_offsets, T, k, E, row_vec, slot_to_row,  \
-                     row_to_slot, (uint4*)x_packed)
+                     topk_idx, c->d_chunk_hist, totals, c->d_seg_order, c->d_dest_rank, T, k, E, \
+                     R, row_vec, slot_to_row, row_to_slot, (uint4*)x_packed, expert_counts,      \
+                     expert_offsets, rank_counts, rank_offsets)
   if (k <= 2) LAUNCH_SCATTER(2);
   else if (k <= 4) LAUNCH_SCATTER(4);
   else if (k <= 8) LAUNCH_SCATTER(8);

@@ -34,8 +34,9 @@ struct moe_ctx {
   int32_t* d_seg_order;   // [E] experts in (dest_rank, id) order
   // dispatch workspace
   int32_t n_chunks_max;   // slot chunks of DISPATCH_CHUNK
-  int32_t* d_chunk_hist;  // [n_chunks_max][E] counts, then exclusive prefix over chunks
-  int32_t* d_ticket;      // [1] arrival counter of the fused histogram+scan
+  int32_t* d_chunk_hist;  // [n_chunks_max][E] per-chunk expert histograms
+  int32_t* d_totals;      // [2][MOE_MAX_EXPERTS] per-expert totals, double-buffered per call
+  uint32_t dispatch_calls;
   float* d_logits;        // [T_max][E] when the caller does not want the logits
   // expert weight pointer tables: device copy [6][MOE_MAX_EXPERTS] (W1, W3, W2, dW1, dW3,
   // dW2), refreshed only when the host tables change
