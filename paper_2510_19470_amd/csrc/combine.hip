@@ -16,27 +16,32 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pa
   const int lane = threadIdx.x & 63;
   const int t = (int)((blockIdx.x * (size_t)blockDim.x + threadIdx.x) >> 6);
   if (t >= Tn) return;
-  int rows[K_MAX];
+  // Rows are wave-uniform.  Missing slots (j >= k, unmapped) read row 0 and are masked out
+  // with a select, so the loads stay unconditional and can all be in flight together.
+  const T* rowp[K_MAX];
   float w[K_MAX];
+  bool ok[K_MAX];
 #pragma unroll
   for (int j = 0; j < K_MAX; ++j) {
     const int r = j < k ? slot_to_row[(size_t)t * k + j] : -1;
-    rows[j] = ((unsigned)r < (unsigned)S) ? r : -1;
+    ok[j] = (unsigned)r < (unsigned)S;
+    rowp[j] = y_packed + (size_t)(ok[j] ? r : 0) * d;
     w[j] = j < k ? topk_w[(size_t)t * k + j] : 0.f;
   }
-#pragma unroll 4
+#pragma unroll(K_MAX <= 4 ? 2 : 1)
   for (int c = lane * N; c < d; c += 64 * N) {
+    uint4 raw[K_MAX];
+#pragma unroll
+    for (int j = 0; j < K_MAX; ++j) raw[j] = Vec16<T>::load_raw(rowp[j] + c);
     float acc[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = 0.f;
 #pragma unroll
     for (int j = 0; j < K_MAX; ++j) {
-      if (rows[j] >= 0) {
-        float v[N];
-        Vec16<T>::load(y_packed + (size_t)rows[j] * d + c, v);
+      float v[N];
+      Vec16<T>::unpack(raw[j], v);
 #pragma unroll
-        for (int i = 0; i < N; ++i) acc[i] = fmaf(w[j], v[i], acc[i]);
-      }
+      for (int i = 0; i < N; ++i) acc[i] = ok[j] ? fmaf(w[j], v[i], acc[i]) : acc[i];
     }
     Vec16<T>::store(out + (size_t)t * d + c, acc);
   }
@@ -55,26 +60,30 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(
   float w[K_MAX], dot[K_MAX];
 #pragma unroll
   for (int j = 0; j < K_MAX; ++j) {
-    const int r = j < k ? slot_to_row[(size_t)t * k + j] : -1;
-    rows[j] = ((unsigned)r < (unsigned)S) ? r : -1;
+    int r = j < k ? slot_to_row[(size_t)t * k + j] : -1;
+    r = ((unsigned)r < (unsigned)S) ? r : -1;
+    rows[j] = __builtin_amdgcn_readfirstlane(r);  // wave-uniform: scalar branches below
     w[j] = j < k ? topk_w[(size_t)t * k + j] : 0.f;
     dot[j] = 0.f;
   }
+#pragma unroll(K_MAX <= 4 ? 2 : 1)
   for (int c = lane * N; c < d; c += 64 * N) {
     float g[N];
     Vec16<T>::load(dout + (size_t)t * d + c, g);
+    uint4 raw[K_MAX];
+#pragma unroll
+    for (int j = 0; j < K_MAX; ++j)  // unconditional (row 0 for a missing slot), masked below
+      raw[j] = Vec16<T>::load_raw(y_packed + (size_t)(rows[j] >= 0 ? rows[j] : 0) * d + c);
 #pragma unroll
     for (int j = 0; j < K_MAX; ++j) {
-      if (rows[j] >= 0) {
-        float v[N], o[N];
-        Vec16<T>::load(y_packed + (size_t)rows[j] * d + c, v);
+      float v[N], o[N];
+      Vec16<T>::unpack(raw[j], v);
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-          dot[j] = fmaf(g[i], v[i], dot[j]);
-          o[i] = w[j] * g[i];
-        }
-        Vec16<T>::store(dy_packed + (size_t)rows[j] * d + c, o);
+      for (int i = 0; i < N; ++i) {
+        dot[j] = rows[j] >= 0 ? fmaf(g[i], v[i], dot[j]) : dot[j];
+        o[i] = w[j] * g[i];
       }
+      if (rows[j] >= 0) Vec16<T>::store(dy_packed + (size_t)rows[j] * d + c, o);
     }
   }
 #pragma unroll
@@ -95,24 +104,28 @@ __global__ __launch_bounds__(256) void dispatch_bwd_kernel(const T* __restrict__
   const int lane = threadIdx.x & 63;
   const int t = (int)((blockIdx.x * (size_t)blockDim.x + threadIdx.x) >> 6);
   if (t >= Tn) return;
-  int rows[K_MAX];
+  const T* rowp[K_MAX];
+  bool ok[K_MAX];
 #pragma unroll
   for (int j = 0; j < K_MAX; ++j) {
     const int r = j < k ? slot_to_row[(size_t)t * k + j] : -1;
-    rows[j] = ((unsigned)r < (unsigned)S) ? r : -1;
+    ok[j] = (unsigned)r < (unsigned)S;
+    rowp[j] = dx_packed + (size_t)(ok[j] ? r : 0) * d;
   }
+#pragma unroll(K_MAX <= 4 ? 2 : 1)
   for (int c = lane * N; c < d; c += 64 * N) {
+    uint4 raw[K_MAX];
+#pragma unroll
+    for (int j = 0; j < K_MAX; ++j) raw[j] = Vec16<T>::load_raw(rowp[j] + c);
     float acc[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = 0.f;
 #pragma unroll
     for (int j = 0; j < K_MAX; ++j) {
-      if (rows[j] >= 0) {
-        float v[N];
-        Vec16<T>::load(dx_packed + (size_t)rows[j] * d + c, v);
+      float v[N];
+      Vec16<T>::unpack(raw[j], v);
 #pragma unroll
-        for (int i = 0; i < N; ++i) acc[i] += v[i];
-      }
+      for (int i = 0; i < N; ++i) acc[i] = ok[j] ? acc[i] + v[i] : acc[i];
     }
     Vec16<T>::store(dx + (size_t)t * d + c, acc);
   }

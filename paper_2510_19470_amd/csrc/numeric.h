@@ -19,6 +19,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// One 16-byte store (a native vector type keeps it a single dwordx4 instruction).
+__device__ __forceinline__ void store16(void* p, uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  u32x4_t q = {a, b, c, d};
+  *reinterpret_cast<u32x4_t*>(p) = q;
+}
+
 // A 16-byte vector of the storage type seen as floats.
 template <typename T>
 struct Vec16;
@@ -26,18 +34,37 @@ struct Vec16;
 template <>
 struct Vec16<float> {
   static constexpr int N = 4;
+  __device__ static __forceinline__ uint4 load_raw(const void* p) {
+    return *reinterpret_cast<const uint4*>(p);
+  }
+  __device__ static __forceinline__ void unpack(const uint4& q, float (&v)[4]) {
+    v[0] = __uint_as_float(q.x); v[1] = __uint_as_float(q.y);
+    v[2] = __uint_as_float(q.z); v[3] = __uint_as_float(q.w);
+  }
   __device__ static __forceinline__ void load(const void* p, float (&v)[4]) {
     const float4 q = *reinterpret_cast<const float4*>(p);
     v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
   }
   __device__ static __forceinline__ void store(void* p, const float (&v)[4]) {
-    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    store16(p, __float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]),
+            __float_as_uint(v[3]));
   }
 };
 
 template <>
 struct Vec16<uint16_t> {
   static constexpr int N = 8;
+  __device__ static __forceinline__ uint4 load_raw(const void* p) {
+    return *reinterpret_cast<const uint4*>(p);
+  }
+  __device__ static __forceinline__ void unpack(const uint4& q, float (&v)[8]) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(w[i] << 16);
+      v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
   __device__ static __forceinline__ void load(const void* p, float (&v)[8]) {
     const uint4 q = *reinterpret_cast<const uint4*>(p);
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
@@ -48,12 +75,8 @@ struct Vec16<uint16_t> {
     }
   }
   __device__ static __forceinline__ void store(void* p, const float (&v)[8]) {
-    uint4 q;
-    q.x = pack_bf16x2(v[0], v[1]);
-    q.y = pack_bf16x2(v[2], v[3]);
-    q.z = pack_bf16x2(v[4], v[5]);
-    q.w = pack_bf16x2(v[6], v[7]);
-    *reinterpret_cast<uint4*>(p) = q;
+    store16(p, pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+            pack_bf16x2(v[6], v[7]));
   }
 };
 
