@@ -175,6 +175,46 @@ int moe_expert_ffn_bwd(moe_ctx* ctx, const void* dy_packed, const void* x_packed
 int moe_dispatch_bwd(moe_ctx* ctx, const void* dx_packed, const int32_t* slot_to_row, int32_t T,
                      void* dx, void* stream);
 
+/* ---- Placement planning (host only; no GPU is touched) --------------------------------
+ * The multilevel description of Sec. 4.1: L levels, SF[l] = workers a level-(l-1) worker
+ * expands into (SF[0] = workers at level 0), S_ED[l] = expert-domain size at level l
+ * (1 <= S_ED[l], S_ED[l] divides SF[l]); G = prod SF[l] GPUs, global rank as in PyTorch.
+ * All arrays are [host]. */
+#define MOE_PLAN_MAX_LEVELS 8
+#define MOE_COMM_NONE 0
+#define MOE_COMM_AG 1
+#define MOE_COMM_A2A 2
+#define MOE_PLAN_CASE_MIX 1     /* 2D - G*P_E <  0: both A2A and AG (Case 1 + 2.1) */
+#define MOE_PLAN_CASE_AG_ONLY 2 /* 2D - G*P_E >= 0: p = 0 (Case 2.2)               */
+
+/* Location renumbering (Sec. 4.1): loc[i] = floor(rank / prod_{j>i} SF[j]) mod SF[i]. */
+int moe_plan_location(int32_t rank, int32_t L, const int32_t* SF, int32_t* loc /*[L]*/);
+
+/* Algorithm 1 "Communication Topology Construction" for the pair (m, n) at one level:
+ * MOE_COMM_AG inside a domain (different offsets), MOE_COMM_A2A across domains (same
+ * offset), else MOE_COMM_NONE; only pairs whose other coordinates agree communicate. */
+int moe_plan_comm_type(int32_t m, int32_t n, int32_t level, int32_t L, const int32_t* SF,
+                       const int32_t* S_ED, int32_t* type_out);
+
+/* Communication frequency (Sec. 5.6, Table 7): number of GPU-to-GPU communications of
+ * each type over all ordered pairs and levels.  G <= 4096. */
+int moe_plan_comm_frequency(int32_t L, const int32_t* SF, const int32_t* S_ED, int64_t* n_ag,
+                            int64_t* n_a2a);
+
+/* The map moe_set_placement takes, for E experts spread evenly over the G GPUs (expert e at
+ * home rank e / (E/G)): dest[e] = local_rank when the home is reachable by all-gather at
+ * every level (the expert is resident), else the rank of the home's domain with the local
+ * offsets (domain rule).  dest [E] out; E must be a multiple of G. */
+int moe_plan_expert_dest_rank(int32_t local_rank, int32_t E, int32_t L, const int32_t* SF,
+                              const int32_t* S_ED, int32_t* dest);
+
+/* Stream model (Sec. 3): D = data bytes leaving a GPU per A2A, P_E = expert bytes per GPU,
+ * B = bandwidth (bytes/s), lat_pe = pre-expert compute time (s), G GPUs.  *p_star = the
+ * closed-form optimal A2A proportion (Sec. 3.4), *case_id = MOE_PLAN_CASE_*, *best_S = the
+ * divisor S of G whose exact proportion (G-S)/(G-1) has the lowest modelled latency. */
+int moe_plan_model(double D, double P_E, double B, double lat_pe, int32_t G, double* p_star,
+                   int32_t* case_id, int32_t* best_S);
+
 /* Measurement aid.  moe_profile_ffn(ctx, n_calls) makes the next n_calls calls of
  * moe_expert_ffn record HIP events on their stream around each internal launch
  * (n_calls = 0 switches it off and frees the events; creates events, so not for use

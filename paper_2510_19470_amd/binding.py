@@ -63,6 +63,17 @@ def load_library(build_if_missing: bool = True):
     lib.moe_combine_bwd.argtypes = [P, P, P, P, P, c_int32, P, P, P]
     lib.moe_expert_ffn_bwd.argtypes = [P, P, P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P]
     lib.moe_dispatch_bwd.argtypes = [P, P, P, c_int32, P, P]
+    I32P = POINTER(c_int32)
+    lib.moe_plan_location.argtypes = [c_int32, c_int32, I32P, I32P]
+    lib.moe_plan_comm_type.argtypes = [c_int32, c_int32, c_int32, c_int32, I32P, I32P, I32P]
+    lib.moe_plan_comm_frequency.argtypes = [c_int32, I32P, I32P, POINTER(ctypes.c_int64),
+                                            POINTER(ctypes.c_int64)]
+    lib.moe_plan_expert_dest_rank.argtypes = [c_int32, c_int32, c_int32, I32P, I32P, I32P]
+    lib.moe_plan_model.argtypes = [ctypes.c_double] * 4 + [c_int32, POINTER(ctypes.c_double), I32P,
+                                                           I32P]
+    for name in ("moe_plan_location", "moe_plan_comm_type", "moe_plan_comm_frequency",
+                 "moe_plan_expert_dest_rank", "moe_plan_model"):
+        getattr(lib, name).restype = c_int
     lib.moe_profile_ffn.argtypes = [P, c_int32]
     lib.moe_profile_ffn_read.argtypes = [P, POINTER(c_float), POINTER(c_int32)]
     for name in ("moe_create", "moe_destroy", "moe_set_placement", "moe_set_ffn_path", "moe_route",
@@ -282,3 +293,50 @@ def moe_profile_ffn_read(ctx):
     _check(load_library().moe_profile_ffn_read(ctx.handle, ms, ctypes.byref(n)),
            "moe_profile_ffn_read")
     return [float(v) for v in ms], int(n.value)
+
+
+# ------------------------------------------------------------------ planning (host only)
+MOE_COMM_NONE, MOE_COMM_AG, MOE_COMM_A2A = 0, 1, 2
+MOE_PLAN_CASE_MIX, MOE_PLAN_CASE_AG_ONLY = 1, 2
+
+
+def _i32(vals):
+    return (c_int32 * len(vals))(*[int(v) for v in vals])
+
+
+def moe_plan_location(rank: int, SF: Sequence[int]) -> List[int]:
+    out = (c_int32 * len(SF))()
+    _check(load_library().moe_plan_location(rank, len(SF), _i32(SF), out), "moe_plan_location")
+    return list(out)
+
+
+def moe_plan_comm_type(m: int, n: int, level: int, SF: Sequence[int], S_ED: Sequence[int]) -> int:
+    t = c_int32(0)
+    _check(load_library().moe_plan_comm_type(m, n, level, len(SF), _i32(SF), _i32(S_ED),
+                                             ctypes.byref(t)), "moe_plan_comm_type")
+    return int(t.value)
+
+
+def moe_plan_comm_frequency(SF: Sequence[int], S_ED: Sequence[int]):
+    """Returns (n_AG, n_A2A)."""
+    ag, a2a = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(load_library().moe_plan_comm_frequency(len(SF), _i32(SF), _i32(S_ED), ctypes.byref(ag),
+                                                  ctypes.byref(a2a)), "moe_plan_comm_frequency")
+    return int(ag.value), int(a2a.value)
+
+
+def moe_plan_expert_dest_rank(local_rank: int, E: int, SF: Sequence[int],
+                              S_ED: Sequence[int]) -> List[int]:
+    out = (c_int32 * E)()
+    _check(load_library().moe_plan_expert_dest_rank(local_rank, E, len(SF), _i32(SF), _i32(S_ED),
+                                                    out), "moe_plan_expert_dest_rank")
+    return list(out)
+
+
+def moe_plan_model(D: float, P_E: float, B: float, lat_pe: float, G: int):
+    """Returns (p_star, case_id, best_S)."""
+    p = ctypes.c_double(0.0)
+    case, best = c_int32(0), c_int32(0)
+    _check(load_library().moe_plan_model(D, P_E, B, lat_pe, G, ctypes.byref(p), ctypes.byref(case),
+                                         ctypes.byref(best)), "moe_plan_model")
+    return float(p.value), int(case.value), int(best.value)

@@ -13,7 +13,7 @@ BUILD_DIR = os.path.join(ROOT, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libmoe_hip.so")
 
 SOURCES = ["moe_api.hip", "route.hip", "dispatch.hip", "combine.hip", "gemm_generic.hip",
-           "ffn_mfma.hip"]
+           "ffn_mfma.hip", "plan.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
@@ -35,7 +35,7 @@ def build(verbose: bool = True, jobs: int = 6) -> str:
     hipcc = _hipcc()
 
     def compile_one(src: str) -> str:
-        obj = os.path.join(BUILD_DIR, src.replace(".hip", ".o"))
+        obj = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".o")
         cmd = [hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
