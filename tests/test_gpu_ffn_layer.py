@@ -244,3 +244,72 @@ def test_backward_matches_oracle(name, T, path, shape):
     bad = {k_: v for k_, v in errs.items() if not v <= tol}
     assert not bad, bad
     lay.close()
+
+
+def test_train_config_full_size_backward_sampled():
+    """The training configuration at full size with resident experts only (the launch shape
+    bench.py times): sampled rows of dx_packed / dx and sampled rows of the weight gradients
+    of one expert against the oracle (every quantity is row-local or one expert's sum)."""
+    from gpu_common import TOL, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
+    cfg = wl.CONFIGS["train"]
+    say(f"[bwd] train full size T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} f={cfg.f}")
+    inp = wl.make_inputs(cfg, experts="resident")
+    lay = layer_from_inputs(inp)
+    x = to_device(inp.x, cfg.dtype)
+    fwd = lay.forward(x, save=True)
+    bwd = lay.backward(fwd, to_device(inp.dOut, cfg.dtype))
+    torch.cuda.synchronize()
+    tol = TOL["bf16"]
+    idx = i32(fwd["topk_idx"])
+    w = fwd["topk_w"].cpu().numpy().astype(np.float64)
+    cnt, off, _, roff, s2r, r2s = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
+    xv = wl.stored_to_f32(inp.x, cfg.dtype).astype(np.float64)
+    dov = wl.stored_to_f32(inp.dOut, cfg.dtype).astype(np.float64)
+    res = wl.resident_experts(cfg)
+    dxp_g = to_host_f32(bwd["dx_packed"])
+    worst = 0.0
+    for e in res:
+        n = int(cnt[e])
+        rows = np.array(sorted({int(off[e]), int(off[e]) + n // 3, int(off[e]) + n - 1}))
+        slots = r2s[rows]
+        W1, W3, W2 = (vals(a[e], cfg.dtype) for a in (inp.W1, inp.W3, inp.W2))
+        xe = xv[slots // cfg.k]
+        g, u = xe @ W1.T, xe @ W3.T
+        sg = 1.0 / (1.0 + np.exp(-g))
+        dy = w.reshape(-1)[slots][:, None] * dov[slots // cfg.k]
+        dh = dy @ W2
+        dxp = (dh * u * sg * (1 + g * (1 - sg))) @ W1 + (dh * g * sg) @ W3
+        err = nerr(dxp_g[rows], dxp)
+        worst = max(worst, err)
+        assert err <= tol, (e, err)
+    say(f"    dx_packed sampled rows: worst normalised error {worst:.3e}")
+    # weight gradients of one resident expert: a few rows of each matrix, summed over all
+    # of the expert's tokens
+    e = res[-1]
+    n, lo = int(cnt[e]), int(off[e])
+    slots = r2s[lo:lo + n]
+    W1, W3, W2 = (vals(a[e], cfg.dtype) for a in (inp.W1, inp.W3, inp.W2))
+    xe = xv[slots // cfg.k]
+    g, u = xe @ W1.T, xe @ W3.T
+    sg = 1.0 / (1.0 + np.exp(-g))
+    h = g * sg * u
+    dy = w.reshape(-1)[slots][:, None] * dov[slots // cfg.k]
+    dh = dy @ W2
+    dg, du = dh * u * sg * (1 + g * (1 - sg)), dh * g * sg
+    pick = [0, 777, cfg.d - 1]
+    dW2 = bwd["dW2"][e].cpu().numpy().astype(np.float64)
+    dW1 = bwd["dW1"][e].cpu().numpy().astype(np.float64)
+    dW3 = bwd["dW3"][e].cpu().numpy().astype(np.float64)
+    scale = np.max(np.abs(dy.T[pick] @ h))
+    errs = dict(dW2=np.max(np.abs(dW2[pick] - dy.T[pick] @ h)) / scale,
+                dW1=np.max(np.abs(dW1[pick] - dg.T[pick] @ xe)) / np.max(np.abs(dg.T[pick] @ xe)),
+                dW3=np.max(np.abs(dW3[pick] - du.T[pick] @ xe)) / np.max(np.abs(du.T[pick] @ xe)))
+    say("    " + ", ".join(f"{k_}={v:.2e}" for k_, v in errs.items()))
+    assert all(v <= tol for v in errs.values()), errs
+    # dx of tokens whose experts are all resident: the sum of their k dx_packed rows
+    tok = [t for t in range(cfg.T) if all(int(a) in set(res) for a in idx[t])][:3]
+    if tok:
+        want = np.stack([sum(dxp_g[s2r[t * cfg.k + j]].astype(np.float64) for j in range(cfg.k))
+                         for t in tok])
+        assert nerr(to_host_f32(bwd["dx"])[tok], want) <= 2.0 ** -7
+    lay.close()
