@@ -15,10 +15,17 @@
 // same columns and applies silu(g)*u in registers.  The weight rows are the MFMA "A"
 // operand and the token rows the "B" operand: a lane then holds 4 consecutive output
 // columns of one token row and stores them as one 8-byte write.
-// LDS: 2 stages x (32 KB tokens + 32 KB weights) = 128 KB, 16-byte chunks XOR-swizzled by
-// row so that the 16-byte fragment reads of 16 consecutive rows fall on distinct banks.
-// Global loads of stage t+1 are issued before the MFMAs of stage t and written to LDS
-// after them: one barrier per k-step.
+// LDS: 2 stages x (32 KB tokens + 32 KB weights) = 128 KB, filled by asynchronous
+// global->LDS copies (no registers in between); 16-byte chunks are XOR-swizzled by row so
+// that the 16-byte fragment reads of 16 consecutive rows fall on distinct banks.
+// Main loop ("ping-pong"): the wavefronts of the upper 128 token rows and those of the
+// lower 128 rows alternate between a memory cluster (fragment reads of one 32-row token
+// block, two copy instructions) and a compute cluster (8 MFMAs), the second group one
+// cluster behind the first, so every SIMD always has one wavefront on the matrix core
+// and one on memory.  A token block is refilled as soon as its group has read it, the
+// weight rows as soon as both groups have read them (first cluster of a step), each with
+// the data of two steps ahead: copies are spread evenly over the step and have more
+// than one step to land.
 // Tile order: tiles of one expert that share a weight panel (same column block) are
 // consecutive, and the block index is remapped so that each of the 8 XCDs (private L2)
 // works on a contiguous range of that order.
@@ -128,66 +135,13 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// One k-step of the wavefront tile: 4 k-slices of 16, each 6 fragment reads + 8 MFMAs.
-// The reads of slice kk+1 are issued before the MFMAs of slice kk (two fragment sets in
-// registers), and the wavefront raises its priority while it feeds the matrix core so
-// that the other wavefront of the SIMD does its LDS reads in the shadow.
-__device__ __forceinline__ void mma_stage(f32x16 (&acc)[2][4], const uint4* __restrict__ As,
-                                          const uint4* __restrict__ Bs, const int (&fr_a)[4],
-                                          const int (&fr_b)[2], int fr_half, int fr_swz) {
-  bf16x8 xa[2][4], wb[2][2];
-  {
-    const int ch = fr_half ^ fr_swz;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) xa[0][i] = __builtin_bit_cast(bf16x8, As[fr_a[i] + ch]);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) wb[0][j] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ch]);
-  }
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    if (kk < 3) {
-      const int ch = ((kk + 1) * 2 + fr_half) ^ fr_swz;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        xa[(kk + 1) & 1][i] = __builtin_bit_cast(bf16x8, As[fr_a[i] + ch]);
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        wb[(kk + 1) & 1][j] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ch]);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[kk & 1][j], xa[kk & 1][i],
-                                                            acc[j][i], 0, 0, 0);
-    __builtin_amdgcn_s_setprio(0);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-}
-
-// Asynchronous global -> LDS copy of one k-step (no registers in between): each wavefront
-// fills 4 blocks of 8 rows x 128 B per operand; a lane's 16 bytes land at lane*16 inside
-// the block, so the swizzle is applied by choosing which global chunk the lane fetches.
-__device__ __forceinline__ void issue_stage(const uint4* const (&a_src)[4],
-                                            const uint4* const (&b_src)[4], int kofs,
-                                            uint4* As, uint4* Bs, int wave) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + kofs), (lptr_t)(As + (wave * 4 + i) * 64),
-                                     16, 0, 0);
-    __builtin_amdgcn_global_load_lds((gptr_t)(b_src[i] + kofs), (lptr_t)(Bs + (wave * 4 + i) * 64),
-                                     16, 0, 0);
-  }
-  // keep the copies at the top of the step: the scheduler would otherwise sink them
-  // below the MFMAs and expose their whole latency at the barrier
-  __builtin_amdgcn_sched_barrier(0);
-}
-
-__device__ __forceinline__ void wait_stage_and_sync() {
-  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): my copies landed, my reads are done
-  __syncthreads();
+// Asynchronous 16 bytes per lane global -> LDS: the wavefront's 1 KB lands at lds_addr
+// (wave-uniform byte address, via M0) + lane * 16.  Written as assembly so that the
+// compiler does not serialise later LDS reads behind it; completion is tracked by hand
+// (vmcnt) in the main loop.
+__device__ __forceinline__ void dma16(const uint4* src, uint32_t lds_addr) {
+  const uint32_t d = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(d) : "memory");
 }
 
 enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_WGRAD = 3 };
@@ -221,16 +175,12 @@ struct GemmArgs {
 // MODE_WGRAD: fp32 dW = AT BT^T, both operands transposed activations (contraction = rows)
 template <int MODE>
 __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
-  // two stages, each 256 token rows + 256 weight rows of 64 bf16 (separate arrays so that
-  // reads of one stage are known not to alias the copy in flight into the other)
-  __shared__ uint4 ldsA0[STAGE_VEC];
-  __shared__ uint4 ldsB0[STAGE_VEC];
-  __shared__ uint4 ldsA1[STAGE_VEC];
-  __shared__ uint4 ldsB1[STAGE_VEC];
+  // stage s: token rows at (2s) * STAGE_VEC, weight rows at (2s+1) * STAGE_VEC
+  __shared__ uint4 lds[4 * STAGE_VEC];
   constexpr bool GATED = MODE == MODE_UP;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = __builtin_amdgcn_readfirstlane(wave >> 2), wn = wave & 3;
   MTile tl;
   int nblk, KT;
   const uint4* a_src[4];
@@ -252,10 +202,12 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
     tl.rows = BM;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row = (wave * 4 + i) * 8 + (lane >> 3);
-      const int ch = (lane & 7) ^ swz(row);
-      a_src[i] = (const uint4*)(p.A + (size_t)(p.a_row0 + mblk * 256 + row) * p.lda + k0) + ch;
-      b_src[i] = (const uint4*)(p.BT + (size_t)(p.b_row0 + nblk * 256 + row) * p.lda + k0) + ch;
+      const int ra = (16 * wm + 4 * i + wn) * 8 + (lane >> 3);
+      const int rb = (8 * i + wave) * 8 + (lane >> 3);
+      a_src[i] = (const uint4*)(p.A + (size_t)(p.a_row0 + mblk * 256 + ra) * p.lda + k0) +
+                 ((lane & 7) ^ swz(ra));
+      b_src[i] = (const uint4*)(p.BT + (size_t)(p.b_row0 + nblk * 256 + rb) * p.lda + k0) +
+                 ((lane & 7) ^ swz(rb));
     }
   } else {
     const int total = p.sched->n_mtiles * p.n_tiles_n;
@@ -267,22 +219,24 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
     tl = p.mt[ent >> 12];
     nblk = ent & 0xfff;
     KT = p.K / BK;
-    // global -> LDS assignment: lane (lane>>3, lane&7) of block b = wave*4+i fills LDS row
-    // 8b + (lane>>3), chunk slot (lane&7), which must hold global chunk slot ^ swz(row)
+    // global -> LDS assignment: one copy instruction fills 8 rows (lane>>3) x 8 chunk slots
+    // (lane&7); slot c of row r must hold global chunk c ^ swz(r).  Token rows: copy i of
+    // a wavefront fills 8 rows of block i of its own group's half; weight rows: copy i
+    // fills row block 8i + wave.
     const uint16_t* B0 = (const uint16_t*)p.Bt0[tl.expert];
     const uint16_t* B1 = GATED ? (const uint16_t*)p.Bt1[tl.expert] : nullptr;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row = (wave * 4 + i) * 8 + (lane >> 3);
-      const int ch = (lane & 7) ^ swz(row);
-      const int arow = min(row, tl.rows - 1);
-      a_src[i] = (const uint4*)(p.A + (size_t)(tl.row0 + arow) * p.lda) + ch;
+      const int ra = (16 * wm + 4 * i + wn) * 8 + (lane >> 3);
+      const int rb = (8 * i + wave) * 8 + (lane >> 3);
+      const int arow = min(ra, tl.rows - 1);
+      a_src[i] = (const uint4*)(p.A + (size_t)(tl.row0 + arow) * p.lda) + ((lane & 7) ^ swz(ra));
       const uint16_t* bp;
       if (GATED)
-        bp = (row < 128 ? B0 : B1) + (size_t)(nblk * 128 + (row & 127)) * p.K;
+        bp = (rb < 128 ? B0 : B1) + (size_t)(nblk * 128 + (rb & 127)) * p.K;
       else
-        bp = B0 + (size_t)(nblk * 256 + row) * p.K;
-      b_src[i] = (const uint4*)bp + ch;
+        bp = B0 + (size_t)(nblk * 256 + rb) * p.K;
+      b_src[i] = (const uint4*)bp + ((lane & 7) ^ swz(rb));
     }
   }
 
@@ -303,22 +257,77 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
-  // K is a multiple of 128, so the number of k-steps is even and the loop can alternate
-  // the two stages without a conditional exit (keeps the accumulators in registers).
+  // K is a multiple of 128: the number of k-steps is even (the loop body covers both stages
+  // with compile-time offsets).  KT == 0 (weight gradient of an expert without rows) skips
+  // everything, for the whole block alike.
   if (KT > 0) {
-    issue_stage(a_src, b_src, 0, ldsA0, ldsB0, wave);
-    wait_stage_and_sync();
-  }
-  for (int kt = 0; kt < KT; kt += 2) {
-    issue_stage(a_src, b_src, (kt + 1) * 8, ldsA1, ldsB1, wave);
-    mma_stage(acc, ldsA0, ldsB0, fr_a, fr_b, fr_half, fr_swz);
-    wait_stage_and_sync();
-    // the copy after the last step re-reads that step into the idle stage: in bounds,
-    // unconditional, and nobody reads it
-    const int kn = kt + 2 < KT ? kt + 2 : kt;
-    issue_stage(a_src, b_src, kn * 8, ldsA0, ldsB0, wave);
-    mma_stage(acc, ldsA1, ldsB1, fr_a, fr_b, fr_half, fr_swz);
-    wait_stage_and_sync();
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
+    const uint32_t a_dst = lds_base + (16 * wm + wn) * 1024;  // + stage * 65536 + block * 4096
+    const uint32_t b_dst = lds_base + 32768 + wave * 1024;    // + stage * 65536 + block * 8192
+    // both stages in full, then the second group falls one cluster behind
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        dma16(a_src[i] + st * 8, a_dst + st * 65536 + i * 4096);
+        dma16(b_src[i] + st * 8, b_dst + st * 65536 + i * 8192);
+      }
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if (wm == 1) asm volatile("s_barrier" ::: "memory");
+    bf16x8 wb[2][4], xa[4];
+    for (int kt = 0; kt < KT; kt += 2) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        const int k = kt + s;
+        const uint4* As = lds + (2 * s) * STAGE_VEC;
+        const uint4* Bs = lds + (2 * s + 1) * STAGE_VEC;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          // ---- memory cluster: fragments of token block i (and, first, of all weight rows)
+          if (i == 0) {
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+              for (int j = 0; j < 2; ++j)
+                wb[j][kk] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ((kk * 2 + fr_half) ^ fr_swz)]);
+          }
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk)
+            xa[kk] = __builtin_bit_cast(bf16x8, As[fr_a[i] + ((kk * 2 + fr_half) ^ fr_swz)]);
+          {
+            // refill what was read one cluster ago with the data of its next use: token
+            // block i-1 and weight row blocks 8(i-1)+wave of this stage with step k+2; at
+            // i == 0 block 3 of the other stage with step k+1.  Past the end the last step
+            // is fetched again (in bounds, never read): the copy count per cluster stays
+            // fixed, which the vmcnt arithmetic below relies on.
+            const int blk = (i + 3) & 3;
+            const int st = i == 0 ? (s ^ 1) : s;
+            int kd = i == 0 ? k + 1 : k + 2;
+            kd = kd < KT ? kd : KT - 1;
+            dma16(a_src[blk] + kd * 8, a_dst + st * 65536 + blk * 4096);
+            dma16(b_src[blk] + kd * 8, b_dst + st * 65536 + blk * 8192);
+          }
+          // My fragment reads are done (the rows may be refilled after the next barrier)
+          // and all but my last 6 copies have landed: the data read in cluster n was
+          // copied in clusters <= n-4, and every wavefront passes this point in cluster
+          // n-1 before anybody reads in cluster n.
+          asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+          // ---- compute cluster
+          __builtin_amdgcn_sched_barrier(0);
+          __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+              acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[j][kk], xa[kk], acc[j][i], 0, 0, 0);
+          __builtin_amdgcn_s_setprio(0);
+          __builtin_amdgcn_sched_barrier(0);
+          asm volatile("s_barrier" ::: "memory");
+        }
+      }
+    }
+    if (wm == 0) asm volatile("s_barrier" ::: "memory");  // as many barriers as the other group
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no copy in flight into LDS at exit
   }
 
   // ---- epilogue: lane holds, per 32x32 accumulator, token row (lane&31) and the weight
@@ -384,7 +393,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
               const float gv = __uint_as_float((r & 1) ? (gw[r >> 1] & 0xffff0000u) : (gw[r >> 1] << 16));
               const float uv = __uint_as_float((r & 1) ? (uw[r >> 1] & 0xffff0000u) : (uw[r >> 1] << 16));
               const float dh = acc[j][i][g * 4 + r];
-              const float sg = 1.f / (1.f + __expf(-gv));
+              const float sg = sigmoid_f(gv);
               dg[r] = dh * uv * sg * (1.f + gv * (1.f - sg));
               du[r] = dh * gv * sg;
               hh[r] = gv * sg * uv;
