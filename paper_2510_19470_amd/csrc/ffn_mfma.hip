@@ -49,8 +49,9 @@ __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row & 
 __global__ __launch_bounds__(256) void mfma_sched_kernel(
     const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets,
     const void* const* __restrict__ present, int E, int S, int max_mtiles, int nt_up, int nt_down,
-    TileSched* __restrict__ sched, MTile* __restrict__ mt, uint32_t* __restrict__ order_up,
-    uint32_t* __restrict__ order_down, int32_t* __restrict__ koff) {
+    int n_cu, int kt_down, TileSched* __restrict__ sched, MTile* __restrict__ mt,
+    uint32_t* __restrict__ order_up, uint32_t* __restrict__ order_down,
+    int32_t* __restrict__ koff) {
   __shared__ int32_t start[MOE_MAX_EXPERTS + 1];
   __shared__ int bad;
   const int tid = threadIdx.x;
@@ -76,7 +77,21 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
     __syncthreads();
   }
   const int total_m = (bad || start[E] > max_mtiles) ? 0 : start[E];
-  if (blockIdx.x == 0 && tid == 0) sched->n_mtiles = total_m;
+  if (blockIdx.x == 0 && tid == 0) {
+    sched->n_mtiles = total_m;
+    // Down GEMM: when the last round of tiles fills at most half of the compute units, its
+    // tiles are cut along the contraction into `split` parts (2, 4 or 8; every part an even
+    // number >= 8 of k-steps; all parts together still one round), summed afterwards.
+    const int total = total_m * nt_down;
+    const int tail = total % n_cu;
+    int split = 1;
+    while (tail > 0 && split < 8 && tail * (split * 2) <= n_cu && kt_down % (4 * split) == 0 &&
+           kt_down / (2 * split) >= 8)
+      split *= 2;
+    sched->down_split = split;
+    sched->down_split_tiles = split > 1 ? tail : 0;
+    sched->down_full = split > 1 ? total - tail : total;
+  }
   // Backward only: column offset of every expert in the transposed activation buffers,
   // each expert's rows padded to a multiple of 128 (koff[e+1]-koff[e] = padded count).
   if (koff != nullptr && blockIdx.x == 0) {
@@ -159,6 +174,7 @@ struct GemmArgs {
   int N;                   // elements per output row
   uint16_t* C;             // UP: H; DOWN: Y / dX; DH: [dG|dU] with row pitch 2N
   uint16_t* C2;            // DH: H
+  float* split_ws;         // DOWN: fp32 partial tiles of the K-split tail
   uint16_t* Gs;            // UP: optional save (out); DH: saved G (in)
   uint16_t* Us;
   // MODE_WGRAD: dW[e][Mo,No] = AT_e * BT_e^T over the expert's padded row range
@@ -183,6 +199,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   const int wm = __builtin_amdgcn_readfirstlane(wave >> 2), wn = wave & 3;
   MTile tl;
   int nblk, KT;
+  int split = 1, part = 0, unit = 0;  // K-split tail of the down GEMM
   const uint4* a_src[4];
   const uint4* b_src[4];
   float* dW = nullptr;
@@ -210,15 +227,35 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
                  ((lane & 7) ^ swz(rb));
     }
   } else {
-    const int total = p.sched->n_mtiles * p.n_tiles_n;
-    const int per_xcd = (total + 7) >> 3;
-    const int slot = blockIdx.x >> 3;
-    const int L = (blockIdx.x & 7) * per_xcd + slot;
-    if (slot >= per_xcd || L >= total) return;
+    // block -> work unit: XCD x (= blockIdx & 7, the hardware deals blocks round-robin to
+    // the XCDs) walks a contiguous range of the tile order; the K-split units of the tail
+    // are spread over the XCDs in the same way and come last
+    int L;
+    {
+      const int total = p.sched->n_mtiles * p.n_tiles_n;
+      const int n_full = MODE == MODE_DOWN ? p.sched->down_full : total;
+      const int per_xcd = (n_full + 7) >> 3;
+      const int slot = blockIdx.x >> 3;
+      if (slot < per_xcd) {
+        L = (blockIdx.x & 7) * per_xcd + slot;
+        if (L >= n_full) return;
+      } else {
+        if (MODE != MODE_DOWN) return;
+        split = p.sched->down_split;
+        const int n_units = p.sched->down_split_tiles * split;
+        const int per_xcd_s = (n_units + 7) >> 3;
+        const int j = slot - per_xcd;
+        unit = (blockIdx.x & 7) * per_xcd_s + j;
+        if (j >= per_xcd_s || unit >= n_units) return;
+        L = n_full + unit / split;
+        part = unit % split;
+      }
+    }
     const uint32_t ent = p.order[L];
     tl = p.mt[ent >> 12];
     nblk = ent & 0xfff;
-    KT = p.K / BK;
+    KT = p.K / BK / split;
+    const int kbeg = part * KT * 8;  // first 16-byte chunk of this part's k-range
     // global -> LDS assignment: one copy instruction fills 8 rows (lane>>3) x 8 chunk slots
     // (lane&7); slot c of row r must hold global chunk c ^ swz(r).  Token rows: copy i of
     // a wavefront fills 8 rows of block i of its own group's half; weight rows: copy i
@@ -230,13 +267,13 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
       const int ra = (16 * wm + 4 * i + wn) * 8 + (lane >> 3);
       const int rb = (8 * i + wave) * 8 + (lane >> 3);
       const int arow = min(ra, tl.rows - 1);
-      a_src[i] = (const uint4*)(p.A + (size_t)(tl.row0 + arow) * p.lda) + ((lane & 7) ^ swz(ra));
+      a_src[i] = (const uint4*)(p.A + (size_t)(tl.row0 + arow) * p.lda) + kbeg + ((lane & 7) ^ swz(ra));
       const uint16_t* bp;
       if (GATED)
         bp = (rb < 128 ? B0 : B1) + (size_t)(nblk * 128 + (rb & 127)) * p.K;
       else
         bp = B0 + (size_t)(nblk * 256 + rb) * p.K;
-      b_src[i] = (const uint4*)bp + ((lane & 7) ^ swz(rb));
+      b_src[i] = (const uint4*)bp + kbeg + ((lane & 7) ^ swz(rb));
     }
   }
 
@@ -330,6 +367,20 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no copy in flight into LDS at exit
   }
 
+  if (MODE == MODE_DOWN && split > 1) {
+    // partial sums of one part, in accumulator order: [unit][j][i][quad][thread] float4
+    float4* ws = reinterpret_cast<float4*>(p.split_ws) + (size_t)unit * (32 * NT) + tid;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          ws[((j * 4 + i) * 4 + q) * NT] = make_float4(acc[j][i][q * 4], acc[j][i][q * 4 + 1],
+                                                       acc[j][i][q * 4 + 2], acc[j][i][q * 4 + 3]);
+    return;
+  }
+
   // ---- epilogue: lane holds, per 32x32 accumulator, token row (lane&31) and the weight
   // rows 8*g + 4*(lane>>5) + {0..3}, g = 0..3
 #pragma unroll
@@ -411,6 +462,44 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   }
 }
 
+// Sums the parts of every K-split tile of the down GEMM in a fixed order (part 0, 1, ...:
+// deterministic) and stores the tile like the GEMM's own epilogue.  One block per split
+// tile; thread and accumulator indices mean what they mean in ffn_mfma_kernel.
+__global__ __launch_bounds__(NT) void ffn_split_reduce_kernel(const GemmArgs p) {
+  const int n_tiles = p.sched->down_split_tiles;
+  if ((int)blockIdx.x >= n_tiles) return;
+  const int split = p.sched->down_split;
+  const uint32_t ent = p.order[p.sched->down_full + blockIdx.x];
+  const MTile tl = p.mt[ent >> 12];
+  const int nblk = ent & 0xfff;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int fr_row = lane & 31, fr_half = lane >> 5;
+  const float4* ws = reinterpret_cast<const float4*>(p.split_ws) +
+                     (size_t)blockIdx.x * split * (32 * NT) + tid;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m_local = wm * 128 + i * 32 + fr_row;
+    const bool live = m_local < tl.rows;
+    const size_t row = (size_t)(tl.row0 + m_local);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col0 = nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float4 v = ws[((j * 4 + i) * 4 + q) * NT];
+        for (int pt = 1; pt < split; ++pt) {
+          const float4 w = ws[(size_t)pt * (32 * NT) + ((j * 4 + i) * 4 + q) * NT];
+          v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+        }
+        if (live)
+          *reinterpret_cast<uint2*>(p.C + row * p.N + col0 + 8 * q) =
+              make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+      }
+    }
+  }
+}
+
 // ---- transposes feeding the backward GEMMs ------------------------------------------
 // All GEMMs here want both operands contiguous along the contraction dimension.  The
 // backward contracts over the other index of the weights (dH = dY W2, dX = dG W1 + dU W3)
@@ -477,11 +566,21 @@ size_t ffn_mfma_order_entries(const moe_ctx* c) {
 }
 
 static int run_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets, int nt_a, int nt_b,
-                     int32_t* koff, hipStream_t s) {
+                     int kt_b, int32_t* koff, hipStream_t s) {
   hipLaunchKernelGGL(mfma_sched_kernel, dim3(32), dim3(256), 0, s, counts, offsets,
                      c->d_wtab + 0 * MOE_MAX_EXPERTS, c->cfg.E, c->S_max, c->max_mtiles[1], nt_a,
-                     nt_b, c->d_sched[1], c->d_mtiles[1], c->d_order_up, c->d_order_down, koff);
+                     nt_b, c->n_cu, kt_b, c->d_sched[1], c->d_mtiles[1], c->d_order_up,
+                     c->d_order_down, koff);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+}
+
+// Down-type GEMM (plain epilogue) with the K-split tail: the GEMM, then the sum of the parts.
+static void launch_down(moe_ctx* c, GemmArgs& a, int nt, hipStream_t s) {
+  a.split_ws = c->d_split_ws;
+  // whole tiles (upper bound, rounded to 8) + one round of split units
+  const int grid = ((c->max_mtiles[1] * nt + 7) / 8) * 8 + ((c->n_cu + 7) / 8) * 8;
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN>), dim3(grid), dim3(NT), 0, s, a);
+  hipLaunchKernelGGL(ffn_split_reduce_kernel, dim3(c->n_cu / 2), dim3(NT), 0, s, a);
 }
 
 static GemmArgs tiled_args(moe_ctx* c, const void* A, int lda, const uint32_t* order, int nt,
@@ -510,10 +609,9 @@ int launch_ffn_mfma(moe_ctx* c, const int32_t* counts, const int32_t* offsets, c
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
   const int max_mt = c->max_mtiles[1];
   prof_mark(c, 0, s);
-  int st = run_sched(c, counts, offsets, nt_up, nt_down, nullptr, s);
+  int st = run_sched(c, counts, offsets, nt_up, nt_down, f / BK, nullptr, s);
   if (st != MOE_OK) return st;
   const int grid_up = ((max_mt * nt_up + 7) / 8) * 8;
-  const int grid_down = ((max_mt * nt_down + 7) / 8) * 8;
   prof_mark(c, 1, s);
   GemmArgs up = tiled_args(c, x_packed, d, c->d_order_up, nt_up, W1, W3, d, f, c->d_H);
   up.Gs = (uint16_t*)G;
@@ -521,7 +619,7 @@ int launch_ffn_mfma(moe_ctx* c, const int32_t* counts, const int32_t* offsets, c
   hipLaunchKernelGGL((ffn_mfma_kernel<MODE_UP>), dim3(grid_up), dim3(NT), 0, s, up);
   prof_mark(c, 2, s);
   GemmArgs dn = tiled_args(c, c->d_H, f, c->d_order_down, nt_down, W2, nullptr, f, d, y_packed);
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN>), dim3(grid_down), dim3(NT), 0, s, dn);
+  launch_down(c, dn, nt_down, s);
   prof_mark(c, 3, s);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
@@ -550,7 +648,7 @@ int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* 
   const void* const* W13T = c->d_wtab + 7 * MOE_MAX_EXPERTS;
   const int nt_f = f / 256, nt_d = d / 256;
   const int max_mt = c->max_mtiles[1];
-  int st = run_sched(c, counts, offsets, nt_f, nt_d, c->d_koff, s);
+  int st = run_sched(c, counts, offsets, nt_f, nt_d, 2 * f / BK, c->d_koff, s);
   if (st != MOE_OK) return st;
   // weights: W2 [d,f] -> W2^T [f,d];  W1, W3 [f,d] -> [W1^T | W3^T] [d,2f]
   hipLaunchKernelGGL(transpose_weights_kernel, dim3(f / 64, d / 64, E), dim3(256), 0, s, W2, W2T, d,
@@ -568,8 +666,7 @@ int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* 
                      dh);
   // dX = [dG|dU] [W1^T|W3^T]^T  (one GEMM with contraction length 2f)
   GemmArgs dx = tiled_args(c, c->d_dGU, 2 * f, c->d_order_down, nt_d, W13T, nullptr, 2 * f, d, dxp);
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN>), dim3(((max_mt * nt_d + 7) / 8) * 8), dim3(NT), 0,
-                     s, dx);
+  launch_down(c, dx, nt_d, s);
   // activations transposed per expert segment (zero padded to x128 rows)
   uint16_t* dYT = (uint16_t*)c->d_actT;
   uint16_t* XT = dYT + (size_t)d * Kt;

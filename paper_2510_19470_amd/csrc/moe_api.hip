@@ -29,6 +29,7 @@ void free_all(moe_ctx* c) {
   }
   (void)hipFree(c->d_order_up);
   (void)hipFree(c->d_order_down);
+  (void)hipFree(c->d_split_ws);
   (void)hipFree(c->d_H);
   (void)hipFree(c->d_dG);
   (void)hipFree(c->d_dU);
@@ -115,7 +116,9 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
   c->elem = cfg->dtype == MOE_BF16 ? 2 : 4;
   c->ffn_path = MOE_FFN_AUTO;
   c->S_max = (int32_t)S;
-  if (hipGetDevice(&c->device) != hipSuccess) {
+  if (hipGetDevice(&c->device) != hipSuccess ||
+      hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device) !=
+          hipSuccess) {
     delete c;
     return MOE_EHIP;
   }
@@ -138,6 +141,7 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
     const size_t n = ffn_mfma_order_entries(c);
     ok = ok && dev_alloc(&c->d_order_up, n) == hipSuccess;
     ok = ok && dev_alloc(&c->d_order_down, n) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_split_ws, (size_t)c->n_cu * MFMA_BM * 256) == hipSuccess;
   }
   ok = ok && hipMalloc(&c->d_H, std::max<size_t>((size_t)S * cfg->f * c->elem, 16)) == hipSuccess;
   ok = ok && hipMemset(c->d_totals, 0, sizeof(int32_t) * 2 * MOE_MAX_EXPERTS) == hipSuccess;

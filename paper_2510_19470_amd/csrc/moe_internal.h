@@ -18,7 +18,12 @@ struct MTile {
 // Tile schedule built on the device from expert_counts/offsets (no host sync).
 struct TileSched {
   int32_t n_mtiles;     // number of valid MTile entries
-  int32_t pad[3];
+  // K-split of the last, partly filled round of the down GEMM (MFMA path): the first
+  // down_full tiles of the order run whole, the remaining down_split_tiles are cut into
+  // down_split parts along the contraction (down_split == 1: nothing is cut)
+  int32_t down_full;
+  int32_t down_split_tiles;
+  int32_t down_split;
 };
 
 // pointer-table rows: W1, W3, W2, dW1, dW3, dW2, W2^T, [W1^T|W3^T]
@@ -51,6 +56,8 @@ struct moe_ctx {
   // first backward call)
   uint32_t* d_order_up;   // MFMA tile order of the gate/up GEMM
   uint32_t* d_order_down; // ... and of the down GEMM
+  int n_cu;               // compute units of the device
+  float* d_split_ws;      // fp32 partial tiles of the K-split tail: [n_cu][256*256]
   int32_t S_max;          // T_max*k
   void* d_H;              // [T_max*k][f]
   void* d_dG;             // [T_max*k][f]   (vector-ALU backward)
