@@ -49,8 +49,9 @@ __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row & 
 __global__ __launch_bounds__(256) void mfma_sched_kernel(
     const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets,
     const void* const* __restrict__ present, int E, int S, int max_mtiles, int nt_up, int nt_down,
-    int n_cu, int kt_down, TileSched* __restrict__ sched, MTile* __restrict__ mt,
-    uint32_t* __restrict__ order_up, uint32_t* __restrict__ order_down,
+    int n_cu, int kt_down, TileSched* __restrict__ sched, const void* const* __restrict__ up_b0,
+    const void* const* __restrict__ up_b1, const void* const* __restrict__ down_b0,
+    TileDesc* __restrict__ order_up, TileDesc* __restrict__ order_down,
     int32_t* __restrict__ koff) {
   __shared__ int32_t start[MOE_MAX_EXPERTS + 1];
   __shared__ int bad;
@@ -113,25 +114,11 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
   }
   const int gsz = gridDim.x * blockDim.x;
   const int gid = blockIdx.x * blockDim.x + tid;
-  for (int i = gid; i < total_m; i += gsz) {
-    int lo = 0, hi = E;  // largest e with start[e] <= i
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (start[mid] <= i) lo = mid; else hi = mid;
-    }
-    const int m = i - start[lo];
-    MTile t;
-    t.expert = lo;
-    t.row0 = offsets[lo] + m * BM;
-    t.rows = min(BM, counts[lo] - m * BM);
-    t.pad = 0;
-    mt[i] = t;
-  }
   // tile order: expert by expert; inside an expert column block by column block, and for
   // one column block all of the expert's row blocks in a row (they share a weight panel)
   for (int pass = 0; pass < 2; ++pass) {
     const int nt = pass == 0 ? nt_up : nt_down;
-    uint32_t* order = pass == 0 ? order_up : order_down;
+    TileDesc* order = pass == 0 ? order_up : order_down;
     const int total = total_m * nt;
     for (int L = gid; L < total; L += gsz) {
       int lo = 0, hi = E;
@@ -142,7 +129,14 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
       const int me = start[lo + 1] - start[lo];
       const int rel = L - start[lo] * nt;
       const int n = rel / me, m = rel % me;
-      order[L] = ((uint32_t)(start[lo] + m) << 12) | (uint32_t)n;
+      TileDesc t;
+      t.row0 = offsets[lo] + m * BM;
+      t.rows = min(BM, counts[lo] - m * BM);
+      t.nblk = n;
+      t.expert = lo;
+      t.b0 = pass == 0 ? up_b0[lo] : down_b0[lo];
+      t.b1 = pass == 0 && up_b1 != nullptr ? up_b1[lo] : nullptr;
+      order[L] = t;
     }
   }
 }
@@ -150,13 +144,14 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// Asynchronous 16 bytes per lane global -> LDS: the wavefront's 1 KB lands at lds_addr
-// (wave-uniform byte address, via M0) + lane * 16.  Written as assembly so that the
-// compiler does not serialise later LDS reads behind it; completion is tracked by hand
+// Asynchronous 16 bytes per lane global -> LDS: lane reads base + off (wave-uniform 64-bit
+// base in scalar registers, 32-bit per-lane byte offset), the wavefront's 1 KB lands at
+// lds_addr (wave-uniform byte address, via M0) + lane * 16.  Written as assembly so that
+// the compiler does not serialise later LDS reads behind it; completion is tracked by hand
 // (vmcnt) in the main loop.
-__device__ __forceinline__ void dma16(const uint4* src, uint32_t lds_addr) {
-  const uint32_t d = __builtin_amdgcn_readfirstlane(lds_addr);
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(d) : "memory");
+__device__ __forceinline__ void dma16(uint32_t off, const char* base, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_addr)
+               : "memory", "m0");
 }
 
 enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_WGRAD = 3 };
@@ -165,11 +160,8 @@ struct GemmArgs {
   const uint16_t* A;    // token-role operand: [rows, lda]
   int lda;              // elements per row of A (and of BT in MODE_WGRAD)
   const TileSched* sched;
-  const MTile* mt;
-  const uint32_t* order;
+  const TileDesc* order;
   int n_tiles_n;
-  const void* const* Bt0;  // weight-role operand table (UP: W1; DOWN: W2 or [W1^T|W3^T]; DH: W2^T)
-  const void* const* Bt1;  // UP: W3
   int K;                   // contraction length (not MODE_WGRAD)
   int N;                   // elements per output row
   uint16_t* C;             // UP: H; DOWN: Y / dX; DH: [dG|dU] with row pitch 2N
@@ -185,10 +177,118 @@ struct GemmArgs {
   int Mo, No, a_row0, b_row0;
 };
 
+// One unit of work of a block: a whole tile, or one K-split part of a tile (all fields are
+// wave-uniform and live in scalar registers).
+struct Unit {
+  int valid;
+  int row0, rows, nblk;     // tile: first packed row, valid rows, column block
+  const char* abase;        // token-role operand: first row of the tile, first k of the range
+  const char* bbase0;       // weight-role operand: first row of the column block (gate/up: W1)
+  const char* bbase1;       // gate/up: the same rows of W3; else bbase0 + 128 rows
+  int KT;                   // k-steps of 64 (even)
+  int ws_unit;              // >= 0: K-split part, index of its partial tile in the workspace
+};
+
+// The idx-th unit of this block.  Tiled modes: XCD x (= blockIdx & 7, the hardware deals
+// blocks round-robin to the XCDs) owns a contiguous range of the tile order and, after it,
+// a contiguous range of the K-split units of the tail; its gridDim/8 blocks take them in
+// turn.  The sequence of a block is dense: once a unit is invalid, all later ones are.
+template <int MODE>
+__device__ __forceinline__ Unit fetch_unit(const GemmArgs& p, int idx) {
+  Unit u;
+  u.valid = 0;
+  u.ws_unit = -1;
+  const int total = p.sched->n_mtiles * p.n_tiles_n;
+  const int n_full = MODE == MODE_DOWN ? p.sched->down_full : total;
+  const int split = MODE == MODE_DOWN ? p.sched->down_split : 1;
+  const int n_units = MODE == MODE_DOWN ? p.sched->down_split_tiles * split : 0;
+  const int per_xcd = (n_full + 7) >> 3, per_xcd_s = (n_units + 7) >> 3;
+  const int x = blockIdx.x & 7;
+  const int nf = max(0, min(per_xcd, n_full - x * per_xcd));
+  const int ns = max(0, min(per_xcd_s, n_units - x * per_xcd_s));
+  const int q = (int)(blockIdx.x >> 3) + idx * (int)(gridDim.x >> 3);
+  if (q >= nf + ns) return u;
+  int L, part = 0;
+  if (q < nf) {
+    L = x * per_xcd + q;
+    u.KT = p.K / BK;
+  } else {
+    const int su = x * per_xcd_s + (q - nf);
+    L = n_full + su / split;
+    part = su % split;
+    u.KT = p.K / BK / split;
+    u.ws_unit = su;
+  }
+  const TileDesc td = p.order[L];
+  u.valid = 1;
+  u.row0 = td.row0;
+  u.rows = td.rows;
+  u.nblk = td.nblk;
+  const size_t kbeg = (size_t)part * u.KT * (BK * 2);  // bytes into a row
+  u.abase = (const char*)p.A + (size_t)td.row0 * p.lda * 2 + kbeg;
+  if (MODE == MODE_UP) {
+    u.bbase0 = (const char*)td.b0 + (size_t)td.nblk * 128 * p.K * 2 + kbeg;
+    u.bbase1 = (const char*)td.b1 + (size_t)td.nblk * 128 * p.K * 2 + kbeg;
+  } else {
+    u.bbase0 = (const char*)td.b0 + (size_t)td.nblk * 256 * p.K * 2 + kbeg;
+    u.bbase1 = u.bbase0 + (size_t)128 * p.K * 2;
+  }
+  return u;
+}
+
+// One cluster pair of the main loop: memory cluster of token block I in stage S (fragment
+// reads; two copies, base + offset each, into the rows read one cluster ago), then the
+// compute cluster.
+template <int S, int I>
+__device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][4],
+                                           const uint4* lds, const int (&fr_a)[4],
+                                           const int (&fr_b)[2], int fr_half, int fr_swz,
+                                           uint32_t offa, const char* basea, uint32_t offb,
+                                           const char* baseb, uint32_t a_dst, uint32_t b_dst) {
+  const uint4* As = lds + (2 * S) * STAGE_VEC;
+  const uint4* Bs = lds + (2 * S + 1) * STAGE_VEC;
+  bf16x8 xa[4];
+  if (I == 0) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        wb[j][kk] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ((kk * 2 + fr_half) ^ fr_swz)]);
+  }
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+    xa[kk] = __builtin_bit_cast(bf16x8, As[fr_a[I] + ((kk * 2 + fr_half) ^ fr_swz)]);
+  constexpr int blk = (I + 3) & 3;
+  constexpr int st = I == 0 ? (S ^ 1) : S;
+  dma16(offa, basea, a_dst + st * 65536 + blk * 4096);
+  dma16(offb, baseb, b_dst + st * 65536 + blk * 8192);
+  // My fragment reads are done (the rows may be refilled after the next barrier) and all
+  // but my last 6 vector-memory operations have completed: the data read in cluster n
+  // was copied in clusters <= n-4, and every wavefront passes this point in cluster n-1
+  // before anybody reads in cluster n.  (Stores of an epilogue count as well and only
+  // make the wait stricter: copies complete in issue order among themselves.)
+  asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      acc[j][I] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[j][kk], xa[kk], acc[j][I], 0, 0, 0);
+  __builtin_amdgcn_s_setprio(0);
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_barrier" ::: "memory");
+}
+
 // MODE_UP   : H = silu(A W1^T) * (A W3^T)            (gate/up, SwiGLU fused)
 // MODE_DOWN : C = A B^T                               (down projection; also dX = [dG|dU][W1^T|W3^T]^T)
 // MODE_DH   : dH = A B^T, then dG = dH*u*silu'(g), dU = dH*silu(g), H = silu(g)*u
 // MODE_WGRAD: fp32 dW = AT BT^T, both operands transposed activations (contraction = rows)
+//
+// Tiled modes run persistent blocks (one per compute unit) over a static share of the tile
+// order, and the copy stream does not stop at a tile boundary: during the last two k-steps
+// of a tile the rows that become free are refilled with the first two k-steps of the
+// block's next tile, so that only the very first tile of a block pays a load latency.
 template <int MODE>
 __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   // stage s: token rows at (2s) * STAGE_VEC, weight rows at (2s+1) * STAGE_VEC
@@ -197,85 +297,49 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = __builtin_amdgcn_readfirstlane(wave >> 2), wn = wave & 3;
-  MTile tl;
-  int nblk, KT;
-  int split = 1, part = 0, unit = 0;  // K-split tail of the down GEMM
-  const uint4* a_src[4];
-  const uint4* b_src[4];
   float* dW = nullptr;
   int mblk = 0;
+  Unit cur;
+  // global -> LDS assignment: one copy instruction fills 8 rows (lane>>3) x 8 chunk slots
+  // (lane&7); slot c of row r must hold global chunk c ^ swz(r).  Token rows: copy i of a
+  // wavefront fills 8 rows of block i of its own group's half; weight rows: copy i fills
+  // row block 8i + wave (gate/up: blocks 0..15 are rows of W1, 16..31 the same rows of W3;
+  // otherwise bbase1 is bbase0 + 128 rows).  Per-lane byte offsets from the unit's bases:
+  uint32_t a_off[4], b_off[4];
+  const int a_pitch = p.lda * 2;                                   // bytes per token-role row
+  const int b_pitch = (MODE == MODE_WGRAD ? p.lda : p.K) * 2;      // ... per weight-role row
+  auto token_off = [&](int rows, int i) -> uint32_t {
+    const int ra = (16 * wm + 4 * i + wn) * 8 + (lane >> 3);
+    return (uint32_t)min(ra, rows - 1) * a_pitch + (((lane & 7) ^ swz(ra)) << 4);
+  };
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int rb = (8 * i + wave) * 8 + (lane >> 3);
+    b_off[i] = (uint32_t)(rb & 127) * b_pitch + (((lane & 7) ^ swz(rb)) << 4);
+  }
   if (MODE == MODE_WGRAD) {
     const int MoT = p.Mo >> 8, NoT = p.No >> 8;
     const int e = blockIdx.x / (MoT * NoT);
     const int rem = blockIdx.x % (MoT * NoT);
     mblk = rem / NoT;
-    nblk = rem % NoT;
     dW = (float*)p.dWt[e];
     if (dW == nullptr || p.present[e] == nullptr) return;
     const int k0 = p.koff[e];
-    KT = (p.koff[e + 1] - k0) / BK;
-    tl.expert = e;
-    tl.row0 = 0;
-    tl.rows = BM;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int ra = (16 * wm + 4 * i + wn) * 8 + (lane >> 3);
-      const int rb = (8 * i + wave) * 8 + (lane >> 3);
-      a_src[i] = (const uint4*)(p.A + (size_t)(p.a_row0 + mblk * 256 + ra) * p.lda + k0) +
-                 ((lane & 7) ^ swz(ra));
-      b_src[i] = (const uint4*)(p.BT + (size_t)(p.b_row0 + nblk * 256 + rb) * p.lda + k0) +
-                 ((lane & 7) ^ swz(rb));
-    }
+    cur.valid = 1;
+    cur.KT = (p.koff[e + 1] - k0) / BK;
+    cur.row0 = 0;
+    cur.rows = BM;
+    cur.nblk = rem % NoT;
+    cur.ws_unit = -1;
+    cur.abase = (const char*)(p.A + (size_t)(p.a_row0 + mblk * 256) * p.lda + k0);
+    cur.bbase0 = (const char*)(p.BT + (size_t)(p.b_row0 + cur.nblk * 256) * p.lda + k0);
+    cur.bbase1 = cur.bbase0 + (size_t)128 * b_pitch;
   } else {
-    // block -> work unit: XCD x (= blockIdx & 7, the hardware deals blocks round-robin to
-    // the XCDs) walks a contiguous range of the tile order; the K-split units of the tail
-    // are spread over the XCDs in the same way and come last
-    int L;
-    {
-      const int total = p.sched->n_mtiles * p.n_tiles_n;
-      const int n_full = MODE == MODE_DOWN ? p.sched->down_full : total;
-      const int per_xcd = (n_full + 7) >> 3;
-      const int slot = blockIdx.x >> 3;
-      if (slot < per_xcd) {
-        L = (blockIdx.x & 7) * per_xcd + slot;
-        if (L >= n_full) return;
-      } else {
-        if (MODE != MODE_DOWN) return;
-        split = p.sched->down_split;
-        const int n_units = p.sched->down_split_tiles * split;
-        const int per_xcd_s = (n_units + 7) >> 3;
-        const int j = slot - per_xcd;
-        unit = (blockIdx.x & 7) * per_xcd_s + j;
-        if (j >= per_xcd_s || unit >= n_units) return;
-        L = n_full + unit / split;
-        part = unit % split;
-      }
-    }
-    const uint32_t ent = p.order[L];
-    tl = p.mt[ent >> 12];
-    nblk = ent & 0xfff;
-    KT = p.K / BK / split;
-    const int kbeg = part * KT * 8;  // first 16-byte chunk of this part's k-range
-    // global -> LDS assignment: one copy instruction fills 8 rows (lane>>3) x 8 chunk slots
-    // (lane&7); slot c of row r must hold global chunk c ^ swz(r).  Token rows: copy i of
-    // a wavefront fills 8 rows of block i of its own group's half; weight rows: copy i
-    // fills row block 8i + wave.
-    const uint16_t* B0 = (const uint16_t*)p.Bt0[tl.expert];
-    const uint16_t* B1 = GATED ? (const uint16_t*)p.Bt1[tl.expert] : nullptr;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int ra = (16 * wm + 4 * i + wn) * 8 + (lane >> 3);
-      const int rb = (8 * i + wave) * 8 + (lane >> 3);
-      const int arow = min(ra, tl.rows - 1);
-      a_src[i] = (const uint4*)(p.A + (size_t)(tl.row0 + arow) * p.lda) + kbeg + ((lane & 7) ^ swz(ra));
-      const uint16_t* bp;
-      if (GATED)
-        bp = (rb < 128 ? B0 : B1) + (size_t)(nblk * 128 + (rb & 127)) * p.K;
-      else
-        bp = B0 + (size_t)(nblk * 256 + rb) * p.K;
-      b_src[i] = (const uint4*)bp + kbeg + ((lane & 7) ^ swz(rb));
-    }
+    cur = fetch_unit<MODE>(p, 0);
+    if (!cur.valid) return;
   }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a_off[i] = token_off(cur.rows, i);
 
   // ---- fragment read offsets (uint4 units inside one operand stage)
   const int fr_row = lane & 31, fr_half = lane >> 5;
@@ -287,179 +351,193 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   for (int j = 0; j < 2; ++j) fr_b[j] = (j * 128 + wn * 32 + fr_row) * 8;
 
   f32x16 acc[2][4];
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
-  // K is a multiple of 128: the number of k-steps is even (the loop body covers both stages
-  // with compile-time offsets).  KT == 0 (weight gradient of an expert without rows) skips
-  // everything, for the whole block alike.
-  if (KT > 0) {
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
-    const uint32_t a_dst = lds_base + (16 * wm + wn) * 1024;  // + stage * 65536 + block * 4096
-    const uint32_t b_dst = lds_base + 32768 + wave * 1024;    // + stage * 65536 + block * 8192
-    // both stages in full, then the second group falls one cluster behind
+  // ---- epilogue of one unit: lane holds, per 32x32 accumulator, token row (lane&31) and
+  // the weight rows 8*g + 4*(lane>>5) + {0..3}, g = 0..3
+  auto epilogue = [&](const Unit& u) {
+    if (MODE == MODE_DOWN && u.ws_unit >= 0) {
+      // partial sums of one K-split part, in accumulator order: [unit][j][i][quad][thread]
+      float4* ws = reinterpret_cast<float4*>(p.split_ws) + (size_t)u.ws_unit * (32 * NT) + tid;
 #pragma unroll
-    for (int st = 0; st < 2; ++st)
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        dma16(a_src[i] + st * 8, a_dst + st * 65536 + i * 4096);
-        dma16(b_src[i] + st * 8, b_dst + st * 65536 + i * 8192);
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            ws[((j * 4 + i) * 4 + q) * NT] = make_float4(acc[j][i][q * 4], acc[j][i][q * 4 + 1],
+                                                         acc[j][i][q * 4 + 2], acc[j][i][q * 4 + 3]);
+      return;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m_local = wm * 128 + i * 32 + fr_row;
+      if (m_local >= u.rows) continue;
+      if (MODE == MODE_WGRAD) {
+        float* orow = dW + (size_t)(mblk * 256 + m_local) * p.No;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int col0 = u.nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            *reinterpret_cast<float4*>(orow + col0 + 8 * g) =
+                make_float4(acc[j][i][g * 4], acc[j][i][g * 4 + 1], acc[j][i][g * 4 + 2],
+                            acc[j][i][g * 4 + 3]);
+        }
+        continue;
       }
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    if (wm == 1) asm volatile("s_barrier" ::: "memory");
-    bf16x8 wb[2][4], xa[4];
-    for (int kt = 0; kt < KT; kt += 2) {
+      const size_t row = (size_t)(u.row0 + m_local);
+      if (MODE == MODE_UP) {
+        const int col0 = u.nblk * 128 + wn * 32 + 4 * fr_half;
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        const int k = kt + s;
-        const uint4* As = lds + (2 * s) * STAGE_VEC;
-        const uint4* Bs = lds + (2 * s + 1) * STAGE_VEC;
+        for (int g = 0; g < 4; ++g) {
+          float h[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          // ---- memory cluster: fragments of token block i (and, first, of all weight rows)
-          if (i == 0) {
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-              for (int j = 0; j < 2; ++j)
-                wb[j][kk] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ((kk * 2 + fr_half) ^ fr_swz)]);
+          for (int r = 0; r < 4; ++r) {
+            const float gv = acc[0][i][g * 4 + r], uv = acc[1][i][g * 4 + r];
+            h[r] = silu_f(gv) * uv;
           }
-#pragma unroll
-          for (int kk = 0; kk < 4; ++kk)
-            xa[kk] = __builtin_bit_cast(bf16x8, As[fr_a[i] + ((kk * 2 + fr_half) ^ fr_swz)]);
-          {
-            // refill what was read one cluster ago with the data of its next use: token
-            // block i-1 and weight row blocks 8(i-1)+wave of this stage with step k+2; at
-            // i == 0 block 3 of the other stage with step k+1.  Past the end the last step
-            // is fetched again (in bounds, never read): the copy count per cluster stays
-            // fixed, which the vmcnt arithmetic below relies on.
-            const int blk = (i + 3) & 3;
-            const int st = i == 0 ? (s ^ 1) : s;
-            int kd = i == 0 ? k + 1 : k + 2;
-            kd = kd < KT ? kd : KT - 1;
-            dma16(a_src[blk] + kd * 8, a_dst + st * 65536 + blk * 4096);
-            dma16(b_src[blk] + kd * 8, b_dst + st * 65536 + blk * 8192);
+          const size_t o = row * p.N + col0 + 8 * g;
+          *reinterpret_cast<uint2*>(p.C + o) =
+              make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+          if (p.Gs != nullptr) {
+            *reinterpret_cast<uint2*>(p.Gs + o) =
+                make_uint2(pack_bf16x2(acc[0][i][g * 4], acc[0][i][g * 4 + 1]),
+                           pack_bf16x2(acc[0][i][g * 4 + 2], acc[0][i][g * 4 + 3]));
+            *reinterpret_cast<uint2*>(p.Us + o) =
+                make_uint2(pack_bf16x2(acc[1][i][g * 4], acc[1][i][g * 4 + 1]),
+                           pack_bf16x2(acc[1][i][g * 4 + 2], acc[1][i][g * 4 + 3]));
           }
-          // My fragment reads are done (the rows may be refilled after the next barrier)
-          // and all but my last 6 copies have landed: the data read in cluster n was
-          // copied in clusters <= n-4, and every wavefront passes this point in cluster
-          // n-1 before anybody reads in cluster n.
-          asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-          // ---- compute cluster
-          __builtin_amdgcn_sched_barrier(0);
-          __builtin_amdgcn_s_setprio(1);
+        }
+      } else {
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk)
+        for (int j = 0; j < 2; ++j) {
+          const int col0 = u.nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-              acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[j][kk], xa[kk], acc[j][i], 0, 0, 0);
-          __builtin_amdgcn_s_setprio(0);
-          __builtin_amdgcn_sched_barrier(0);
-          asm volatile("s_barrier" ::: "memory");
+          for (int g = 0; g < 4; ++g) {
+            const int col = col0 + 8 * g;
+            if (MODE == MODE_DOWN) {
+              *reinterpret_cast<uint2*>(p.C + row * p.N + col) =
+                  make_uint2(pack_bf16x2(acc[j][i][g * 4], acc[j][i][g * 4 + 1]),
+                             pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]));
+            } else {  // MODE_DH
+              const uint2 gq = *reinterpret_cast<const uint2*>(p.Gs + row * p.N + col);
+              const uint2 uq = *reinterpret_cast<const uint2*>(p.Us + row * p.N + col);
+              const uint32_t gw[2] = {gq.x, gq.y}, uw[2] = {uq.x, uq.y};
+              float dg[4], du[4], hh[4];
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const float gv = __uint_as_float((r & 1) ? (gw[r >> 1] & 0xffff0000u) : (gw[r >> 1] << 16));
+                const float uv = __uint_as_float((r & 1) ? (uw[r >> 1] & 0xffff0000u) : (uw[r >> 1] << 16));
+                const float dh = acc[j][i][g * 4 + r];
+                const float sg = sigmoid_f(gv);
+                dg[r] = dh * uv * sg * (1.f + gv * (1.f - sg));
+                du[r] = dh * gv * sg;
+                hh[r] = gv * sg * uv;
+              }
+              *reinterpret_cast<uint2*>(p.C + row * (2 * (size_t)p.N) + col) =
+                  make_uint2(pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3]));
+              *reinterpret_cast<uint2*>(p.C + row * (2 * (size_t)p.N) + p.N + col) =
+                  make_uint2(pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3]));
+              *reinterpret_cast<uint2*>(p.C2 + row * p.N + col) =
+                  make_uint2(pack_bf16x2(hh[0], hh[1]), pack_bf16x2(hh[2], hh[3]));
+            }
+          }
         }
       }
     }
-    if (wm == 0) asm volatile("s_barrier" ::: "memory");  // as many barriers as the other group
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no copy in flight into LDS at exit
-  }
+  };
 
-  if (MODE == MODE_DOWN && split > 1) {
-    // partial sums of one part, in accumulator order: [unit][j][i][quad][thread] float4
-    float4* ws = reinterpret_cast<float4*>(p.split_ws) + (size_t)unit * (32 * NT) + tid;
+  auto zero_acc = [&]() {
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          ws[((j * 4 + i) * 4 + q) * NT] = make_float4(acc[j][i][q * 4], acc[j][i][q * 4 + 1],
-                                                       acc[j][i][q * 4 + 2], acc[j][i][q * 4 + 3]);
+        for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+  };
+
+  // Every unit has an even number of k-steps (K and the padded expert segments are
+  // multiples of 128; the K-split keeps parts even).  KT == 0 happens only for the weight
+  // gradient of an expert without rows: nothing is loaded, zeros are stored.
+  if (cur.KT == 0) {
+    zero_acc();
+    epilogue(cur);
     return;
   }
 
-  // ---- epilogue: lane holds, per 32x32 accumulator, token row (lane&31) and the weight
-  // rows 8*g + 4*(lane>>5) + {0..3}, g = 0..3
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
+  // wave-uniform LDS byte addresses: + stage * 65536 + block * 4096 (tokens) / 8192 (weights)
+  const uint32_t a_dst = __builtin_amdgcn_readfirstlane(lds_base + (16 * wm + wn) * 1024);
+  const uint32_t b_dst = __builtin_amdgcn_readfirstlane(lds_base + 32768 + wave * 1024);
+  // first unit: both stages in full (stage 0 first), then the second group falls one
+  // cluster behind
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m_local = wm * 128 + i * 32 + fr_row;
-    if (m_local >= tl.rows) continue;
-    if (MODE == MODE_WGRAD) {
-      float* orow = dW + (size_t)(mblk * 256 + m_local) * p.No;
+  for (int st = 0; st < 2; ++st)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col0 = nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-          *reinterpret_cast<float4*>(orow + col0 + 8 * g) =
-              make_float4(acc[j][i][g * 4], acc[j][i][g * 4 + 1], acc[j][i][g * 4 + 2],
-                          acc[j][i][g * 4 + 3]);
-      }
-      continue;
+    for (int i = 0; i < 4; ++i) {
+      dma16(a_off[i], cur.abase + st * 128, a_dst + st * 65536 + i * 4096);
+      dma16(b_off[i], (i < 2 ? cur.bbase0 : cur.bbase1) + st * 128, b_dst + st * 65536 + i * 8192);
     }
-    const size_t row = (size_t)(tl.row0 + m_local);
-    if (MODE == MODE_UP) {
-      const int col0 = nblk * 128 + wn * 32 + 4 * fr_half;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        float h[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float gv = acc[0][i][g * 4 + r], uv = acc[1][i][g * 4 + r];
-          h[r] = silu_f(gv) * uv;
-        }
-        const size_t o = row * p.N + col0 + 8 * g;
-        *reinterpret_cast<uint2*>(p.C + o) =
-            make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
-        if (p.Gs != nullptr) {
-          *reinterpret_cast<uint2*>(p.Gs + o) =
-              make_uint2(pack_bf16x2(acc[0][i][g * 4], acc[0][i][g * 4 + 1]),
-                         pack_bf16x2(acc[0][i][g * 4 + 2], acc[0][i][g * 4 + 3]));
-          *reinterpret_cast<uint2*>(p.Us + o) =
-              make_uint2(pack_bf16x2(acc[1][i][g * 4], acc[1][i][g * 4 + 1]),
-                         pack_bf16x2(acc[1][i][g * 4 + 2], acc[1][i][g * 4 + 3]));
-        }
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col0 = nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int col = col0 + 8 * g;
-          if (MODE == MODE_DOWN) {
-            *reinterpret_cast<uint2*>(p.C + row * p.N + col) =
-                make_uint2(pack_bf16x2(acc[j][i][g * 4], acc[j][i][g * 4 + 1]),
-                           pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]));
-          } else {  // MODE_DH
-            const uint2 gq = *reinterpret_cast<const uint2*>(p.Gs + row * p.N + col);
-            const uint2 uq = *reinterpret_cast<const uint2*>(p.Us + row * p.N + col);
-            const uint32_t gw[2] = {gq.x, gq.y}, uw[2] = {uq.x, uq.y};
-            float dg[4], du[4], hh[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const float gv = __uint_as_float((r & 1) ? (gw[r >> 1] & 0xffff0000u) : (gw[r >> 1] << 16));
-              const float uv = __uint_as_float((r & 1) ? (uw[r >> 1] & 0xffff0000u) : (uw[r >> 1] << 16));
-              const float dh = acc[j][i][g * 4 + r];
-              const float sg = sigmoid_f(gv);
-              dg[r] = dh * uv * sg * (1.f + gv * (1.f - sg));
-              du[r] = dh * gv * sg;
-              hh[r] = gv * sg * uv;
-            }
-            *reinterpret_cast<uint2*>(p.C + row * (2 * (size_t)p.N) + col) =
-                make_uint2(pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3]));
-            *reinterpret_cast<uint2*>(p.C + row * (2 * (size_t)p.N) + p.N + col) =
-                make_uint2(pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3]));
-            *reinterpret_cast<uint2*>(p.C2 + row * p.N + col) =
-                make_uint2(pack_bf16x2(hh[0], hh[1]), pack_bf16x2(hh[2], hh[3]));
-          }
-        }
-      }
+  // stage 0 has landed (stage 1 is first read four clusters on, after the vmcnt(6) waits)
+  asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+  if (wm == 1) asm volatile("s_barrier" ::: "memory");
+
+  bf16x8 wb[2][4];
+  for (int idx = 0;; ++idx) {
+    Unit nxt;
+    nxt.valid = 0;
+    if (MODE != MODE_WGRAD) nxt = fetch_unit<MODE>(p, idx + 1);
+    zero_acc();
+    const int KT = cur.KT;
+    // steady part: steps 0 .. KT-3; what was read one cluster ago is refilled with the data
+    // of its next use (token block i-1 and weight row blocks 8(i-1)+wave of this stage with
+    // step k+2; at i == 0 block 3 of the other stage with step k+1)
+    for (int kt = 0; kt < KT - 2; kt += 2) {
+      const char* a1 = cur.abase + (kt + 1) * 128;  // step kt+1 (+128: kt+2, +256: kt+3)
+      const char* b01 = cur.bbase0 + (kt + 1) * 128;
+      const char* b11 = cur.bbase1 + (kt + 1) * 128;
+#define PP(S, I, OA, BA, OB, BB) \
+  pp_cluster<S, I>(acc, wb, lds, fr_a, fr_b, fr_half, fr_swz, OA, BA, OB, BB, a_dst, b_dst)
+      PP(0, 0, a_off[3], a1, b_off[3], b11);
+      PP(0, 1, a_off[0], a1 + 128, b_off[0], b01 + 128);
+      PP(0, 2, a_off[1], a1 + 128, b_off[1], b01 + 128);
+      PP(0, 3, a_off[2], a1 + 128, b_off[2], b11 + 128);
+      PP(1, 0, a_off[3], a1 + 128, b_off[3], b11 + 128);
+      PP(1, 1, a_off[0], a1 + 256, b_off[0], b01 + 256);
+      PP(1, 2, a_off[1], a1 + 256, b_off[1], b01 + 256);
+      PP(1, 3, a_off[2], a1 + 256, b_off[2], b11 + 256);
     }
+    // last two steps: the refills fetch steps 0 and 1 of the next unit (the token offsets
+    // are switched block by block, each right after its last use for this unit).  Without a
+    // next unit the last step is fetched again (in bounds, never read): the copy count per
+    // cluster stays fixed, which the vmcnt arithmetic relies on.
+    {
+      const int last = (KT - 1) * 128;
+      const char* na = nxt.valid ? nxt.abase : cur.abase + last;      // next unit's step 0
+      const char* nb0 = nxt.valid ? nxt.bbase0 : cur.bbase0 + last;
+      const char* nb1 = nxt.valid ? nxt.bbase1 : cur.bbase1 + last;
+      const int o1 = nxt.valid ? 128 : 0;                             // ... its step 1
+      PP(0, 0, a_off[3], cur.abase + last, b_off[3], cur.bbase1 + last);
+      if (nxt.valid) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) a_off[i] = token_off(nxt.rows, i);
+      }
+      PP(0, 1, a_off[0], na, b_off[0], nb0);
+      PP(0, 2, a_off[1], na, b_off[1], nb0);
+      PP(0, 3, a_off[2], na, b_off[2], nb1);
+      if (nxt.valid) a_off[3] = token_off(nxt.rows, 3);
+      PP(1, 0, a_off[3], na, b_off[3], nb1);
+      PP(1, 1, a_off[0], na + o1, b_off[0], nb0 + o1);
+      PP(1, 2, a_off[1], na + o1, b_off[1], nb0 + o1);
+      PP(1, 3, a_off[2], na + o1, b_off[2], nb1 + o1);
+#undef PP
+    }
+    epilogue(cur);
+    if (!nxt.valid) break;
+    cur = nxt;
   }
+  if (wm == 0) asm volatile("s_barrier" ::: "memory");  // as many barriers as the other group
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no copy in flight into LDS at exit
 }
 
 // Sums the parts of every K-split tile of the down GEMM in a fixed order (part 0, 1, ...:
@@ -469,9 +547,8 @@ __global__ __launch_bounds__(NT) void ffn_split_reduce_kernel(const GemmArgs p) 
   const int n_tiles = p.sched->down_split_tiles;
   if ((int)blockIdx.x >= n_tiles) return;
   const int split = p.sched->down_split;
-  const uint32_t ent = p.order[p.sched->down_full + blockIdx.x];
-  const MTile tl = p.mt[ent >> 12];
-  const int nblk = ent & 0xfff;
+  const TileDesc tl = p.order[p.sched->down_full + blockIdx.x];
+  const int nblk = tl.nblk;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
   const int fr_row = lane & 31, fr_half = lane >> 5;
@@ -566,34 +643,34 @@ size_t ffn_mfma_order_entries(const moe_ctx* c) {
 }
 
 static int run_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets, int nt_a, int nt_b,
-                     int kt_b, int32_t* koff, hipStream_t s) {
+                     int kt_b, const void* const* up_b0, const void* const* up_b1,
+                     const void* const* down_b0, int32_t* koff, hipStream_t s) {
   hipLaunchKernelGGL(mfma_sched_kernel, dim3(32), dim3(256), 0, s, counts, offsets,
                      c->d_wtab + 0 * MOE_MAX_EXPERTS, c->cfg.E, c->S_max, c->max_mtiles[1], nt_a,
-                     nt_b, c->n_cu, kt_b, c->d_sched[1], c->d_mtiles[1], c->d_order_up,
+                     nt_b, c->n_cu, kt_b, c->d_sched[1], up_b0, up_b1, down_b0, c->d_order_up,
                      c->d_order_down, koff);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 
+// One block per compute unit (a block takes all of a unit's LDS), a multiple of 8 so that
+// every XCD gets the same number of blocks.
+static int persistent_grid(const moe_ctx* c) { return (c->n_cu / 8) * 8; }
+
 // Down-type GEMM (plain epilogue) with the K-split tail: the GEMM, then the sum of the parts.
 static void launch_down(moe_ctx* c, GemmArgs& a, int nt, hipStream_t s) {
   a.split_ws = c->d_split_ws;
-  // whole tiles (upper bound, rounded to 8) + one round of split units
-  const int grid = ((c->max_mtiles[1] * nt + 7) / 8) * 8 + ((c->n_cu + 7) / 8) * 8;
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN>), dim3(grid), dim3(NT), 0, s, a);
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN>), dim3(persistent_grid(c)), dim3(NT), 0, s, a);
   hipLaunchKernelGGL(ffn_split_reduce_kernel, dim3(c->n_cu / 2), dim3(NT), 0, s, a);
 }
 
-static GemmArgs tiled_args(moe_ctx* c, const void* A, int lda, const uint32_t* order, int nt,
-                           const void* const* B0, const void* const* B1, int K, int N, void* C) {
+static GemmArgs tiled_args(moe_ctx* c, const void* A, int lda, const TileDesc* order, int nt,
+                           int K, int N, void* C) {
   GemmArgs a{};
   a.A = (const uint16_t*)A;
   a.lda = lda;
   a.sched = c->d_sched[1];
-  a.mt = c->d_mtiles[1];
   a.order = order;
   a.n_tiles_n = nt;
-  a.Bt0 = B0;
-  a.Bt1 = B1;
   a.K = K;
   a.N = N;
   a.C = (uint16_t*)C;
@@ -609,16 +686,15 @@ int launch_ffn_mfma(moe_ctx* c, const int32_t* counts, const int32_t* offsets, c
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
   const int max_mt = c->max_mtiles[1];
   prof_mark(c, 0, s);
-  int st = run_sched(c, counts, offsets, nt_up, nt_down, f / BK, nullptr, s);
+  int st = run_sched(c, counts, offsets, nt_up, nt_down, f / BK, W1, W3, W2, nullptr, s);
   if (st != MOE_OK) return st;
-  const int grid_up = ((max_mt * nt_up + 7) / 8) * 8;
   prof_mark(c, 1, s);
-  GemmArgs up = tiled_args(c, x_packed, d, c->d_order_up, nt_up, W1, W3, d, f, c->d_H);
+  GemmArgs up = tiled_args(c, x_packed, d, c->d_order_up, nt_up, d, f, c->d_H);
   up.Gs = (uint16_t*)G;
   up.Us = (uint16_t*)U;
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_UP>), dim3(grid_up), dim3(NT), 0, s, up);
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_UP>), dim3(persistent_grid(c)), dim3(NT), 0, s, up);
   prof_mark(c, 2, s);
-  GemmArgs dn = tiled_args(c, c->d_H, f, c->d_order_down, nt_down, W2, nullptr, f, d, y_packed);
+  GemmArgs dn = tiled_args(c, c->d_H, f, c->d_order_down, nt_down, f, d, y_packed);
   launch_down(c, dn, nt_down, s);
   prof_mark(c, 3, s);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
@@ -648,7 +724,7 @@ int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* 
   const void* const* W13T = c->d_wtab + 7 * MOE_MAX_EXPERTS;
   const int nt_f = f / 256, nt_d = d / 256;
   const int max_mt = c->max_mtiles[1];
-  int st = run_sched(c, counts, offsets, nt_f, nt_d, 2 * f / BK, c->d_koff, s);
+  int st = run_sched(c, counts, offsets, nt_f, nt_d, 2 * f / BK, W2T, nullptr, W13T, c->d_koff, s);
   if (st != MOE_OK) return st;
   // weights: W2 [d,f] -> W2^T [f,d];  W1, W3 [f,d] -> [W1^T | W3^T] [d,2f]
   hipLaunchKernelGGL(transpose_weights_kernel, dim3(f / 64, d / 64, E), dim3(256), 0, s, W2, W2T, d,
@@ -658,14 +734,13 @@ int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* 
   hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, s, W3, W13T, f,
                      d, 2 * f, f);
   // dH = dY W2 with the SwiGLU derivative in the epilogue -> [dG|dU], H
-  GemmArgs dh = tiled_args(c, dy, d, c->d_order_up, nt_f, W2T, nullptr, d, f, c->d_dGU);
+  GemmArgs dh = tiled_args(c, dy, d, c->d_order_up, nt_f, d, f, c->d_dGU);
   dh.C2 = (uint16_t*)c->d_H;
   dh.Gs = (uint16_t*)const_cast<void*>(G);
   dh.Us = (uint16_t*)const_cast<void*>(U);
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH>), dim3(((max_mt * nt_f + 7) / 8) * 8), dim3(NT), 0, s,
-                     dh);
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
   // dX = [dG|dU] [W1^T|W3^T]^T  (one GEMM with contraction length 2f)
-  GemmArgs dx = tiled_args(c, c->d_dGU, 2 * f, c->d_order_down, nt_d, W13T, nullptr, 2 * f, d, dxp);
+  GemmArgs dx = tiled_args(c, c->d_dGU, 2 * f, c->d_order_down, nt_d, 2 * f, d, dxp);
   launch_down(c, dx, nt_d, s);
   // activations transposed per expert segment (zero padded to x128 rows)
   uint16_t* dYT = (uint16_t*)c->d_actT;

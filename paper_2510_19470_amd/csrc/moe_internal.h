@@ -15,6 +15,16 @@ struct MTile {
   int32_t pad;
 };
 
+// One tile of an MFMA grouped GEMM, complete: a block needs one 32-byte read to start.
+struct TileDesc {
+  int32_t row0;    // first packed row
+  int32_t rows;    // valid rows (1..256)
+  int32_t nblk;    // column block
+  int32_t expert;
+  const void* b0;  // weight-role operand of this expert (gate/up: W1)
+  const void* b1;  // gate/up: W3
+};
+
 // Tile schedule built on the device from expert_counts/offsets (no host sync).
 struct TileSched {
   int32_t n_mtiles;     // number of valid MTile entries
@@ -54,8 +64,8 @@ struct moe_ctx {
   int32_t max_mtiles[2];
   // activations between the two GEMMs, and the backward's temporaries (allocated on the
   // first backward call)
-  uint32_t* d_order_up;   // MFMA tile order of the gate/up GEMM
-  uint32_t* d_order_down; // ... and of the down GEMM
+  TileDesc* d_order_up;   // MFMA tile order of the gate/up GEMM
+  TileDesc* d_order_down; // ... and of the down GEMM
   int n_cu;               // compute units of the device
   float* d_split_ws;      // fp32 partial tiles of the K-split tail: [n_cu][256*256]
   int32_t S_max;          // T_max*k
