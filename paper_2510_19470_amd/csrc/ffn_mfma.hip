@@ -541,39 +541,40 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
 }
 
 // Sums the parts of every K-split tile of the down GEMM in a fixed order (part 0, 1, ...:
-// deterministic) and stores the tile like the GEMM's own epilogue.  One block per split
-// tile; thread and accumulator indices mean what they mean in ffn_mfma_kernel.
+// deterministic) and stores the tile like the GEMM's own epilogue.  Eight blocks per split
+// tile, one per accumulator (j, i) of the GEMM's wavefront tile; thread and accumulator
+// indices mean what they mean in ffn_mfma_kernel.  All parts of a quad are loaded before
+// they are added (up to 8 loads in flight per quad).
 __global__ __launch_bounds__(NT) void ffn_split_reduce_kernel(const GemmArgs p) {
   const int n_tiles = p.sched->down_split_tiles;
-  if ((int)blockIdx.x >= n_tiles) return;
+  const int tile = blockIdx.x >> 3, ji = blockIdx.x & 7;
+  if (tile >= n_tiles) return;
   const int split = p.sched->down_split;
-  const TileDesc tl = p.order[p.sched->down_full + blockIdx.x];
-  const int nblk = tl.nblk;
+  const TileDesc tl = p.order[p.sched->down_full + tile];
+  const int j = ji >> 2, i = ji & 3;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
   const int fr_row = lane & 31, fr_half = lane >> 5;
   const float4* ws = reinterpret_cast<const float4*>(p.split_ws) +
-                     (size_t)blockIdx.x * split * (32 * NT) + tid;
+                     (size_t)tile * split * (32 * NT) + (size_t)(ji * 4) * NT + tid;
+  const int m_local = wm * 128 + i * 32 + fr_row;
+  const bool live = m_local < tl.rows;
+  const size_t row = (size_t)(tl.row0 + m_local);
+  const int col0 = tl.nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m_local = wm * 128 + i * 32 + fr_row;
-    const bool live = m_local < tl.rows;
-    const size_t row = (size_t)(tl.row0 + m_local);
+  for (int q = 0; q < 4; ++q) {
+    float4 part[8];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col0 = nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
+    for (int pt = 0; pt < 8; ++pt)
+      part[pt] = pt < split ? ws[(size_t)pt * (32 * NT) + q * NT] : make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 v = part[0];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float4 v = ws[((j * 4 + i) * 4 + q) * NT];
-        for (int pt = 1; pt < split; ++pt) {
-          const float4 w = ws[(size_t)pt * (32 * NT) + ((j * 4 + i) * 4 + q) * NT];
-          v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
-        }
-        if (live)
-          *reinterpret_cast<uint2*>(p.C + row * p.N + col0 + 8 * q) =
-              make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
-      }
+    for (int pt = 1; pt < 8; ++pt) {
+      v.x += part[pt].x; v.y += part[pt].y; v.z += part[pt].z; v.w += part[pt].w;
     }
+    if (live)
+      *reinterpret_cast<uint2*>(p.C + row * p.N + col0 + 8 * q) =
+          make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
   }
 }
 
@@ -660,7 +661,7 @@ static int persistent_grid(const moe_ctx* c) { return (c->n_cu / 8) * 8; }
 static void launch_down(moe_ctx* c, GemmArgs& a, int nt, hipStream_t s) {
   a.split_ws = c->d_split_ws;
   hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN>), dim3(persistent_grid(c)), dim3(NT), 0, s, a);
-  hipLaunchKernelGGL(ffn_split_reduce_kernel, dim3(c->n_cu / 2), dim3(NT), 0, s, a);
+  hipLaunchKernelGGL(ffn_split_reduce_kernel, dim3((c->n_cu / 2) * 8), dim3(NT), 0, s, a);
 }
 
 static GemmArgs tiled_args(moe_ctx* c, const void* A, int lda, const TileDesc* order, int nt,
