@@ -200,3 +200,33 @@ def random_routing(T: int, E: int, k: int, seed: int, skew: float = 0.0) -> np.n
     rng = np.random.default_rng(seed)
     g = rng.standard_normal((T, E)) - skew * np.log(np.arange(E) + 1.0)[None, :]
     return np.argsort(-g, axis=1, kind="stable")[:, :k].astype(np.int32)
+
+
+# ------------------------------------------------------------ shared/residual compression
+def make_sr_inputs(shape: Tuple[int, int], seed: int, dtype: str, n_experts: int = 2,
+                   ties: bool = False):
+    """Weights for the shared/residual expert compression (paper Sec. 4.2): a shared
+    expert and `n_experts` experts that differ from it by a residual concentrated in few
+    entries (Fig. "SRexpert"(a): the residuals' distribution is much narrower than the
+    weights', the differences sit in a small number of parameters).
+
+    Recipe (one default_rng(seed) stream, fp32 draws): shared [rows, cols] ~ N(0, 1/cols);
+    per expert: a dense part ~ N(0, (0.05)^2 / cols) and, on a random 2 % of the entries, a
+    large part ~ N(0, 1/cols) added on top; expert = shared + residual.  With `ties`, the
+    residual is quantised to multiples of 2^-7/sqrt(cols) so that many magnitudes are equal.
+    Everything is rounded to the storage type; returns (shared, [experts]) as stored arrays.
+    """
+    rows, cols = shape
+    rng = np.random.default_rng(seed)
+    sd = 1.0 / np.sqrt(cols)
+    shared = (rng.standard_normal((rows, cols), dtype=np.float32) * np.float32(sd)).astype(np.float32)
+    experts = []
+    for _ in range(n_experts):
+        res = rng.standard_normal((rows, cols), dtype=np.float32) * np.float32(0.05 * sd)
+        big = rng.random((rows, cols), dtype=np.float32) < np.float32(0.02)
+        res = res + big * (rng.standard_normal((rows, cols), dtype=np.float32) * np.float32(sd))
+        if ties:
+            q = np.float32(sd / 128.0)
+            res = np.round(res / q) * q
+        experts.append(store((shared + res).astype(np.float32), dtype))
+    return store(shared, dtype), experts
