@@ -215,6 +215,32 @@ int moe_plan_expert_dest_rank(int32_t local_rank, int32_t E, int32_t L, const in
 int moe_plan_model(double D, double P_E, double B, double lat_pe, int32_t G, double* p_star,
                    int32_t* case_id, int32_t* best_S);
 
+/* ---- Shared/residual expert compression (Sec. 4.2 "SR-Based Expert Compression";
+ * compression ratio CR: Sec. 5.4).  An expert weight matrix is sent to the other GPUs of
+ * its domain as the k largest-magnitude entries of (expert - shared expert) in value-index
+ * form and rebuilt there as shared + scattered residual.  n = elements of the matrix (any
+ * shape, taken flat), 1 <= n < 2^31; storage type = the context's dtype.
+ *
+ * moe_sr_keep_count: k = max(1, floor(n / cr)); 0 if n < 1 or cr < 1.  Host only.
+ *
+ * moe_sr_encode: expert, shared [dev][n] dtype in (16-byte aligned); values [dev][k] dtype
+ * and indices [dev][k] int32 out: the k entries with the largest |expert - shared| (float32
+ * difference of the stored values; equal magnitudes: lower index first), ordered by
+ * ascending index; values = that difference rounded to dtype.  1 <= k <= n.  Exact
+ * (radix select), deterministic.  Uses a workspace in the context that grows with the
+ * largest n seen (the growing call allocates and synchronises the device).
+ *
+ * moe_sr_decode: shared [dev][n] in, values/indices [dev][k] in (indices ascending, in
+ * [0, n)), expert_out [dev][n] out (16-byte aligned, must not alias shared):
+ * expert_out[i] = shared[i], except expert_out[indices[j]] = shared[indices[j]] + values[j]
+ * (float32 add, rounded once to dtype).  Entries with an index outside [0, n) or out of
+ * order may be ignored; nothing outside expert_out[0..n) is written. */
+int64_t moe_sr_keep_count(int64_t n, int32_t cr);
+int moe_sr_encode(moe_ctx* ctx, const void* expert, const void* shared, int64_t n, int64_t k,
+                  void* values, int32_t* indices, void* stream);
+int moe_sr_decode(moe_ctx* ctx, const void* shared, const void* values, const int32_t* indices,
+                  int64_t n, int64_t k, void* expert_out, void* stream);
+
 /* Measurement aid.  moe_profile_ffn(ctx, n_calls) makes the next n_calls calls of
  * moe_expert_ffn record HIP events on their stream around each internal launch
  * (n_calls = 0 switches it off and frees the events; creates events, so not for use

@@ -74,6 +74,13 @@ def load_library(build_if_missing: bool = True):
     for name in ("moe_plan_location", "moe_plan_comm_type", "moe_plan_comm_frequency",
                  "moe_plan_expert_dest_rank", "moe_plan_model"):
         getattr(lib, name).restype = c_int
+    I64 = ctypes.c_int64
+    lib.moe_sr_keep_count.argtypes = [I64, c_int32]
+    lib.moe_sr_keep_count.restype = I64
+    lib.moe_sr_encode.argtypes = [P, P, P, I64, I64, P, P, P]
+    lib.moe_sr_decode.argtypes = [P, P, P, P, I64, I64, P, P]
+    lib.moe_sr_encode.restype = c_int
+    lib.moe_sr_decode.restype = c_int
     lib.moe_profile_ffn.argtypes = [P, c_int32]
     lib.moe_profile_ffn_read.argtypes = [P, POINTER(c_float), POINTER(c_int32)]
     for name in ("moe_create", "moe_destroy", "moe_set_placement", "moe_set_ffn_path", "moe_route",
@@ -293,6 +300,33 @@ def moe_profile_ffn_read(ctx):
     _check(load_library().moe_profile_ffn_read(ctx.handle, ms, ctypes.byref(n)),
            "moe_profile_ffn_read")
     return [float(v) for v in ms], int(n.value)
+
+
+# ------------------------------------------------------------------ shared/residual compression
+def moe_sr_keep_count(n: int, cr: int) -> int:
+    return int(load_library().moe_sr_keep_count(n, cr))
+
+
+def moe_sr_encode(ctx, expert, shared, k: int, values=None, indices=None):
+    """expert, shared: device tensors of the context's dtype, same number of elements (taken
+    flat).  Returns (values [k], indices [k] int32)."""
+    n = expert.numel()
+    if values is None:
+        values = torch.empty(k, dtype=expert.dtype, device=expert.device)
+    if indices is None:
+        indices = torch.empty(k, dtype=torch.int32, device=expert.device)
+    _check(load_library().moe_sr_encode(ctx.handle, _ptr(expert), _ptr(shared), n, k, _ptr(values),
+                                        _ptr(indices), _stream()), "moe_sr_encode")
+    return values, indices
+
+
+def moe_sr_decode(ctx, shared, values, indices, out=None):
+    n, k = shared.numel(), values.numel()
+    if out is None:
+        out = torch.empty_like(shared)
+    _check(load_library().moe_sr_decode(ctx.handle, _ptr(shared), _ptr(values), _ptr(indices), n, k,
+                                        _ptr(out), _stream()), "moe_sr_decode")
+    return out
 
 
 # ------------------------------------------------------------------ planning (host only)

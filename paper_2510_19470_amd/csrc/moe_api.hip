@@ -30,6 +30,7 @@ void free_all(moe_ctx* c) {
   (void)hipFree(c->d_order_up);
   (void)hipFree(c->d_order_down);
   (void)hipFree(c->d_split_ws);
+  (void)hipFree(c->d_sr_ws);
   (void)hipFree(c->d_H);
   (void)hipFree(c->d_dG);
   (void)hipFree(c->d_dU);
@@ -208,6 +209,44 @@ int moe_profile_ffn_read(moe_ctx* c, float* ms, int32_t* n_recorded) {
   for (int i = 0; i < MOE_PROF_SLOTS; ++i) ms[i] /= (float)c->prof_n;
   c->prof_n = 0;
   return MOE_OK;
+}
+
+int64_t moe_sr_keep_count(int64_t n, int32_t cr) {
+  if (n < 1 || cr < 1) return 0;
+  const int64_t k = n / cr;
+  return k < 1 ? 1 : k;
+}
+
+int moe_sr_encode(moe_ctx* c, const void* expert, const void* shared, int64_t n, int64_t k,
+                  void* values, int32_t* indices, void* stream) {
+  if (c == nullptr || expert == nullptr || shared == nullptr || values == nullptr ||
+      indices == nullptr)
+    return MOE_EINVAL;
+  if (n < 1 || n > 0x7fffffffLL || k < 1 || k > n) return MOE_EINVAL;
+  if (!aligned16(expert) || !aligned16(shared)) return MOE_EINVAL;
+  const size_t need = sr_workspace_ints(n);
+  if (need > c->sr_ws_ints) {   // grow the workspace (synchronises: earlier calls may use it)
+    (void)hipFree(c->d_sr_ws);
+    c->d_sr_ws = nullptr;
+    c->sr_ws_ints = 0;
+    if (hipMalloc(reinterpret_cast<void**>(&c->d_sr_ws), need * sizeof(int32_t)) != hipSuccess) {
+      (void)hipGetLastError();
+      return MOE_ENOMEM;
+    }
+    if (hipMemset(c->d_sr_ws, 0, need * sizeof(int32_t)) != hipSuccess) return MOE_EHIP;
+    c->sr_ws_ints = need;
+  }
+  return launch_sr_encode(c, expert, shared, n, k, values, indices, (hipStream_t)stream);
+}
+
+int moe_sr_decode(moe_ctx* c, const void* shared, const void* values, const int32_t* indices,
+                  int64_t n, int64_t k, void* expert_out, void* stream) {
+  if (c == nullptr || shared == nullptr || values == nullptr || indices == nullptr ||
+      expert_out == nullptr)
+    return MOE_EINVAL;
+  if (n < 1 || n > 0x7fffffffLL || k < 1 || k > n) return MOE_EINVAL;
+  if (!aligned16(shared) || !aligned16(expert_out) || shared == expert_out) return MOE_EINVAL;
+  return launch_sr_decode(c, shared, values, indices, n, k, expert_out, (hipStream_t)stream);
 }
 
 int moe_destroy(moe_ctx* c) {

@@ -77,6 +77,9 @@ struct moe_ctx {
   int32_t* d_koff;        // [E+1] padded row offsets of the experts in d_actT
   void* d_wT;             // transposed weights of the MFMA backward
   size_t wT_experts;      // experts d_wT has room for
+  // shared/residual compression: selection state, histogram, per-chunk counts
+  int32_t* d_sr_ws;
+  size_t sr_ws_ints;      // capacity of d_sr_ws
   // optional HIP-event timing of the internal launches of moe_expert_ffn
   int prof_calls;         // capacity in calls (0 = off)
   int prof_n;             // calls recorded so far
@@ -124,6 +127,11 @@ bool ffn_bwd_mfma_supported(const moe_ctx* c);
 int ffn_bwd_ktot(const moe_ctx* c);
 int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* G, const void* U,
                         const int32_t* counts, const int32_t* offsets, void* dxp, hipStream_t s);
+size_t sr_workspace_ints(int64_t n);
+int launch_sr_encode(moe_ctx* c, const void* W, const void* S, int64_t n, int64_t k, void* values,
+                     int32_t* indices, hipStream_t s);
+int launch_sr_decode(moe_ctx* c, const void* S, const void* values, const int32_t* indices,
+                     int64_t n, int64_t k, void* out, hipStream_t s);
 int launch_ffn_bwd_generic(moe_ctx* c, const void* dy, const void* xp, const void* G,
                            const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
                            void* dG_tmp, void* dU_tmp, void* H_tmp, hipStream_t s);

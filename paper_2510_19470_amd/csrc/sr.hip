@@ -1,0 +1,457 @@
+// Shared/residual expert compression (paper Sec. 4.2 "SR-Based Expert Compression",
+// Fig. "SRexpert"(b); compression ratio: Sec. 5.4).
+//
+//   encode: residual = expert - shared expert (float32); keep the k entries of largest
+//           magnitude (equal magnitudes: lower index first) as a value-index list in
+//           ascending index order, values rounded to the storage type;
+//   decode: expert' = shared + scattered residual, one pass.
+//
+// The selection is exact.  The magnitude of a float32 is monotone in its low 31 bits, so the
+// k-th largest magnitude is found by a radix select over that 31-bit key: three histogram
+// passes (12 + 12 + 7 bits, LDS-private histograms added to a global one with integer
+// atomics, so the result does not depend on the order), each followed by a one-block kernel
+// that picks the bin holding the k-th largest.  A fourth pass counts, per chunk of 8192
+// elements, the keys above the threshold and the keys equal to it; a one-block scan turns
+// the counts into output positions (of the equal keys only the first k - #above in index
+// order are taken); a fifth pass writes the list.  Every pass re-reads expert and shared
+// (2 x 5 reads per element): the kernels are HBM-bound, nothing but the output is written.
+#include "moe_internal.h"
+#include "numeric.h"
+
+#include <algorithm>
+
+namespace {
+
+constexpr int SR_THREADS = 512;
+constexpr int SR_PER_THREAD = 16;
+constexpr int SR_CHUNK = SR_THREADS * SR_PER_THREAD;  // 8192 elements per block iteration
+constexpr int SR_BINS = 4096;
+
+struct SrState {          // device-side selection state
+  uint32_t prefix;        // key bits fixed so far (right-aligned)
+  int32_t k_rem;          // entries still to take among the keys that match the prefix
+};
+
+template <typename T>
+__device__ __forceinline__ uint32_t sr_key(T w, T s, float* r) {
+  *r = to_f32(w) - to_f32(s);
+  return __float_as_uint(*r) & 0x7fffffffu;
+}
+
+// The 16 consecutive elements of one thread: element base + j for j < 16, or fewer at the
+// end of the array (keys of missing elements are never used: `cnt` says how many exist).
+template <typename T>
+struct SrLane {
+  float r[SR_PER_THREAD];
+  uint32_t key[SR_PER_THREAD];
+  int cnt;
+  __device__ __forceinline__ void load(const T* __restrict__ W, const T* __restrict__ S,
+                                       int64_t base, int64_t n) {
+    cnt = (int)max((int64_t)0, min((int64_t)SR_PER_THREAD, n - base));
+    if (cnt == SR_PER_THREAD) {
+      constexpr int V = 16 / sizeof(T);           // elements per 16-byte vector
+      constexpr int NV = SR_PER_THREAD / V;
+      uint4 wq[NV], sq[NV];
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        wq[v] = reinterpret_cast<const uint4*>(W + base)[v];
+        sq[v] = reinterpret_cast<const uint4*>(S + base)[v];
+      }
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        float wf[V], sf[V];
+        Vec16<T>::unpack(wq[v], wf);
+        Vec16<T>::unpack(sq[v], sf);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          r[v * V + e] = wf[e] - sf[e];
+          key[v * V + e] = __float_as_uint(r[v * V + e]) & 0x7fffffffu;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < SR_PER_THREAD; ++j) {
+        r[j] = 0.f;
+        key[j] = 0;
+        if (j < cnt) key[j] = sr_key(W[base + j], S[base + j], &r[j]);
+      }
+    }
+  }
+};
+
+// PASS 0: bin = key[30:19];  PASS 1: keys with key[30:19] == prefix, bin = key[18:7];
+// PASS 2: keys with key[30:7] == prefix, bin = key[6:0].
+template <typename T, int PASS>
+__global__ __launch_bounds__(SR_THREADS) void sr_hist_kernel(const T* __restrict__ W,
+                                                             const T* __restrict__ S, int64_t n,
+                                                             const SrState* __restrict__ st,
+                                                             int32_t* __restrict__ hist) {
+  __shared__ int32_t h[SR_BINS];
+  for (int i = threadIdx.x; i < SR_BINS; i += SR_THREADS) h[i] = 0;
+  __syncthreads();
+  const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
+  const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    SrLane<T> L;
+    L.load(W, S, c * SR_CHUNK + (int64_t)threadIdx.x * SR_PER_THREAD, n);
+#pragma unroll
+    for (int j = 0; j < SR_PER_THREAD; ++j) {
+      if (j >= L.cnt) break;
+      const uint32_t key = L.key[j];
+      if (PASS == 0) atomicAdd(&h[key >> 19], 1);
+      else if (PASS == 1) { if ((key >> 19) == prefix) atomicAdd(&h[(key >> 7) & 0xfffu], 1); }
+      else { if ((key >> 7) == prefix) atomicAdd(&h[key & 0x7fu], 1); }
+    }
+  }
+  __syncthreads();
+  constexpr int NB = PASS == 2 ? 128 : SR_BINS;
+  for (int i = threadIdx.x; i < NB; i += SR_THREADS)
+    if (h[i] != 0) atomicAdd(&hist[i], h[i]);
+}
+
+// One block: the bin b with  #(keys in bins > b) < k_rem <= #(keys in bins >= b)  is the one
+// that holds the k_rem-th largest key; it is appended to the prefix, k_rem loses the keys
+// above it, and the histogram is cleared for the next pass.
+template <int PASS>
+__global__ __launch_bounds__(1024) void sr_pick_kernel(SrState* __restrict__ st,
+                                                       int32_t* __restrict__ hist, int32_t k) {
+  constexpr int NB = PASS == 2 ? 128 : SR_BINS;
+  constexpr int BITS = PASS == 2 ? 7 : 12;
+  __shared__ int32_t suf[SR_BINS + 1];   // suf[b] = sum of hist[b..NB-1]
+  const int tid = threadIdx.x;
+  // each thread sums 4 consecutive bins (or fewer), then a suffix scan over the 1024 partials
+  __shared__ int32_t part[1024];
+  int local[4] = {0, 0, 0, 0};
+  int s4 = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int b = tid * 4 + j;
+    local[j] = b < NB ? hist[b] : 0;
+    s4 += local[j];
+  }
+  part[tid] = s4;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {   // inclusive suffix scan
+    int v = 0;
+    if (tid + off < 1024) v = part[tid + off];
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  int run = tid + 1 < 1024 ? part[tid + 1] : 0;  // keys in the bins above this thread's four
+#pragma unroll
+  for (int j = 3; j >= 0; --j) {
+    const int b = tid * 4 + j;
+    run += local[j];
+    if (b < NB) suf[b] = run;
+  }
+  if (tid == 0) suf[NB] = 0;
+  __syncthreads();
+  const int32_t k_rem = PASS == 0 ? k : st->k_rem;
+  const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
+  __syncthreads();
+  for (int b = tid; b < NB; b += 1024)
+    if (suf[b + 1] < k_rem && k_rem <= suf[b]) {   // exactly one b satisfies this
+      st->prefix = (prefix << BITS) | (uint32_t)b;
+      st->k_rem = k_rem - suf[b + 1];
+    }
+  for (int b = tid; b < SR_BINS; b += 1024) hist[b] = 0;
+}
+
+// Per chunk: keys above the threshold, keys equal to it.
+template <typename T>
+__global__ __launch_bounds__(SR_THREADS) void sr_count_kernel(const T* __restrict__ W,
+                                                              const T* __restrict__ S, int64_t n,
+                                                              const SrState* __restrict__ st,
+                                                              int32_t* __restrict__ cnt_gt,
+                                                              int32_t* __restrict__ cnt_eq) {
+  __shared__ int32_t red[2][SR_THREADS / 64];
+  const uint32_t thr = st->prefix;
+  const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    SrLane<T> L;
+    L.load(W, S, c * SR_CHUNK + (int64_t)threadIdx.x * SR_PER_THREAD, n);
+    int gt = 0, eq = 0;
+#pragma unroll
+    for (int j = 0; j < SR_PER_THREAD; ++j) {
+      if (j < L.cnt) {
+        gt += L.key[j] > thr;
+        eq += L.key[j] == thr;
+      }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      gt += __shfl_xor(gt, off, 64);
+      eq += __shfl_xor(eq, off, 64);
+    }
+    if (lane == 0) {
+      red[0][wave] = gt;
+      red[1][wave] = eq;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int g = 0, e = 0;
+      for (int w = 0; w < SR_THREADS / 64; ++w) {
+        g += red[0][w];
+        e += red[1][w];
+      }
+      cnt_gt[c] = g;
+      cnt_eq[c] = e;
+    }
+    __syncthreads();
+  }
+}
+
+// One block: exclusive prefix of the equal-key counts, entries each chunk emits (all of its
+// keys above the threshold plus its share of the first k_rem equal keys), exclusive prefix
+// of those.  Chunks are walked in order, 1024 at a time.
+__global__ __launch_bounds__(1024) void sr_scan_kernel(const SrState* __restrict__ st,
+                                                       const int32_t* __restrict__ cnt_gt,
+                                                       const int32_t* __restrict__ cnt_eq,
+                                                       int64_t n_chunks,
+                                                       int32_t* __restrict__ eq_prefix,
+                                                       int32_t* __restrict__ out_prefix) {
+  __shared__ int32_t sc[1024];
+  __shared__ int32_t carry[2];
+  const int tid = threadIdx.x;
+  if (tid == 0) {
+    carry[0] = 0;
+    carry[1] = 0;
+  }
+  __syncthreads();
+  const int32_t need_eq = st->k_rem;
+  for (int64_t base = 0; base < n_chunks; base += 1024) {
+    const int64_t c = base + tid;
+    const int eq = c < n_chunks ? cnt_eq[c] : 0;
+    const int gt = c < n_chunks ? cnt_gt[c] : 0;
+    // exclusive scan of eq
+    sc[tid] = eq;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+      int v = 0;
+      if (tid >= off) v = sc[tid - off];
+      __syncthreads();
+      sc[tid] += v;
+      __syncthreads();
+    }
+    const int eq_before = carry[0] + sc[tid] - eq;
+    const int eq_total = carry[0] + sc[1023];
+    __syncthreads();
+    const int take = gt + max(0, min(eq, need_eq - eq_before));
+    sc[tid] = take;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+      int v = 0;
+      if (tid >= off) v = sc[tid - off];
+      __syncthreads();
+      sc[tid] += v;
+      __syncthreads();
+    }
+    if (c < n_chunks) {
+      eq_prefix[c] = eq_before;
+      out_prefix[c] = carry[1] + sc[tid] - take;
+    }
+    const int out_total = carry[1] + sc[1023];
+    __syncthreads();
+    if (tid == 0) {
+      carry[0] = eq_total;
+      carry[1] = out_total;
+    }
+    __syncthreads();
+  }
+}
+
+// Writes the value-index list: a chunk's entries go to out_prefix[chunk] + rank inside the
+// chunk (thread order = index order: a thread owns 16 consecutive elements).
+template <typename T>
+__global__ __launch_bounds__(SR_THREADS) void sr_emit_kernel(
+    const T* __restrict__ W, const T* __restrict__ S, int64_t n, const SrState* __restrict__ st,
+    const int32_t* __restrict__ eq_prefix, const int32_t* __restrict__ out_prefix, int64_t k,
+    T* __restrict__ values, int32_t* __restrict__ indices) {
+  __shared__ int32_t wsum[2][SR_THREADS / 64];
+  const uint32_t thr = st->prefix;
+  const int32_t need_eq = st->k_rem;
+  const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const int64_t base = c * SR_CHUNK + (int64_t)threadIdx.x * SR_PER_THREAD;
+    SrLane<T> L;
+    L.load(W, S, base, n);
+    // rank of this thread's first equal key among the chunk's equal keys
+    int eq = 0;
+#pragma unroll
+    for (int j = 0; j < SR_PER_THREAD; ++j)
+      if (j < L.cnt) eq += L.key[j] == thr;
+    int incl = eq;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int v = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += v;
+    }
+    if (lane == 63) wsum[0][wave] = incl;
+    __syncthreads();
+    int eq_rank = eq_prefix[c] + incl - eq;
+    for (int w = 0; w < wave; ++w) eq_rank += wsum[0][w];
+    // selection flags and this thread's count
+    uint32_t sel = 0;
+    int taken = 0;
+#pragma unroll
+    for (int j = 0; j < SR_PER_THREAD; ++j) {
+      if (j < L.cnt) {
+        bool s = L.key[j] > thr;
+        if (L.key[j] == thr) {
+          s = eq_rank < need_eq;
+          ++eq_rank;
+        }
+        if (s) {
+          sel |= 1u << j;
+          ++taken;
+        }
+      }
+    }
+    int incl2 = taken;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int v = __shfl_up(incl2, off, 64);
+      if (lane >= off) incl2 += v;
+    }
+    if (lane == 63) wsum[1][wave] = incl2;
+    __syncthreads();
+    int64_t pos = (int64_t)out_prefix[c] + incl2 - taken;
+    for (int w = 0; w < wave; ++w) pos += wsum[1][w];
+#pragma unroll
+    for (int j = 0; j < SR_PER_THREAD; ++j)
+      if ((sel >> j) & 1u) {
+        if (pos < k) {   // always true when the counts are consistent
+          values[pos] = from_f32<T>(L.r[j]);
+          indices[pos] = (int32_t)(base + j);
+        }
+        ++pos;
+      }
+    __syncthreads();
+  }
+}
+
+// Decode: out = shared, plus the residual where the list has an entry.  A block stages the
+// entries of its chunk (a contiguous piece of the ascending list, found by binary search)
+// in LDS as float32 plus a presence flag, so that untouched elements keep the shared
+// expert's exact bits.
+template <typename T>
+__global__ __launch_bounds__(SR_THREADS) void sr_decode_kernel(
+    const T* __restrict__ S, const T* __restrict__ values, const int32_t* __restrict__ indices,
+    int64_t n, int64_t k, T* __restrict__ out) {
+  __shared__ float res[SR_CHUNK];
+  __shared__ uint8_t has[SR_CHUNK];
+  __shared__ int64_t range[2];
+  const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const int64_t start = c * SR_CHUNK, end = min(n, start + SR_CHUNK);
+    if (threadIdx.x < 2) {   // lower_bound of start / end in the ascending index list
+      const int64_t target = threadIdx.x == 0 ? start : end;
+      int64_t lo = 0, hi = k;
+      while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)indices[mid] < target) lo = mid + 1; else hi = mid;
+      }
+      range[threadIdx.x] = lo;
+    }
+    for (int i = threadIdx.x; i < SR_CHUNK / 4; i += SR_THREADS)
+      reinterpret_cast<uint32_t*>(has)[i] = 0;
+    __syncthreads();
+    for (int64_t e = range[0] + threadIdx.x; e < range[1]; e += SR_THREADS) {
+      const int64_t i = (int64_t)indices[e] - start;
+      if (i >= 0 && i < SR_CHUNK) {   // the list is the caller's: stay inside the chunk
+        res[i] = to_f32(values[e]);
+        has[i] = 1;
+      }
+    }
+    __syncthreads();
+    const int64_t base = start + (int64_t)threadIdx.x * SR_PER_THREAD;
+    const int cnt = (int)max((int64_t)0, min((int64_t)SR_PER_THREAD, n - base));
+    const int l0 = threadIdx.x * SR_PER_THREAD;
+    if (cnt == SR_PER_THREAD) {
+      constexpr int V = 16 / sizeof(T);
+      constexpr int NV = SR_PER_THREAD / V;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        uint4 q = reinterpret_cast<const uint4*>(S + base)[v];
+        bool any = false;
+#pragma unroll
+        for (int e = 0; e < V; ++e) any |= has[l0 + v * V + e] != 0;
+        if (any) {
+          float f[V];
+          Vec16<T>::unpack(q, f);
+          T o[V];
+          const T* raw = reinterpret_cast<const T*>(&q);
+#pragma unroll
+          for (int e = 0; e < V; ++e)
+            o[e] = has[l0 + v * V + e] ? from_f32<T>(f[e] + res[l0 + v * V + e]) : raw[e];
+          __builtin_memcpy(&q, o, 16);
+        }
+        reinterpret_cast<uint4*>(out + base)[v] = q;
+      }
+    } else {
+      for (int j = 0; j < cnt; ++j) {
+        const T s = S[base + j];
+        out[base + j] = has[l0 + j] ? from_f32<T>(to_f32(s) + res[l0 + j]) : s;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+template <typename T>
+int encode_t(moe_ctx* c, const T* W, const T* S, int64_t n, int64_t k, T* values, int32_t* indices,
+             hipStream_t s) {
+  const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
+  const int grid = (int)std::min<int64_t>(n_chunks, (int64_t)c->n_cu * 8);
+  SrState* st = reinterpret_cast<SrState*>(c->d_sr_ws);
+  int32_t* hist = c->d_sr_ws + 4;
+  int32_t* cnt_gt = hist + SR_BINS;
+  int32_t* cnt_eq = cnt_gt + n_chunks;
+  int32_t* eq_prefix = cnt_eq + n_chunks;
+  int32_t* out_prefix = eq_prefix + n_chunks;
+  // the histogram is zero on entry: cleared at allocation and by every pick kernel
+  hipLaunchKernelGGL((sr_hist_kernel<T, 0>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
+  hipLaunchKernelGGL((sr_pick_kernel<0>), dim3(1), dim3(1024), 0, s, st, hist, (int32_t)k);
+  hipLaunchKernelGGL((sr_hist_kernel<T, 1>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
+  hipLaunchKernelGGL((sr_pick_kernel<1>), dim3(1), dim3(1024), 0, s, st, hist, (int32_t)k);
+  hipLaunchKernelGGL((sr_hist_kernel<T, 2>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
+  hipLaunchKernelGGL((sr_pick_kernel<2>), dim3(1), dim3(1024), 0, s, st, hist, (int32_t)k);
+  hipLaunchKernelGGL((sr_count_kernel<T>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, cnt_gt,
+                     cnt_eq);
+  hipLaunchKernelGGL(sr_scan_kernel, dim3(1), dim3(1024), 0, s, st, cnt_gt, cnt_eq, n_chunks,
+                     eq_prefix, out_prefix);
+  hipLaunchKernelGGL((sr_emit_kernel<T>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, eq_prefix,
+                     out_prefix, k, values, indices);
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+}
+
+}  // namespace
+
+size_t sr_workspace_ints(int64_t n) {
+  const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
+  return (size_t)(4 + SR_BINS + 4 * n_chunks);
+}
+
+int launch_sr_encode(moe_ctx* c, const void* W, const void* S, int64_t n, int64_t k, void* values,
+                     int32_t* indices, hipStream_t s) {
+  if (c->cfg.dtype == MOE_BF16)
+    return encode_t<uint16_t>(c, (const uint16_t*)W, (const uint16_t*)S, n, k, (uint16_t*)values,
+                              indices, s);
+  return encode_t<float>(c, (const float*)W, (const float*)S, n, k, (float*)values, indices, s);
+}
+
+int launch_sr_decode(moe_ctx* c, const void* S, const void* values, const int32_t* indices,
+                     int64_t n, int64_t k, void* out, hipStream_t s) {
+  const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
+  const int grid = (int)std::min<int64_t>(n_chunks, (int64_t)c->n_cu * 8);
+  if (c->cfg.dtype == MOE_BF16)
+    hipLaunchKernelGGL((sr_decode_kernel<uint16_t>), dim3(grid), dim3(SR_THREADS), 0, s,
+                       (const uint16_t*)S, (const uint16_t*)values, indices, n, k, (uint16_t*)out);
+  else
+    hipLaunchKernelGGL((sr_decode_kernel<float>), dim3(grid), dim3(SR_THREADS), 0, s,
+                       (const float*)S, (const float*)values, indices, n, k, (float*)out);
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+}

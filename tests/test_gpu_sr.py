@@ -1,0 +1,118 @@
+"""GPU parity of the shared/residual compression kernels against the oracle
+(paper Sec. 4.2): indices bit-exact, values and decoded weights bit-exact (the float32
+subtraction / addition and the rounding are the same operations on both sides)."""
+import numpy as np
+import pytest
+import torch
+
+import moe_workloads as wl
+import paper_2510_19470_amd as moe
+from oracle import sr_oracle as sr
+from gpu_common import to_device, to_host_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def _ctx(dtype):
+    return moe.moe_create(T_max=64, d=64, E=8, k=2, f=64, R=2, local_rank=0,
+                          dtype=moe.MOE_BF16 if dtype == "bf16" else moe.MOE_F32, renormalize=1)
+
+
+def _run(shape, seed, dtype, k, ties=False, ctx=None):
+    shared, experts = wl.make_sr_inputs(shape, seed, dtype, n_experts=1, ties=ties)
+    expert = experts[0]
+    own = ctx is None
+    ctx = ctx or _ctx(dtype)
+    dS, dW = to_device(shared, dtype), to_device(expert, dtype)
+    vals, idx = moe.moe_sr_encode(ctx, dW, dS, k)
+    out = moe.moe_sr_decode(ctx, dS, vals, idx)
+    torch.cuda.synchronize()
+    ovals, oidx = sr.sr_encode(expert, shared, k, dtype)
+    oout = sr.sr_decode(shared, ovals, oidx, dtype)
+    assert np.array_equal(idx.cpu().numpy(), oidx)
+    assert np.array_equal(to_host_bits(vals), ovals.view(np.uint16 if dtype == "bf16" else np.uint32))
+    assert np.array_equal(to_host_bits(out).ravel(),
+                          oout.ravel().view(np.uint16 if dtype == "bf16" else np.uint32))
+    if own:
+        moe.moe_destroy(ctx)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape,k", [((8, 16), 1), ((8, 16), 128), ((96, 200), 384),
+                                     ((257, 1031), 5299), ((1024, 2048), 41943)])
+def test_encode_decode_match_oracle(dtype, shape, k):
+    _run(shape, 31, dtype, k)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_many_equal_magnitudes(dtype):
+    # residuals quantised to a coarse grid: the threshold bin holds many equal keys and the
+    # tie rule (lower index first) decides
+    _run((300, 517), 32, dtype, wl_keep((300, 517)), ties=True)
+    _run((300, 517), 33, dtype, 300 * 517 // 3, ties=True)
+
+
+def wl_keep(shape):
+    return sr.keep_count(shape[0] * shape[1], 50)
+
+
+def test_identical_expert_and_shared():
+    # every residual is zero: the first k indices are kept, decode returns the shared expert
+    dtype = "bf16"
+    shared, _ = wl.make_sr_inputs((64, 130), 34, dtype, n_experts=1)
+    ctx = _ctx(dtype)
+    dS = to_device(shared, dtype)
+    vals, idx = moe.moe_sr_encode(ctx, dS.clone(), dS, 100)
+    out = moe.moe_sr_decode(ctx, dS, vals, idx)
+    torch.cuda.synchronize()
+    assert idx.cpu().tolist() == list(range(100))
+    assert np.array_equal(to_host_bits(out), shared.view(np.uint16))
+    moe.moe_destroy(ctx)
+
+
+def test_workspace_grows_and_calls_repeat():
+    ctx = _ctx("bf16")
+    for shape, seed in (((64, 64), 40), ((512, 1024), 41), ((64, 64), 42), ((512, 1024), 41)):
+        _run(shape, seed, "bf16", wl_keep(shape), ctx=ctx)
+    moe.moe_destroy(ctx)
+
+
+def test_full_size_expert_matrix_sampled_properties():
+    """One Mixtral-size matrix (14336 x 4096, CR = 50): the oracle's selection needs a sort of
+    58.7 M keys (~10 s), so the check is by properties that hold at any size plus an exact
+    comparison of the threshold computed with numpy.partition."""
+    dtype = "bf16"
+    rows, cols = 14336, 4096
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    S = (torch.randn(rows, cols, device="cuda", generator=g) / 64).to(torch.bfloat16)
+    R = torch.randn(rows, cols, device="cuda", generator=g) * (0.05 / 64)
+    big = torch.rand(rows, cols, device="cuda", generator=g) < 0.02
+    R = R + big * torch.randn(rows, cols, device="cuda", generator=g) / 64
+    W = (S.float() + R).to(torch.bfloat16)
+    del R, big
+    n = rows * cols
+    k = sr.keep_count(n, 50)
+    ctx = _ctx(dtype)
+    vals, idx = moe.moe_sr_encode(ctx, W, S, k)
+    out = moe.moe_sr_decode(ctx, S, vals, idx)
+    torch.cuda.synchronize()
+    res = (W.float() - S.float()).flatten()
+    mag = res.abs().cpu().numpy()
+    idx_h = idx.cpu().numpy().astype(np.int64)
+    assert idx_h.shape == (k,) and np.all(np.diff(idx_h) > 0) and idx_h[0] >= 0 and idx_h[-1] < n
+    thr = np.partition(mag, n - k)[n - k]          # k-th largest magnitude
+    kept = np.zeros(n, bool); kept[idx_h] = True
+    assert mag[kept].min() == thr and mag[~kept].max() <= thr
+    # equal-to-threshold entries: exactly the lowest indices are kept
+    eq = np.flatnonzero(mag == thr)
+    n_eq_kept = int(kept[eq].sum())
+    assert np.array_equal(eq[:n_eq_kept], eq[kept[eq]])
+    # values and decode, on all kept entries and a sample of dropped ones
+    v = to_host_bits(vals)
+    assert np.array_equal(v, sr.f32_to_bf16_rne(res.cpu().numpy()[idx_h]))
+    o = to_host_bits(out).ravel()
+    s_bits = to_host_bits(S).ravel()
+    want = sr.f32_to_bf16_rne(sr.bf16_to_f32(s_bits[idx_h]) + sr.bf16_to_f32(v))
+    assert np.array_equal(o[idx_h], want)
+    assert np.array_equal(o[~kept], s_bits[~kept])
+    moe.moe_destroy(ctx)
