@@ -66,6 +66,49 @@ def cpu_baseline(cfg, inp, sample_tokens: int):
                       f"resident experts only, {dt:.2f} s"}
 
 
+def sr_compression_bench(ctx, rows: int, cols: int, cr: int = 50, reps: int = 10):
+    """Shared/residual expert compression (paper Sec. 4.2) on one weight matrix of the
+    workload's expert shape: encode and decode timed with events, outside the timed steps.
+    Synthetic weights drawn on the device: shared ~ N(0, 1/cols); residual = a dense part of
+    5 % of that scale plus, on 2 % of the entries, a part of the full scale."""
+    import torch
+    import paper_2510_19470_amd as moe
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4242)
+    sd = cols ** -0.5
+    S = (torch.randn(rows, cols, device="cuda", generator=g) * sd).to(torch.bfloat16)
+    R = torch.randn(rows, cols, device="cuda", generator=g) * (0.05 * sd)
+    big = torch.rand(rows, cols, device="cuda", generator=g) < 0.02
+    R = R + big * (torch.randn(rows, cols, device="cuda", generator=g) * sd)
+    W = (S.float() + R).to(torch.bfloat16)
+    del R, big
+    n = rows * cols
+    k = moe.moe_sr_keep_count(n, cr)
+    vals, idx = moe.moe_sr_encode(ctx, W, S, k)
+    out = moe.moe_sr_decode(ctx, S, vals, idx)
+
+    def timed(fn):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    t_enc = timed(lambda: moe.moe_sr_encode(ctx, W, S, k, vals, idx))
+    t_dec = timed(lambda: moe.moe_sr_decode(ctx, S, vals, idx, out))
+    by_enc = 2 * n * 2 + k * 6          # expert + shared read once, list written
+    by_dec = 2 * n * 2 + k * 6          # shared read, expert written, list read
+    return {"matrix": f"{rows}x{cols} bf16", "cr": cr, "kept": int(k),
+            "encode_ms": t_enc, "decode_ms": t_dec,
+            "encode_algorithmic_gbs": by_enc / (t_enc * 1e-3) / 1e9,
+            "encode_streamed_gbs": (5 * 2 * n * 2 + k * 6) / (t_enc * 1e-3) / 1e9,
+            "decode_gbs": by_dec / (t_dec * 1e-3) / 1e9,
+            "decode_frac_of_hbm_peak": by_dec / (t_dec * 1e-3) / 1e9 / PEAK_HBM_GBS}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +119,9 @@ def main() -> int:
     ap.add_argument("--cpu-sample-tokens", type=int, default=0,
                     help="tokens of the oracle baseline sample (0 = sized for ~10-30 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sr", action="store_true",
+                    help="skip the shared/residual compression measurement (one expert matrix, "
+                         "outside the timed steps)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -243,6 +289,8 @@ def main() -> int:
         "call_ms": call_ms,
         "input_generation_s": t_gen,
     }
+    if mfma and not args.no_sr:
+        rec["sr_compression"] = sr_compression_bench(lay.ctx, f, d)
     if not args.no_cpu_baseline:
         flops_tok = 6.0 * d * f * k * (3 if cfg.backward else 1) + 2.0 * d * E
         sample = args.cpu_sample_tokens or int(max(16, min(cfg.T, 4e12 / flops_tok / 4)))

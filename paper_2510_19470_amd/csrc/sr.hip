@@ -8,7 +8,7 @@
 //
 // The selection is exact.  The magnitude of a float32 is monotone in its low 31 bits, so the
 // k-th largest magnitude is found by a radix select over that 31-bit key: three histogram
-// passes (12 + 12 + 7 bits, LDS-private histograms added to a global one with integer
+// passes (12 + 12 + 7 bits, LDS-private histograms added to 16 global copies with integer
 // atomics, so the result does not depend on the order), each followed by a one-block kernel
 // that picks the bin holding the k-th largest.  A fourth pass counts, per chunk of 8192
 // elements, the keys above the threshold and the keys equal to it; a one-block scan turns
@@ -26,6 +26,7 @@ constexpr int SR_THREADS = 512;
 constexpr int SR_PER_THREAD = 16;
 constexpr int SR_CHUNK = SR_THREADS * SR_PER_THREAD;  // 8192 elements per block iteration
 constexpr int SR_BINS = 4096;
+constexpr int SR_REPL = 16;   // copies of the global histogram (fewer same-address atomics)
 
 struct SrState {          // device-side selection state
   uint32_t prefix;        // key bits fixed so far (right-aligned)
@@ -96,17 +97,20 @@ __global__ __launch_bounds__(SR_THREADS) void sr_hist_kernel(const T* __restrict
     L.load(W, S, c * SR_CHUNK + (int64_t)threadIdx.x * SR_PER_THREAD, n);
 #pragma unroll
     for (int j = 0; j < SR_PER_THREAD; ++j) {
-      if (j >= L.cnt) break;
       const uint32_t key = L.key[j];
-      if (PASS == 0) atomicAdd(&h[key >> 19], 1);
-      else if (PASS == 1) { if ((key >> 19) == prefix) atomicAdd(&h[(key >> 7) & 0xfffu], 1); }
-      else { if ((key >> 7) == prefix) atomicAdd(&h[key & 0x7fu], 1); }
+      bool hit = j < L.cnt;
+      int bin;
+      if (PASS == 0) bin = key >> 19;
+      else if (PASS == 1) { hit = hit && (key >> 19) == prefix; bin = (key >> 7) & 0xfffu; }
+      else { hit = hit && (key >> 7) == prefix; bin = key & 0x7fu; }
+      if (hit) atomicAdd(&h[bin], 1);
     }
   }
   __syncthreads();
   constexpr int NB = PASS == 2 ? 128 : SR_BINS;
+  int32_t* mine = hist + (blockIdx.x % SR_REPL) * SR_BINS;
   for (int i = threadIdx.x; i < NB; i += SR_THREADS)
-    if (h[i] != 0) atomicAdd(&hist[i], h[i]);
+    if (h[i] != 0) atomicAdd(&mine[i], h[i]);
 }
 
 // One block: the bin b with  #(keys in bins > b) < k_rem <= #(keys in bins >= b)  is the one
@@ -126,7 +130,8 @@ __global__ __launch_bounds__(1024) void sr_pick_kernel(SrState* __restrict__ st,
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int b = tid * 4 + j;
-    local[j] = b < NB ? hist[b] : 0;
+    if (b < NB)
+      for (int rp = 0; rp < SR_REPL; ++rp) local[j] += hist[rp * SR_BINS + b];
     s4 += local[j];
   }
   part[tid] = s4;
@@ -155,7 +160,7 @@ __global__ __launch_bounds__(1024) void sr_pick_kernel(SrState* __restrict__ st,
       st->prefix = (prefix << BITS) | (uint32_t)b;
       st->k_rem = k_rem - suf[b + 1];
     }
-  for (int b = tid; b < SR_BINS; b += 1024) hist[b] = 0;
+  for (int b = tid; b < SR_REPL * SR_BINS; b += 1024) hist[b] = 0;
 }
 
 // Per chunk: keys above the threshold, keys equal to it.
@@ -205,7 +210,8 @@ __global__ __launch_bounds__(SR_THREADS) void sr_count_kernel(const T* __restric
 
 // One block: exclusive prefix of the equal-key counts, entries each chunk emits (all of its
 // keys above the threshold plus its share of the first k_rem equal keys), exclusive prefix
-// of those.  Chunks are walked in order, 1024 at a time.
+// of those.  Every thread owns a contiguous run of chunks; the runs are chained by two
+// block-wide scans of the per-thread totals.
 __global__ __launch_bounds__(1024) void sr_scan_kernel(const SrState* __restrict__ st,
                                                        const int32_t* __restrict__ cnt_gt,
                                                        const int32_t* __restrict__ cnt_eq,
@@ -213,52 +219,38 @@ __global__ __launch_bounds__(1024) void sr_scan_kernel(const SrState* __restrict
                                                        int32_t* __restrict__ eq_prefix,
                                                        int32_t* __restrict__ out_prefix) {
   __shared__ int32_t sc[1024];
-  __shared__ int32_t carry[2];
   const int tid = threadIdx.x;
-  if (tid == 0) {
-    carry[0] = 0;
-    carry[1] = 0;
-  }
-  __syncthreads();
+  const int64_t per = (n_chunks + 1023) / 1024;
+  const int64_t c0 = min(n_chunks, tid * per), c1 = min(n_chunks, c0 + per);
   const int32_t need_eq = st->k_rem;
-  for (int64_t base = 0; base < n_chunks; base += 1024) {
-    const int64_t c = base + tid;
-    const int eq = c < n_chunks ? cnt_eq[c] : 0;
-    const int gt = c < n_chunks ? cnt_gt[c] : 0;
-    // exclusive scan of eq
-    sc[tid] = eq;
+  auto excl_scan = [&](int v) -> int {   // exclusive prefix of v over the block
+    sc[tid] = v;
     __syncthreads();
     for (int off = 1; off < 1024; off <<= 1) {
-      int v = 0;
-      if (tid >= off) v = sc[tid - off];
+      int t = 0;
+      if (tid >= off) t = sc[tid - off];
       __syncthreads();
-      sc[tid] += v;
-      __syncthreads();
-    }
-    const int eq_before = carry[0] + sc[tid] - eq;
-    const int eq_total = carry[0] + sc[1023];
-    __syncthreads();
-    const int take = gt + max(0, min(eq, need_eq - eq_before));
-    sc[tid] = take;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-      int v = 0;
-      if (tid >= off) v = sc[tid - off];
-      __syncthreads();
-      sc[tid] += v;
+      sc[tid] += t;
       __syncthreads();
     }
-    if (c < n_chunks) {
-      eq_prefix[c] = eq_before;
-      out_prefix[c] = carry[1] + sc[tid] - take;
-    }
-    const int out_total = carry[1] + sc[1023];
+    const int r = sc[tid] - v;
     __syncthreads();
-    if (tid == 0) {
-      carry[0] = eq_total;
-      carry[1] = out_total;
-    }
-    __syncthreads();
+    return r;
+  };
+  int eq_sum = 0;
+  for (int64_t c = c0; c < c1; ++c) eq_sum += cnt_eq[c];
+  int eq_before = excl_scan(eq_sum);
+  int take_sum = 0;
+  for (int64_t c = c0; c < c1; ++c) {
+    const int eq = cnt_eq[c];
+    eq_prefix[c] = eq_before;
+    take_sum += cnt_gt[c] + max(0, min(eq, need_eq - eq_before));
+    eq_before += eq;
+  }
+  int out_before = excl_scan(take_sum);
+  for (int64_t c = c0; c < c1; ++c) {
+    out_prefix[c] = out_before;
+    out_before += cnt_gt[c] + max(0, min(cnt_eq[c], need_eq - eq_prefix[c]));
   }
 }
 
@@ -347,14 +339,24 @@ __global__ __launch_bounds__(SR_THREADS) void sr_decode_kernel(
   const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
   for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
     const int64_t start = c * SR_CHUNK, end = min(n, start + SR_CHUNK);
-    if (threadIdx.x < 2) {   // lower_bound of start / end in the ascending index list
-      const int64_t target = threadIdx.x == 0 ? start : end;
+    if (threadIdx.x < 128) {   // lower_bound of start (wavefront 0) / end (wavefront 1) in
+      // the ascending index list, 64 probes per round (4 rounds for a million entries)
+      const int lane = threadIdx.x & 63;
+      const int64_t target = threadIdx.x < 64 ? start : end;
       int64_t lo = 0, hi = k;
-      while (lo < hi) {
-        const int64_t mid = (lo + hi) >> 1;
-        if ((int64_t)indices[mid] < target) lo = mid + 1; else hi = mid;
+      while (hi > lo) {
+        const int64_t stride = (hi - lo + 63) / 64;
+        const int64_t pos = lo + lane * stride;
+        const bool below = pos < hi && (int64_t)indices[pos] < target;
+        const int m = __popcll(__ballot(below));   // probes 0..m-1 are below the target
+        if (m == 0) {
+          hi = lo;
+        } else {
+          hi = min(hi, lo + m * stride);           // probe m (if any) is not below
+          lo = lo + (m - 1) * stride + 1;
+        }
       }
-      range[threadIdx.x] = lo;
+      if (lane == 0) range[threadIdx.x >> 6] = lo;
     }
     for (int i = threadIdx.x; i < SR_CHUNK / 4; i += SR_THREADS)
       reinterpret_cast<uint32_t*>(has)[i] = 0;
@@ -408,16 +410,17 @@ int encode_t(moe_ctx* c, const T* W, const T* S, int64_t n, int64_t k, T* values
   const int grid = (int)std::min<int64_t>(n_chunks, (int64_t)c->n_cu * 8);
   SrState* st = reinterpret_cast<SrState*>(c->d_sr_ws);
   int32_t* hist = c->d_sr_ws + 4;
-  int32_t* cnt_gt = hist + SR_BINS;
+  int32_t* cnt_gt = hist + SR_REPL * SR_BINS;
   int32_t* cnt_eq = cnt_gt + n_chunks;
   int32_t* eq_prefix = cnt_eq + n_chunks;
   int32_t* out_prefix = eq_prefix + n_chunks;
   // the histogram is zero on entry: cleared at allocation and by every pick kernel
-  hipLaunchKernelGGL((sr_hist_kernel<T, 0>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
+  const int hgrid = (int)std::min<int64_t>(n_chunks, (int64_t)c->n_cu * 2);
+  hipLaunchKernelGGL((sr_hist_kernel<T, 0>), dim3(hgrid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
   hipLaunchKernelGGL((sr_pick_kernel<0>), dim3(1), dim3(1024), 0, s, st, hist, (int32_t)k);
-  hipLaunchKernelGGL((sr_hist_kernel<T, 1>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
+  hipLaunchKernelGGL((sr_hist_kernel<T, 1>), dim3(hgrid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
   hipLaunchKernelGGL((sr_pick_kernel<1>), dim3(1), dim3(1024), 0, s, st, hist, (int32_t)k);
-  hipLaunchKernelGGL((sr_hist_kernel<T, 2>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
+  hipLaunchKernelGGL((sr_hist_kernel<T, 2>), dim3(hgrid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
   hipLaunchKernelGGL((sr_pick_kernel<2>), dim3(1), dim3(1024), 0, s, st, hist, (int32_t)k);
   hipLaunchKernelGGL((sr_count_kernel<T>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, cnt_gt,
                      cnt_eq);
@@ -432,7 +435,7 @@ int encode_t(moe_ctx* c, const T* W, const T* S, int64_t n, int64_t k, T* values
 
 size_t sr_workspace_ints(int64_t n) {
   const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
-  return (size_t)(4 + SR_BINS + 4 * n_chunks);
+  return (size_t)(4 + SR_REPL * SR_BINS + 4 * n_chunks);
 }
 
 int launch_sr_encode(moe_ctx* c, const void* W, const void* S, int64_t n, int64_t k, void* values,
