@@ -28,7 +28,7 @@ definition written out, in float64 by default.  Steps:
   O7 pack_rows        x_packed[row] = x[token of the slot stored in that row]
   O8 expert_ffn       y = (silu(x W1^T) * (x W3^T)) W2^T per expert segment
   O9 combine          out[t] = sum_j w[t,j] y_packed[slot_to_row[t*k+j]]
-  O10 backward        of O9, O8, O7 (chain rule written out)
+  O10 backward        of O9, O8, O7 and of the gate O1-O3 (chain rule written out)
   layer_dense         the whole layer by its definition, without any packing
 
 Pins (tests/test_oracle_*.py): brute force in pure Python loops (oracle/brute.py),
@@ -197,6 +197,31 @@ def combine_bwd(dout: np.ndarray, y_packed: np.ndarray, slot_to_row: np.ndarray,
         dy[rows[:, j]] = topk_w[:, j].astype(dtype)[:, None] * do
         dw[:, j] = np.sum(do * y_packed[rows[:, j]].astype(dtype), axis=1)
     return dy, dw
+
+
+def route_bwd(x: np.ndarray, Wg: np.ndarray, logits: np.ndarray, idx: np.ndarray,
+              dw: np.ndarray, renormalize: bool = True, dtype=F64):
+    """O10d.  Backward of the gate (O1-O3) for a fixed selection (the Top-k choice is
+    piecewise constant, so it carries no gradient): with p = softmax of the logits over the
+    selected experts (renormalize) or over all E, w_j = p[idx_j] and
+        dlogits[t,e] = p_e * ( [e selected] dw_e  -  sum_j dw_j p[idx_j] )
+    (zero outside the selection when renormalizing); then the linear layer:
+        dWg = dlogits^T x,  dbias = sum_t dlogits[t],  dx = dlogits Wg.
+    Returns (dlogits [T,E], dWg [E,d], dbias [E], dx [T,d])."""
+    L = logits.astype(dtype)
+    T, E = L.shape
+    ii = idx.astype(np.int64)
+    mask = np.zeros((T, E), dtype=bool)
+    np.put_along_axis(mask, ii, True, axis=1)
+    z = np.where(mask, L, -np.inf) if renormalize else L
+    m = z.max(axis=1, keepdims=True)
+    p = np.exp(z - m)
+    p = p / p.sum(axis=1, keepdims=True)
+    dsel = np.zeros((T, E), dtype=dtype)
+    np.put_along_axis(dsel, ii, dw.astype(dtype), axis=1)
+    inner = np.sum(dsel * p, axis=1, keepdims=True)
+    dL = p * (dsel - inner)
+    return dL, dL.T @ x.astype(dtype), dL.sum(axis=0), dL @ Wg.astype(dtype)
 
 
 def expert_ffn_bwd(dy_packed, x_packed, G, U, counts, offsets, W1, W3, W2, dtype=F64):

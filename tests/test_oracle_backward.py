@@ -1,6 +1,7 @@
 """Pins for the oracle's backward (O10): torch CPU autograd on the dense definition of
 the layer (float64), central finite differences, and the adjoint identity of the pack."""
 import numpy as np
+import pytest
 import torch
 import torch.nn.functional as F
 
@@ -116,3 +117,65 @@ def test_experts_without_weights_get_no_gradient_and_zero_dx():
     dxp, dW1, dW3, dW2 = orc.expert_ffn_bwd(dy, xp, G, U, cnt, off, W1, W3, W2)
     assert dW1[2] is None and dW3[2] is None and dW2[2] is None
     assert np.all(dxp[off[2]:off[2] + cnt[2]] == 0)
+
+
+# ------------------------------------------------------------------ gate backward (O10d)
+@pytest.mark.parametrize("renorm", [True, False])
+def test_route_bwd_against_torch_autograd(renorm):
+    rng = np.random.default_rng(77)
+    T, d, E, k = 37, 24, 10, 3
+    x = rng.standard_normal((T, d))
+    Wg = rng.standard_normal((E, d)) / np.sqrt(d)
+    bias = rng.standard_normal(E) * 0.3
+    dw = rng.standard_normal((T, k))
+    logits = orc.gate_logits(x, Wg, bias)
+    idx = orc.topk_select(logits, k)
+    xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    Wt = torch.tensor(Wg, dtype=torch.float64, requires_grad=True)
+    bt = torch.tensor(bias, dtype=torch.float64, requires_grad=True)
+    Lt = xt @ Wt.T + bt
+    Lt.retain_grad()
+    it = torch.tensor(idx.astype(np.int64))
+    if renorm:
+        wt = torch.softmax(torch.gather(Lt, 1, it), dim=1)
+    else:
+        wt = torch.gather(torch.softmax(Lt, dim=1), 1, it)
+    assert np.allclose(wt.detach().numpy(), orc.topk_weights(logits, idx, renorm), atol=1e-12)
+    (wt * torch.tensor(dw)).sum().backward()
+    dL, dWg, db, dx = orc.route_bwd(x, Wg, logits, idx, dw, renorm)
+    assert np.allclose(dL, Lt.grad.numpy(), atol=1e-12)
+    assert np.allclose(dWg, Wt.grad.numpy(), atol=1e-12)
+    assert np.allclose(db, bt.grad.numpy(), atol=1e-12)
+    assert np.allclose(dx, xt.grad.numpy(), atol=1e-12)
+
+
+def test_route_bwd_closed_forms():
+    rng = np.random.default_rng(78)
+    T, d, E, k = 16, 8, 6, 2
+    x = rng.standard_normal((T, d))
+    Wg = rng.standard_normal((E, d))
+    logits = orc.gate_logits(x, Wg)
+    idx = orc.topk_select(logits, k)
+    for renorm in (True, False):
+        # the weights of a token sum to a constant under renormalisation, so a gradient that
+        # is the same for all k slots gives no logit gradient; rows of dlogits always sum to 0
+        dL, _, db, _ = orc.route_bwd(x, Wg, logits, idx, np.ones((T, k)), renorm)
+        if renorm:
+            assert np.allclose(dL, 0, atol=1e-14)
+        dL, dWg, db, dx = orc.route_bwd(x, Wg, logits, idx, rng.standard_normal((T, k)), renorm)
+        assert np.allclose(dL.sum(axis=1), 0, atol=1e-13)
+        assert np.allclose(db.sum(), 0, atol=1e-12)
+        if renorm:
+            mask = np.zeros((T, E), bool)
+            np.put_along_axis(mask, idx.astype(np.int64), True, axis=1)
+            assert np.all(dL[~mask] == 0)
+        # central finite difference on one logit
+        dw = rng.standard_normal((T, k))
+        dL, _, _, _ = orc.route_bwd(x, Wg, logits, idx, dw, renorm)
+        t, e, h = 3, int(idx[3, 1]), 1e-6
+        Lp, Lm = logits.copy(), logits.copy()
+        Lp[t, e] += h
+        Lm[t, e] -= h
+        fp = np.sum(orc.topk_weights(Lp, idx, renorm) * dw)
+        fm = np.sum(orc.topk_weights(Lm, idx, renorm) * dw)
+        assert abs((fp - fm) / (2 * h) - dL[t, e]) < 1e-7
