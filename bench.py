@@ -291,6 +291,24 @@ def main() -> int:
     }
     if mfma and not args.no_sr:
         rec["sr_compression"] = sr_compression_bench(lay.ctx, f, d)
+    if cfg.backward:
+        # gate backward (not one of the steps the training configuration names): timed on its
+        # own after the steps, on the last step's tensors
+        def gate_bwd():
+            moe.moe_route_bwd(lay.ctx, x, lay.Wg, topk_idx, topk_w, dw, dx=dx)
+        gate_bwd()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            gate_bwd()
+        e1.record()
+        torch.cuda.synchronize()
+        t_rb = e0.elapsed_time(e1) / 10
+        by = (2 * T * d + E * d) * elem + T * d * elem + T * E * 4 * 3 + E * d * 4
+        rec["route_bwd"] = {"ms": t_rb, "algorithmic_bytes": by,
+                            "gbs": by / (t_rb * 1e-3) / 1e9,
+                            "note": "dlogits, dWg and dx += dlogits Wg; x read once, dx read and "
+                                    "written; not part of the timed step"}
     if not args.no_cpu_baseline:
         flops_tok = 6.0 * d * f * k * (3 if cfg.backward else 1) + 2.0 * d * E
         sample = args.cpu_sample_tokens or int(max(16, min(cfg.T, 4e12 / flops_tok / 4)))

@@ -215,6 +215,24 @@ int moe_plan_expert_dest_rank(int32_t local_rank, int32_t E, int32_t L, const in
 int moe_plan_model(double D, double P_E, double B, double lat_pe, int32_t G, double* p_star,
                    int32_t* case_id, int32_t* best_S);
 
+/* Backward of the gate (Sec. 2.1: the gate network picks the K experts of a token; the
+ * output depends on it through the K combine weights).  The Top-k choice itself is
+ * piecewise constant and carries no gradient.  With p = softmax of the logits over the
+ * selected experts (renormalize = 1) or over all E (renormalize = 0), w_j = p[idx_j]:
+ *   dlogits[t,e] = p_e * ( [e selected] dtopk_w[t,j(e)] - sum_j dtopk_w[t,j] topk_w[t,j] )
+ *   dWg = dlogits^T x      dbias[e] = sum_t dlogits[t,e]      dx[t] += dlogits[t] Wg
+ * x [dev][T,d] dtype (needed for dWg); Wg [dev][E,d] dtype (needed for dx); logits
+ * [dev][T,E] fp32 as moe_route returned them (needed when renormalize = 0, else may be
+ * NULL); topk_idx, topk_w from moe_route; dtopk_w [dev][T,k] fp32 from moe_combine_bwd.
+ * dlogits [dev][T,E] fp32 out (required); dWg [dev][E,d] fp32 out or NULL; dbias [dev][E]
+ * fp32 out or NULL; dx [dev][T,d] dtype IN/OUT or NULL: the gate's contribution is ADDED to
+ * what moe_dispatch_bwd wrote there (fp32 add, rounded once to dtype).  Deterministic
+ * (fixed-order partial sums).  The first call that asks for dWg allocates a workspace
+ * of ceil(T_max/128) * E * d floats. */
+int moe_route_bwd(moe_ctx* ctx, const void* x, const void* Wg, const float* logits,
+                  const int32_t* topk_idx, const float* topk_w, const float* dtopk_w, int32_t T,
+                  float* dlogits, float* dWg, float* dbias, void* dx, void* stream);
+
 /* ---- Shared/residual expert compression (Sec. 4.2 "SR-Based Expert Compression";
  * compression ratio CR: Sec. 5.4).  An expert weight matrix is sent to the other GPUs of
  * its domain as the k largest-magnitude entries of (expert - shared expert) in value-index

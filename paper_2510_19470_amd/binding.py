@@ -74,6 +74,8 @@ def load_library(build_if_missing: bool = True):
     for name in ("moe_plan_location", "moe_plan_comm_type", "moe_plan_comm_frequency",
                  "moe_plan_expert_dest_rank", "moe_plan_model"):
         getattr(lib, name).restype = c_int
+    lib.moe_route_bwd.argtypes = [P, P, P, P, P, P, P, c_int32, P, P, P, P, P]
+    lib.moe_route_bwd.restype = c_int
     I64 = ctypes.c_int64
     lib.moe_sr_keep_count.argtypes = [I64, c_int32]
     lib.moe_sr_keep_count.restype = I64
@@ -287,6 +289,22 @@ def moe_dispatch_bwd(ctx, dx_packed, slot_to_row, dx=None):
 
 
 MOE_PROF_SLOTS = 3
+
+
+def moe_route_bwd(ctx, x, Wg, topk_idx, topk_w, dtopk_w, logits=None, dx=None, want_dWg=True,
+                  want_dbias=False):
+    """Returns (dlogits [T,E], dWg [E,d] or None, dbias [E] or None); adds the gate's
+    contribution to dx in place when dx is given."""
+    T = topk_w.shape[0]
+    dev = topk_w.device
+    E, d = ctx.cfg.E, ctx.cfg.d
+    dlogits = torch.empty((T, E), dtype=torch.float32, device=dev)
+    dWg = torch.empty((E, d), dtype=torch.float32, device=dev) if want_dWg else None
+    dbias = torch.empty(E, dtype=torch.float32, device=dev) if want_dbias else None
+    _check(load_library().moe_route_bwd(
+        ctx.handle, _ptr(x), _ptr(Wg), _ptr(logits), _ptr(topk_idx), _ptr(topk_w), _ptr(dtopk_w), T,
+        _ptr(dlogits), _ptr(dWg), _ptr(dbias), _ptr(dx), _stream()), "moe_route_bwd")
+    return dlogits, dWg, dbias
 
 
 def moe_profile_ffn(ctx, n_calls: int) -> None:

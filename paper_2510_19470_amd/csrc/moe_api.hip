@@ -31,6 +31,7 @@ void free_all(moe_ctx* c) {
   (void)hipFree(c->d_order_down);
   (void)hipFree(c->d_split_ws);
   (void)hipFree(c->d_sr_ws);
+  (void)hipFree(c->d_rbwd_ws);
   (void)hipFree(c->d_H);
   (void)hipFree(c->d_dG);
   (void)hipFree(c->d_dU);
@@ -227,6 +228,7 @@ int moe_sr_encode(moe_ctx* c, const void* expert, const void* shared, int64_t n,
   const size_t need = sr_workspace_ints(n);
   if (need > c->sr_ws_ints) {   // grow the workspace (synchronises: earlier calls may use it)
     (void)hipFree(c->d_sr_ws);
+  (void)hipFree(c->d_rbwd_ws);
     c->d_sr_ws = nullptr;
     c->sr_ws_ints = 0;
     if (hipMalloc(reinterpret_cast<void**>(&c->d_sr_ws), need * sizeof(int32_t)) != hipSuccess) {
@@ -498,6 +500,29 @@ int moe_dispatch_bwd(moe_ctx* c, const void* dx_packed, const int32_t* slot_to_r
   if (dx_packed == nullptr || slot_to_row == nullptr || dx == nullptr) return MOE_EINVAL;
   if (!aligned16(dx_packed) || !aligned16(dx)) return MOE_EINVAL;
   return launch_dispatch_bwd(c, dx_packed, slot_to_row, T, dx, (hipStream_t)stream);
+}
+
+int moe_route_bwd(moe_ctx* c, const void* x, const void* Wg, const float* logits,
+                  const int32_t* topk_idx, const float* topk_w, const float* dtopk_w, int32_t T,
+                  float* dlogits, float* dWg, float* dbias, void* dx, void* stream) {
+  int st = check_ctx_T(c, T);
+  if (st != MOE_OK) return st;
+  if (T > 0 && (topk_idx == nullptr || topk_w == nullptr || dtopk_w == nullptr ||
+                dlogits == nullptr))
+    return MOE_EINVAL;
+  if (T > 0 && c->cfg.renormalize == 0 && logits == nullptr) return MOE_EINVAL;
+  if (T > 0 && dWg != nullptr && x == nullptr) return MOE_EINVAL;
+  if (T > 0 && dx != nullptr && (Wg == nullptr || !aligned16(dx) || !aligned16(Wg))) return MOE_EINVAL;
+  if (T > 0 && dWg != nullptr && c->d_rbwd_ws == nullptr) {
+    if (hipMalloc(reinterpret_cast<void**>(&c->d_rbwd_ws),
+                  std::max<size_t>(route_bwd_workspace_floats(c), 4) * sizeof(float)) != hipSuccess) {
+      (void)hipGetLastError();
+      c->d_rbwd_ws = nullptr;
+      return MOE_ENOMEM;
+    }
+  }
+  return launch_route_bwd(c, x, Wg, logits, topk_idx, topk_w, dtopk_w, T, dlogits, dWg, dbias, dx,
+                          (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -77,6 +77,8 @@ struct moe_ctx {
   int32_t* d_koff;        // [E+1] padded row offsets of the experts in d_actT
   void* d_wT;             // transposed weights of the MFMA backward
   size_t wT_experts;      // experts d_wT has room for
+  // gate backward: per-chunk partial sums of dWg, [T_max/128][E][d] (first call allocates)
+  float* d_rbwd_ws;
   // shared/residual compression: selection state, histogram, per-chunk counts
   int32_t* d_sr_ws;
   size_t sr_ws_ints;      // capacity of d_sr_ws
@@ -127,6 +129,10 @@ bool ffn_bwd_mfma_supported(const moe_ctx* c);
 int ffn_bwd_ktot(const moe_ctx* c);
 int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* G, const void* U,
                         const int32_t* counts, const int32_t* offsets, void* dxp, hipStream_t s);
+size_t route_bwd_workspace_floats(const moe_ctx* c);
+int launch_route_bwd(moe_ctx* c, const void* x, const void* Wg, const float* logits,
+                     const int32_t* topk_idx, const float* topk_w, const float* dtopk_w, int T,
+                     float* dlogits, float* dWg, float* dbias, void* dx, hipStream_t s);
 size_t sr_workspace_ints(int64_t n);
 int launch_sr_encode(moe_ctx* c, const void* W, const void* S, int64_t n, int64_t k, void* values,
                      int32_t* indices, hipStream_t s);
