@@ -582,24 +582,53 @@ __global__ __launch_bounds__(NT) void ffn_split_reduce_kernel(const GemmArgs p) 
 // All GEMMs here want both operands contiguous along the contraction dimension.  The
 // backward contracts over the other index of the weights (dH = dY W2, dX = dG W1 + dU W3)
 // and over the token rows (dW = P^T Q), so the weights and the activations are transposed
-// once per call with a 64x64 LDS tile.
+// once per call, 64 x 64 elements per block through LDS, 16 bytes per lane on both the
+// global reads and the global writes.  LDS row pitch 66 elements: the eight 2-byte reads
+// that gather one output chunk fall on distinct banks across the wavefront.
+constexpr int TP = 66;
+
+// in: 64 x 64 tile, row r at src + r * pitch (rows >= valid_rows read as zero)
+__device__ __forceinline__ void tile_in(uint16_t (*tile)[TP], const uint16_t* src, size_t pitch,
+                                        int valid_rows) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int chunk = threadIdx.x + h * 256;
+    const int r = chunk >> 3, ch = chunk & 7;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r < valid_rows) v = *reinterpret_cast<const uint4*>(src + (size_t)r * pitch + ch * 8);
+    uint32_t* d = reinterpret_cast<uint32_t*>(&tile[r][ch * 8]);   // 4-byte aligned (pitch 132 B)
+    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+  }
+}
+
+// out: row c of the transposed tile (= column c of the input) at dst + c * pitch, 64 elements
+__device__ __forceinline__ void tile_out_t(const uint16_t (*tile)[TP], uint16_t* dst, size_t pitch) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int chunk = threadIdx.x + h * 256;
+    const int c = chunk >> 3, q = chunk & 7;
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      w[j] = (uint32_t)tile[8 * q + 2 * j][c] | ((uint32_t)tile[8 * q + 2 * j + 1][c] << 16);
+    store16(dst + (size_t)c * pitch + q * 8, w[0], w[1], w[2], w[3]);
+  }
+}
 
 // out[c][col_off + r] = in[r][c] for every expert with a source; in: [R,C], out pitch given.
 __global__ __launch_bounds__(256) void transpose_weights_kernel(const void* const* __restrict__ src_t,
                                                                 const void* const* __restrict__ dst_t,
                                                                 int R, int C, int dst_pitch,
                                                                 int col_off) {
-  __shared__ uint16_t tile[64][66];
+  __shared__ uint16_t tile[64][TP];
   const int e = blockIdx.z;
   const uint16_t* src = (const uint16_t*)src_t[e];
   uint16_t* dst = (uint16_t*)dst_t[e];
   if (src == nullptr || dst == nullptr) return;
   const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int i = ty; i < 64; i += 4) tile[i][tx] = src[(size_t)(r0 + i) * C + c0 + tx];
+  tile_in(tile, src + (size_t)r0 * C + c0, C, 64);
   __syncthreads();
-  for (int i = ty; i < 64; i += 4)
-    dst[(size_t)(c0 + i) * dst_pitch + col_off + r0 + tx] = tile[tx][i];
+  tile_out_t(tile, dst + (size_t)c0 * dst_pitch + col_off + r0, dst_pitch);
 }
 
 // dst[c][koff[e] + r] = src[offsets[e] + r][c] for r < counts[e], 0 for the padding rows.
@@ -607,7 +636,7 @@ __global__ __launch_bounds__(256) void transpose_acts_kernel(
     const uint16_t* __restrict__ src, int src_pitch, int C, const int32_t* __restrict__ counts,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ koff, int E,
     uint16_t* __restrict__ dst, int dst_pitch) {
-  __shared__ uint16_t tile[64][66];
+  __shared__ uint16_t tile[64][TP];
   __shared__ int32_t s_koff[MOE_MAX_EXPERTS + 1];
   for (int i = threadIdx.x; i <= E; i += 256) s_koff[i] = koff[i];
   __syncthreads();
@@ -622,11 +651,9 @@ __global__ __launch_bounds__(256) void transpose_acts_kernel(
   const int rel = k0 - s_koff[e];
   const int n = counts[e], row0 = offsets[e];
   const int c0 = blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int i = ty; i < 64; i += 4)
-    tile[i][tx] = (rel + i < n) ? src[(size_t)(row0 + rel + i) * src_pitch + c0 + tx] : (uint16_t)0;
+  tile_in(tile, src + (size_t)(row0 + rel) * src_pitch + c0, src_pitch, n - rel);
   __syncthreads();
-  for (int i = ty; i < 64; i += 4) dst[(size_t)(c0 + i) * dst_pitch + k0 + tx] = tile[tx][i];
+  tile_out_t(tile, dst + (size_t)c0 * dst_pitch + k0, dst_pitch);
 }
 
 }  // namespace
