@@ -169,12 +169,16 @@ struct GemmArgs {
   float* split_ws;         // DOWN: fp32 partial tiles of the K-split tail
   uint16_t* Gs;            // UP: optional save (out); DH: saved G (in)
   uint16_t* Us;
-  // MODE_WGRAD: dW[e][Mo,No] = AT_e * BT_e^T over the expert's padded row range
-  const uint16_t* BT;
+  // MODE_WGRAD: up to three products dW[e][Mo,No] = AT_e * BT_e^T over the expert's padded
+  // row range in one launch (blocks [j * tiles, (j+1) * tiles) belong to job j)
+  struct WJob {
+    const uint16_t* AT;      // [rows >= a_row0 + Mo][lda]
+    const uint16_t* BT;      // [No][lda]
+    const void* const* dWt;  // table of fp32 outputs
+    int Mo, No, a_row0;
+  } wj[3];
   const int32_t* koff;
   const void* const* present;
-  const void* const* dWt;
-  int Mo, No, a_row0, b_row0;
 };
 
 // One unit of work of a block: a whole tile, or one K-split part of a tile (all fields are
@@ -298,7 +302,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = __builtin_amdgcn_readfirstlane(wave >> 2), wn = wave & 3;
   float* dW = nullptr;
-  int mblk = 0;
+  int mblk = 0, w_No = 0;
   Unit cur;
   // global -> LDS assignment: one copy instruction fills 8 rows (lane>>3) x 8 chunk slots
   // (lane&7); slot c of row r must hold global chunk c ^ swz(r).  Token rows: copy i of a
@@ -318,11 +322,18 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
     b_off[i] = (uint32_t)(rb & 127) * b_pitch + (((lane & 7) ^ swz(rb)) << 4);
   }
   if (MODE == MODE_WGRAD) {
-    const int MoT = p.Mo >> 8, NoT = p.No >> 8;
-    const int e = blockIdx.x / (MoT * NoT);
-    const int rem = blockIdx.x % (MoT * NoT);
+    // all jobs have the same number of tiles per expert: (d/256) * (f/256)
+    const int tiles = (p.wj[0].Mo >> 8) * (p.wj[0].No >> 8);
+    const int per_job = (int)gridDim.x / 3;
+    const int job = blockIdx.x / per_job;
+    const int jb = blockIdx.x % per_job;
+    const GemmArgs::WJob& J = p.wj[job];
+    const int NoT = J.No >> 8;
+    const int e = jb / tiles;
+    const int rem = jb % tiles;
     mblk = rem / NoT;
-    dW = (float*)p.dWt[e];
+    w_No = J.No;
+    dW = (float*)J.dWt[e];
     if (dW == nullptr || p.present[e] == nullptr) return;
     const int k0 = p.koff[e];
     cur.valid = 1;
@@ -331,8 +342,8 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
     cur.rows = BM;
     cur.nblk = rem % NoT;
     cur.ws_unit = -1;
-    cur.abase = (const char*)(p.A + (size_t)(p.a_row0 + mblk * 256) * p.lda + k0);
-    cur.bbase0 = (const char*)(p.BT + (size_t)(p.b_row0 + cur.nblk * 256) * p.lda + k0);
+    cur.abase = (const char*)(J.AT + (size_t)(J.a_row0 + mblk * 256) * p.lda + k0);
+    cur.bbase0 = (const char*)(J.BT + (size_t)(cur.nblk * 256) * p.lda + k0);
     cur.bbase1 = cur.bbase0 + (size_t)128 * b_pitch;
   } else {
     cur = fetch_unit<MODE>(p, 0);
@@ -373,7 +384,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
       const int m_local = wm * 128 + i * 32 + fr_row;
       if (m_local >= u.rows) continue;
       if (MODE == MODE_WGRAD) {
-        float* orow = dW + (size_t)(mblk * 256 + m_local) * p.No;
+        float* orow = dW + (size_t)(mblk * 256 + m_local) * w_No;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           const int col0 = u.nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
@@ -790,14 +801,9 @@ int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* 
   w.lda = Kt;
   w.koff = c->d_koff;
   w.present = W1;
-  // dW2 [d,f] = dY^T H
-  w.A = dYT; w.BT = HT; w.dWt = dW2; w.Mo = d; w.No = f; w.a_row0 = 0; w.b_row0 = 0;
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_WGRAD>), dim3(E * nt_d * nt_f), dim3(NT), 0, s, w);
-  // dW1 [f,d] = dG^T X
-  w.A = dGUT; w.BT = XT; w.dWt = dW1; w.Mo = f; w.No = d; w.a_row0 = 0;
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_WGRAD>), dim3(E * nt_d * nt_f), dim3(NT), 0, s, w);
-  // dW3 [f,d] = dU^T X
-  w.dWt = dW3; w.a_row0 = f;
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_WGRAD>), dim3(E * nt_d * nt_f), dim3(NT), 0, s, w);
+  w.wj[0] = {dYT, HT, dW2, d, f, 0};     // dW2 [d,f] = dY^T H
+  w.wj[1] = {dGUT, XT, dW1, f, d, 0};    // dW1 [f,d] = dG^T X
+  w.wj[2] = {dGUT, XT, dW3, f, d, f};    // dW3 [f,d] = dU^T X
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_WGRAD>), dim3(3 * E * nt_d * nt_f), dim3(NT), 0, s, w);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }

@@ -152,6 +152,14 @@ __global__ __launch_bounds__(256) void route_bwd_dx_kernel(
   }
 }
 
+// T == 0: the sums are empty.  (A fill kernel rather than a memset call, so that the launch
+// can be part of a captured graph.)
+__global__ void route_bwd_zero_kernel(float* __restrict__ p, size_t n) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    p[i] = 0.f;
+}
+
 }  // namespace
 
 size_t route_bwd_workspace_floats(const moe_ctx* c) {
@@ -164,10 +172,11 @@ int launch_route_bwd(moe_ctx* c, const void* x, const void* Wg, const float* log
                      float* dlogits, float* dWg, float* dbias, void* dx, hipStream_t s) {
   const int E = c->cfg.E, d = c->cfg.d, k = c->cfg.k, rn = c->cfg.renormalize;
   if (T == 0) {
-    if (dWg != nullptr && hipMemsetAsync(dWg, 0, sizeof(float) * (size_t)E * d, s) != hipSuccess)
-      return MOE_EHIP;
-    if (dbias != nullptr && hipMemsetAsync(dbias, 0, sizeof(float) * E, s) != hipSuccess)
-      return MOE_EHIP;
+    if (dWg != nullptr)
+      hipLaunchKernelGGL(route_bwd_zero_kernel, dim3(256), dim3(256), 0, s, dWg, (size_t)E * d);
+    if (dbias != nullptr)
+      hipLaunchKernelGGL(route_bwd_zero_kernel, dim3(1), dim3(256), 0, s, dbias, (size_t)E);
+    if (hipGetLastError() != hipSuccess) return MOE_EHIP;
     return MOE_OK;
   }
   const int wave_grid = (T + 3) / 4;
