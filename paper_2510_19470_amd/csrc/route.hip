@@ -126,75 +126,80 @@ __global__ __launch_bounds__(256) void route_select_kernel(const float* __restri
 }
 
 // ---- fused gate projection + selection for bf16 inputs (matrix cores) -----------------
-// One block = 32 tokens.  Its 4 wavefronts split d into quarters; each accumulates
-// logits[32 tokens][64 experts] with MFMA 32x32x16 (gate rows are the "A" operand, token
-// rows the "B" operand, both read straight from global memory: a lane fetches 64
-// contiguous bytes of its row per 64-wide k-step, with the same k-to-lane assignment on
-// both operands).  The partial sums meet in LDS, the bias is added, the logits are written
-// out when the caller wants them, and the block selects the top-k of its 32 tokens from
-// LDS.  The token rows are read exactly once: the kernel is bound by HBM.
+// One block = 32 tokens.  Its 8 wavefronts split d into eighths; each accumulates
+// logits[32 tokens][16*NEB experts] with MFMA 16x16x32 (gate rows are the "A" operand, token
+// rows the "B" operand, both read straight from global memory with the same k-to-lane
+// assignment: lane (n = lane & 15, q = lane >> 4) fetches the 16 bytes at k = 32*ks + 8*q of
+// row n, so one load instruction covers 16 rows x 64 contiguous bytes).  A gate fragment is
+// used for both token groups of the wavefront; the gate matrix is re-read once per 32
+// tokens (from L2).  The partial sums meet in LDS, the bias is added, the logits are
+// written out when the caller wants them, and the block selects the top-k of its 32 tokens
+// from LDS.  The token rows are read exactly once: the kernel is bound by HBM.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-constexpr int GATE_TOK = 32;
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+constexpr int GATE_TOK = 32;    // tokens per block
+constexpr int GATE_WAVES = 8;   // wavefronts per block, each with an eighth of d
+constexpr int GATE_TB = GATE_TOK / 16;
 
-template <int W, int VPL>
-__global__ __launch_bounds__(256) void gate_route_mfma_kernel(
+template <int W, int VPL, int NEB>
+__global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
     const float* __restrict__ bias, int T, int E, int d, int k, int renormalize,
     float* __restrict__ logits_out, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+  constexpr int EG = 16 * NEB;                     // experts per pass over the token rows
   constexpr int EP = W * VPL < 64 ? 64 : W * VPL;  // expert slots kept in LDS
-  __shared__ float part[4][GATE_TOK][64 + 1];
+  __shared__ float part[GATE_WAVES][GATE_TOK][EG + 1];
   __shared__ float fin[GATE_TOK][EP + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r = lane & 31, h = lane >> 5;
+  const int n = lane & 15, q = lane >> 4;
   const int t0 = blockIdx.x * GATE_TOK;
-  const int kq = d >> 2;  // k range of this wavefront
-  const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)min(t0 + r, T - 1) * d +
-                                                   wave * kq + h * 32);
-  for (int e0 = 0; e0 < E; e0 += 64) {
-    const uint4* wp[2];
+  const int kq = d / GATE_WAVES;  // k range of this wavefront
+  const uint4* xp[GATE_TB];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      wp[j] = reinterpret_cast<const uint4*>(Wg + (size_t)min(e0 + j * 32 + r, E - 1) * d +
-                                             wave * kq + h * 32);
-    f32x16_t acc[2];
+  for (int tb = 0; tb < GATE_TB; ++tb)
+    xp[tb] = reinterpret_cast<const uint4*>(x + (size_t)min(t0 + 16 * tb + n, T - 1) * d +
+                                            wave * kq + q * 8);
+  for (int e0 = 0; e0 < E; e0 += EG) {
+    const uint4* wp[NEB];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int eb = 0; eb < NEB; ++eb)
+      wp[eb] = reinterpret_cast<const uint4*>(Wg + (size_t)min(e0 + 16 * eb + n, E - 1) * d +
+                                              wave * kq + q * 8);
+    f32x4_t acc[NEB][GATE_TB];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
-    for (int ks = 0; ks < kq / 64; ++ks) {
-      uint4 xv[4], wv0[4], wv1[4];
+    for (int eb = 0; eb < NEB; ++eb)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        xv[c] = xp[ks * 8 + c];
-        wv0[c] = wp[0][ks * 8 + c];
-        wv1[c] = wp[1][ks * 8 + c];
-      }
+      for (int tb = 0; tb < GATE_TB; ++tb) acc[eb][tb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int ks = 0; ks < kq / 32; ++ks) {   // a k-slice of 32 = 4 chunks of 16 bytes per row
+      uint4 xv[GATE_TB], wv[NEB];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wv0[c]),
-                                                         __builtin_bit_cast(bf16x8_t, xv[c]),
-                                                         acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wv1[c]),
-                                                         __builtin_bit_cast(bf16x8_t, xv[c]),
-                                                         acc[1], 0, 0, 0);
-      }
+      for (int tb = 0; tb < GATE_TB; ++tb) xv[tb] = xp[tb][ks * 4];
+#pragma unroll
+      for (int eb = 0; eb < NEB; ++eb) wv[eb] = wp[eb][ks * 4];
+#pragma unroll
+      for (int eb = 0; eb < NEB; ++eb)
+#pragma unroll
+        for (int tb = 0; tb < GATE_TB; ++tb)
+          acc[eb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              __builtin_bit_cast(bf16x8_t, wv[eb]), __builtin_bit_cast(bf16x8_t, xv[tb]),
+              acc[eb][tb], 0, 0, 0);
     }
-    // the lane holds token r and experts 32j + 8g + 4h + i of this group of 64
+    // the lane holds token 16*tb + n and experts 16*eb + 4*q + i of this group
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int eb = 0; eb < NEB; ++eb)
 #pragma unroll
-      for (int g = 0; g < 4; ++g)
+      for (int tb = 0; tb < GATE_TB; ++tb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          part[wave][r][32 * j + 8 * g + 4 * h + i] = acc[j][g * 4 + i];
+        for (int i = 0; i < 4; ++i) part[wave][16 * tb + n][16 * eb + 4 * q + i] = acc[eb][tb][i];
     __syncthreads();
-    for (int idx = tid; idx < GATE_TOK * 64; idx += 256) {
-      const int tok = idx >> 6, el = idx & 63, e = e0 + el;
+    for (int idx = tid; idx < GATE_TOK * EG; idx += 64 * GATE_WAVES) {
+      const int tok = idx / EG, el = idx % EG, e = e0 + el;
       if (e < E) {
-        const float v = ((part[0][tok][el] + part[1][tok][el]) +
-                         (part[2][tok][el] + part[3][tok][el])) +
-                        (bias != nullptr ? bias[e] : 0.f);
+        float v = 0.f;
+#pragma unroll
+        for (int w8 = 0; w8 < GATE_WAVES; ++w8) v += part[w8][tok][el];   // fixed order
+        if (bias != nullptr) v += bias[e];
         fin[tok][e] = v;
         if (logits_out != nullptr && t0 + tok < T) logits_out[(size_t)(t0 + tok) * E + e] = v;
       }
@@ -202,7 +207,7 @@ __global__ __launch_bounds__(256) void gate_route_mfma_kernel(
     __syncthreads();
   }
   constexpr int TOK_PER_WAVE = 64 / W;
-  for (int base = 0; base < GATE_TOK; base += 4 * TOK_PER_WAVE) {
+  for (int base = 0; base < GATE_TOK; base += GATE_WAVES * TOK_PER_WAVE) {
     const int tok = base + wave * TOK_PER_WAVE + lane / W;
     const bool live = tok < GATE_TOK && t0 + tok < T;
     select_token<W, VPL>(&fin[live ? tok : 0][0], live, t0 + tok, E, k, renormalize, topk_idx,
@@ -221,11 +226,11 @@ int launch_sel(const float* logits, int T, int E, int k, int renorm, int32_t* id
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 
-template <int W, int VPL>
+template <int W, int VPL, int NEB>
 int launch_gate(const moe_ctx* c, const void* x, const void* Wg, const float* bias, int T,
                 float* logits, int32_t* idx, float* w, hipStream_t s) {
   const int grid = (T + GATE_TOK - 1) / GATE_TOK;
-  hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL>), dim3(grid), dim3(256), 0, s,
+  hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB>), dim3(grid), dim3(64 * GATE_WAVES), 0, s,
                      (const uint16_t*)x, (const uint16_t*)Wg, bias, T, c->cfg.E, c->cfg.d,
                      c->cfg.k, c->cfg.renormalize, logits, idx, w);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
@@ -256,13 +261,14 @@ int launch_gate_route_fused(const moe_ctx* c, const void* x, const void* Wg, con
                             int T, float* logits, int32_t* idx, float* w, hipStream_t s) {
   if (T == 0) return MOE_OK;
   const int E = c->cfg.E;
-  if (E <= 2) return launch_gate<2, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 4) return launch_gate<4, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 8) return launch_gate<8, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 16) return launch_gate<16, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 32) return launch_gate<32, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 64) return launch_gate<64, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 128) return launch_gate<64, 2>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 256) return launch_gate<64, 4>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 2) return launch_gate<2, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 4) return launch_gate<4, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 8) return launch_gate<8, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 16) return launch_gate<16, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 32) return launch_gate<32, 1, 2>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 48) return launch_gate<64, 1, 3>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 64) return launch_gate<64, 1, 4>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 128) return launch_gate<64, 2, 4>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 256) return launch_gate<64, 4, 4>(c, x, Wg, bias, T, logits, idx, w, s);
   return MOE_EUNSUPPORTED;
 }
