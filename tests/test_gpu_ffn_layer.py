@@ -76,6 +76,23 @@ def test_ffn_bf16_reduced_shapes(path, T, d, E, k, f, skew, present):
     say(f"    normalised max error {err:.3e}")
 
 
+@pytest.mark.parametrize("T,d,E,k,f", [
+    (600, 256, 4, 2, 1024),     # 16 k-steps: the tail of the down GEMM is cut in 2
+    (900, 512, 4, 2, 2048),     # 32 k-steps: cut in 4
+    (700, 256, 3, 2, 4096),     # 64 k-steps: cut in 8
+    (16600, 512, 2, 2, 4096),   # 260 tiles: one full round of whole tiles + 4 tiles cut in 8
+])
+def test_ffn_down_gemm_k_split_tail(T, d, E, k, f):
+    """Shapes whose last, partly filled round of down-GEMM tiles is split along the
+    contraction (fp32 partial tiles summed in a fixed order) next to whole tiles."""
+    from gpu_common import moe, say
+    say(f"[ffn] K-split tail T={T} d={d} E={E} k={k} f={f}")
+    cfg = wl.MoEConfig("ksplit", 999 + T, "bf16", T=T, d=d, E=E, k=k, f=f, R=1)
+    idx = wl.random_routing(T, E, k, seed=T + 1, skew=0.3)
+    err = _run_ffn_case(cfg, idx, moe.MOE_FFN_AUTO, save=False)
+    say(f"    normalised max error {err:.3e}")
+
+
 @pytest.mark.parametrize("name,T", [("tiny", None), ("small", 1024), ("finegrained", 1024),
                                     ("train", 1024)])
 def test_whole_layer_loopback_matches_dense_definition(name, T):
