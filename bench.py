@@ -311,7 +311,7 @@ def main() -> int:
                                     "written; not part of the timed step"}
     if not args.no_cpu_baseline:
         flops_tok = 6.0 * d * f * k * (3 if cfg.backward else 1) + 2.0 * d * E
-        sample = args.cpu_sample_tokens or int(max(16, min(cfg.T, 4e12 / flops_tok / 4)))
+        sample = args.cpu_sample_tokens or int(max(16, min(cfg.T, 8e12 / flops_tok)))
         rec["cpu_baseline"] = cpu_baseline(cfg, inp, sample)
     print(json.dumps(rec))
     lay.close()
