@@ -27,6 +27,7 @@ definition written out, in float64 by default.  Steps:
   O4-O6 dispatch_maps counts, (dest_rank, expert)-ordered offsets, stable permutation
   O7 pack_rows        x_packed[row] = x[token of the slot stored in that row]
   O8 expert_ffn       y = (silu(x W1^T) * (x W3^T)) W2^T per expert segment
+  O8' expert_ffn2     y = max(x W1^T, 0) W2^T: the paper's two-matrix expert (forward only)
   O9 combine          out[t] = sum_j w[t,j] y_packed[slot_to_row[t*k+j]]
   O10 backward        of O9, O8, O7 and of the gate O1-O3 (chain rule written out)
   layer_dense         the whole layer by its definition, without any packing
@@ -170,6 +171,30 @@ def expert_ffn(x_packed: np.ndarray, counts: np.ndarray, offsets: np.ndarray,
         G[lo:lo + n] = g
         U[lo:lo + n] = u
     return y, G, U
+
+
+def expert_ffn2(x_packed: np.ndarray, counts: np.ndarray, offsets: np.ndarray,
+                W1: Sequence[Optional[np.ndarray]], W2: Sequence[Optional[np.ndarray]],
+                dtype=F64) -> Tuple[np.ndarray, np.ndarray]:
+    """O8'.  The paper's own expert: a two-matrix FFN (Sec. 2.1: the expert is the FFN of
+    the Transformer; Table 2 counts 2*H*M parameters per expert).  The activation is not
+    named in the paper; the cited Transformer FFN uses ReLU, which is taken here:
+        g = x_r W1[e]^T,  y_r = max(g, 0) W2[e]^T,   W1[e]: [f,d], W2[e]: [d,f].
+    Returns (y_packed [S,d], G [S,f])."""
+    S, d = x_packed.shape
+    f = next(w.shape[0] for w in W1 if w is not None) if any(w is not None for w in W1) else 0
+    y = np.zeros((S, d), dtype=dtype)
+    G = np.zeros((S, f), dtype=dtype)
+    for e in range(len(W1)):
+        if W1[e] is None:
+            continue
+        lo, n = int(offsets[e]), int(counts[e])
+        if n == 0:
+            continue
+        g = x_packed[lo:lo + n].astype(dtype) @ W1[e].astype(dtype).T
+        y[lo:lo + n] = np.maximum(g, 0.0) @ W2[e].astype(dtype).T
+        G[lo:lo + n] = g
+    return y, G
 
 
 # --------------------------------------------------------------------- combine

@@ -148,3 +148,44 @@ def test_bf16_storage_rounding_is_nearest_even():
     want = torch.from_numpy(r).to(torch.bfloat16)
     assert np.array_equal(wl.f32_to_bf16_bits(r), want.view(torch.int16).numpy().view(np.uint16))
     assert np.array_equal(wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(r)), want.float().numpy())
+
+
+# ------------------------------------------------------------------ two-matrix expert (O8')
+def test_two_matrix_expert_against_torch_and_closed_forms():
+    import torch
+    import torch.nn.functional as F
+    rng = np.random.default_rng(91)
+    d, f, E = 12, 20, 3
+    counts = np.array([5, 0, 7], dtype=np.int32)
+    offsets = np.array([0, 5, 5], dtype=np.int32)
+    S = int(counts.sum())
+    x = rng.standard_normal((S, d))
+    W1 = [rng.standard_normal((f, d)) for _ in range(E)]
+    W2 = [rng.standard_normal((d, f)) for _ in range(E)]
+    y, G = orc.expert_ffn2(x, counts, offsets, W1, W2)
+    for e in range(E):
+        lo, n = int(offsets[e]), int(counts[e])
+        xe = torch.tensor(x[lo:lo + n])
+        want = F.linear(F.relu(F.linear(xe, torch.tensor(W1[e]))), torch.tensor(W2[e])).numpy()
+        assert np.allclose(y[lo:lo + n], want, atol=1e-12)
+        assert np.allclose(G[lo:lo + n], (xe @ torch.tensor(W1[e]).T).numpy(), atol=1e-12)
+    # pure-Python scalar loops on one row
+    r = 8
+    h = [max(sum(x[r][c] * W1[2][n][c] for c in range(d)), 0.0) for n in range(f)]
+    want_row = [sum(h[n] * W2[2][c][n] for n in range(f)) for c in range(d)]
+    assert np.allclose(y[r], want_row, atol=1e-12)
+    # closed forms: positive homogeneity; all pre-activations negative -> zero output;
+    # linear in W2; an absent expert leaves zeros
+    y2, _ = orc.expert_ffn2(2.5 * x, counts, offsets, W1, W2)
+    assert np.allclose(y2, 2.5 * y, atol=1e-11)
+    xpos = np.abs(x)
+    Wneg = [-np.abs(w) for w in W1]
+    y0, G0 = orc.expert_ffn2(xpos, counts, offsets, Wneg, W2)
+    assert np.all(G0 <= 0) and np.all(y0 == 0)
+    y3, _ = orc.expert_ffn2(x, counts, offsets, W1, [3.0 * w for w in W2])
+    assert np.allclose(y3, 3.0 * y, atol=1e-11)
+    y4, _ = orc.expert_ffn2(x, counts, offsets, [W1[0], None, None], [W2[0], None, None])
+    assert np.allclose(y4[:5], y[:5]) and np.all(y4[5:] == 0)
+    # it is not the gated expert with any choice of sign: differs from silu gating
+    yg, _, _ = orc.expert_ffn(x, counts, offsets, W1, W1, W2)
+    assert not np.allclose(yg, y)
