@@ -45,7 +45,7 @@ def cpu_baseline(cfg, inp, sample_tokens: int):
     x = f32(inp.x)[:T]
     Wg = f32(inp.Wg)
     W1 = [f32(w) for w in inp.W1]
-    W3 = [f32(w) for w in inp.W3]
+    W3 = [f32(w) for w in inp.W3] if cfg.gated else None
     W2 = [f32(w) for w in inp.W2]
     t0 = time.perf_counter()
     res = orc.layer_forward(x, Wg, inp.bias, cfg.k, inp.dest_rank, cfg.R, W1, W3, W2)
@@ -115,7 +115,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="mixtral",
-                    help="workload: tiny | small | mixtral | finegrained | train")
+                    help="workload: tiny | small | mixtral | finegrained | train | paper (a layer "
+                         "of the paper's own sweep with its two-matrix expert)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0,
                     help="tokens of the oracle baseline sample (0 = sized for ~10-30 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -240,7 +241,8 @@ def main() -> int:
     n_res = len(wl.resident_experts(cfg))
 
     # ---- algorithmic work ------------------------------------------------------------
-    flops_up = 4.0 * n_loc * d * f            # gate and up projections of the compute region
+    n_up = 2 if cfg.gated else 1              # matrices in the first GEMM (gate and up / W1 only)
+    flops_up = 2.0 * n_up * n_loc * d * f     # first GEMM over the compute region
     flops_down = 2.0 * n_loc * d * f
     bytes_dispatch = T * d * elem + S * d * elem + S * 4 + 2 * S * 4
     bytes_combine = S * d * elem + T * d * elem + S * 8
@@ -265,12 +267,13 @@ def main() -> int:
                    "resident_experts": n_res, "n_loc_rows": n_loc,
                    "steps_in_path": names},
         "roofline": {
-            "kernel": "ffn_mfma_kernel<0> (MODE_UP: gate/up grouped GEMM + SwiGLU)" if mfma
+            "kernel": ("ffn_mfma_kernel<0> (MODE_UP: gate/up grouped GEMM + SwiGLU)" if cfg.gated
+                       else "ffn_mfma_kernel<4> (MODE_UP1: first GEMM of the two-matrix expert + ReLU)") if mfma
                       else "ffn_gate_up_kernel<float>",
             "bound": "mfma" if mfma else "alu",
             "achieved": ach_up, "peak": peak, "unit": "TFLOP/s", "frac": ach_up / peak,
             "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if mfma else None,
-            "algorithmic_bytes": (2 * n_res * d * f + n_loc * d + n_loc * f) * elem,
+            "algorithmic_bytes": (n_up * n_res * d * f + n_loc * d + n_loc * f) * elem,
             "avg_launch_ms": ffn_ms[1], "flops_per_launch": flops_up, "launches": n_rec,
         },
         "grouped_gemm": {

@@ -138,7 +138,13 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int32_t T
  * resident set; loopback tests pass every expert.
  * y_packed [dev][S,d] dtype out.  G_save,U_save [dev][S,f] dtype out or both NULL:
  * the pre-activation projections kept for the backward.  bf16: h (and g,u when
- * saved) are rounded to bf16 between the two GEMMs. */
+ * saved) are rounded to bf16 between the two GEMMs.
+ * W3 == NULL (the table pointer itself) selects the paper's own expert, a two-matrix FFN
+ * (Sec. 2.1; Table 2 counts 2*H*M parameters per expert):
+ *   g = x_r W1[e]^T, y_r = max(g, 0) W2[e]^T
+ * (the paper does not name the activation; ReLU, as in the Transformer FFN it cites).
+ * U_save must then be NULL, G_save may receive g.  Forward only: moe_expert_ffn_bwd
+ * requires W3. */
 int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* expert_counts,
                    const int32_t* expert_offsets, const void* const* W1, const void* const* W3,
                    const void* const* W2, int32_t T, void* y_packed, void* G_save, void* U_save,

@@ -49,6 +49,7 @@ class MoEConfig:
     all_resident: bool = False        # every expert computed locally
     bias_scale: float = 0.0           # per-expert gate bias b_e = bias_scale*ln(1/(e+1))
     backward: bool = False
+    gated: bool = True                # False: the paper's two-matrix expert (no W3)
 
     @property
     def S(self) -> int:
@@ -66,6 +67,10 @@ CONFIGS: Dict[str, MoEConfig] = {
     "train": MoEConfig("train", 1005, "bf16", T=8192, d=2048, E=32, k=4, f=2048, R=8,
                        migrated=(5, 9), backward=True),
 }
+# Not one of the five configurations of the benchmark spec: a layer of the paper's own sweep
+# (Table 3: E = 32, H = 1024, M = 4096, K = 2, B*L = 16*512 tokens) with its two-matrix expert.
+CONFIGS["paper"] = MoEConfig("paper", 1006, "bf16", T=8192, d=1024, E=32, k=2, f=4096, R=8,
+                             migrated=(4, 5, 6, 7), gated=False)
 CONFIG_ORDER = ["tiny", "small", "mixtral", "finegrained", "train"]
 
 
@@ -165,6 +170,9 @@ def make_inputs(cfg: MoEConfig, experts: str = "all") -> MoEInputs:
     if experts != "none":
         for name, shape, fan_in in (("W1", (f, d), d), ("W3", (f, d), d), ("W2", (d, f), f)):
             lst = getattr(inp, name)
+            if name == "W3" and not cfg.gated:   # two-matrix expert: nothing drawn for W3
+                lst.extend([None] * E)
+                continue
             s = np.float32(1.0 / np.sqrt(fan_in))
             for e in range(E):
                 w = rng.standard_normal(shape, dtype=np.float32)

@@ -316,7 +316,11 @@ def layer_forward(x, Wg, bias, k, dest_rank, R, W1, W3, W2, renormalize=True, dt
     w = topk_weights(L, idx, renormalize, dtype)
     cnt, off, rcnt, roff, s2r, r2s = dispatch_maps(idx, dest_rank, R)
     xp = pack_rows(x, r2s, k)
-    y, G, U = expert_ffn(xp, cnt, off, W1, W3, W2, dtype)
+    if W3 is None:   # the paper's two-matrix expert
+        y, G = expert_ffn2(xp, cnt, off, W1, W2, dtype)
+        U = None
+    else:
+        y, G, U = expert_ffn(xp, cnt, off, W1, W3, W2, dtype)
     out = combine(y, s2r, w, dtype)
     return dict(logits=L, topk_idx=idx, topk_w=w, expert_counts=cnt, expert_offsets=off,
                 rank_counts=rcnt, rank_offsets=roff, slot_to_row=s2r, row_to_slot=r2s,

@@ -227,8 +227,9 @@ def moe_expert_ffn(ctx, x_packed, expert_counts, expert_offsets, W1, W3, W2, y_p
         y_packed = torch.zeros_like(x_packed)
     if save and G_save is None:
         G_save = torch.zeros((S, ctx.cfg.f), dtype=x_packed.dtype, device=x_packed.device)
-        U_save = torch.zeros((S, ctx.cfg.f), dtype=x_packed.dtype, device=x_packed.device)
-    t1, t3, t2 = _table(W1), _table(W3), _table(W2)
+        if W3 is not None:   # the two-matrix expert (W3 = None) has no second projection
+            U_save = torch.zeros((S, ctx.cfg.f), dtype=x_packed.dtype, device=x_packed.device)
+    t1, t3, t2 = _table(W1), (None if W3 is None else _table(W3)), _table(W2)
     _check(load_library().moe_expert_ffn(
         ctx.handle, _ptr(x_packed), _ptr(expert_counts), _ptr(expert_offsets), t1, t3, t2, T,
         _ptr(y_packed), _ptr(G_save), _ptr(U_save), _stream()), "moe_expert_ffn")

@@ -154,7 +154,7 @@ __device__ __forceinline__ void dma16(uint32_t off, const char* base, uint32_t l
                : "memory", "m0");
 }
 
-enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_WGRAD = 3 };
+enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_WGRAD = 3, MODE_UP1 = 4 };
 
 struct GemmArgs {
   const uint16_t* A;    // token-role operand: [rows, lda]
@@ -285,6 +285,7 @@ __device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][
 }
 
 // MODE_UP   : H = silu(A W1^T) * (A W3^T)            (gate/up, SwiGLU fused)
+// MODE_UP1  : H = max(A W1^T, 0)                      (first GEMM of the two-matrix expert)
 // MODE_DOWN : C = A B^T                               (down projection; also dX = [dG|dU][W1^T|W3^T]^T)
 // MODE_DH   : dH = A B^T, then dG = dH*u*silu'(g), dU = dH*silu(g), H = silu(g)*u
 // MODE_WGRAD: fp32 dW = AT BT^T, both operands transposed activations (contraction = rows)
@@ -430,6 +431,14 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
               *reinterpret_cast<uint2*>(p.C + row * p.N + col) =
                   make_uint2(pack_bf16x2(acc[j][i][g * 4], acc[j][i][g * 4 + 1]),
                              pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]));
+            } else if (MODE == MODE_UP1) {
+              *reinterpret_cast<uint2*>(p.C + row * p.N + col) =
+                  make_uint2(pack_bf16x2(fmaxf(acc[j][i][g * 4], 0.f), fmaxf(acc[j][i][g * 4 + 1], 0.f)),
+                             pack_bf16x2(fmaxf(acc[j][i][g * 4 + 2], 0.f), fmaxf(acc[j][i][g * 4 + 3], 0.f)));
+              if (p.Gs != nullptr)
+                *reinterpret_cast<uint2*>(p.Gs + row * p.N + col) =
+                    make_uint2(pack_bf16x2(acc[j][i][g * 4], acc[j][i][g * 4 + 1]),
+                               pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]));
             } else {  // MODE_DH
               const uint2 gq = *reinterpret_cast<const uint2*>(p.Gs + row * p.N + col);
               const uint2 uq = *reinterpret_cast<const uint2*>(p.Us + row * p.N + col);
@@ -669,6 +678,11 @@ __global__ __launch_bounds__(256) void transpose_acts_kernel(
 
 }  // namespace
 
+// two-matrix expert: the first GEMM has 256-column blocks of one matrix
+bool ffn_mfma_supported_2mat(const moe_ctx* c) {
+  return c->cfg.dtype == MOE_BF16 && c->cfg.d % 256 == 0 && c->cfg.f % 256 == 0;
+}
+
 bool ffn_mfma_supported(const moe_ctx* c) {
   const int d = c->cfg.d, f = c->cfg.f;
   return c->cfg.dtype == MOE_BF16 && d % 256 == 0 && f % 128 == 0 &&  // K % 128 == 0 too
@@ -716,22 +730,26 @@ static GemmArgs tiled_args(moe_ctx* c, const void* A, int lda, const TileDesc* o
   return a;
 }
 
-int launch_ffn_mfma(moe_ctx* c, const int32_t* counts, const int32_t* offsets, const void* x_packed,
-                    void* y_packed, void* G, void* U, hipStream_t s) {
+int launch_ffn_mfma(moe_ctx* c, bool gated, const int32_t* counts, const int32_t* offsets,
+                    const void* x_packed, void* y_packed, void* G, void* U, hipStream_t s) {
   const int d = c->cfg.d, f = c->cfg.f;
-  const int nt_up = f / 128, nt_down = d / 256;
+  const int nt_up = gated ? f / 128 : f / 256, nt_down = d / 256;
   const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
   const void* const* W3 = c->d_wtab + 1 * MOE_MAX_EXPERTS;
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
   const int max_mt = c->max_mtiles[1];
   prof_mark(c, 0, s);
-  int st = run_sched(c, counts, offsets, nt_up, nt_down, f / BK, W1, W3, W2, nullptr, s);
+  int st = run_sched(c, counts, offsets, nt_up, nt_down, f / BK, W1, gated ? W3 : nullptr, W2,
+                     nullptr, s);
   if (st != MOE_OK) return st;
   prof_mark(c, 1, s);
   GemmArgs up = tiled_args(c, x_packed, d, c->d_order_up, nt_up, d, f, c->d_H);
   up.Gs = (uint16_t*)G;
   up.Us = (uint16_t*)U;
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_UP>), dim3(persistent_grid(c)), dim3(NT), 0, s, up);
+  if (gated)
+    hipLaunchKernelGGL((ffn_mfma_kernel<MODE_UP>), dim3(persistent_grid(c)), dim3(NT), 0, s, up);
+  else
+    hipLaunchKernelGGL((ffn_mfma_kernel<MODE_UP1>), dim3(persistent_grid(c)), dim3(NT), 0, s, up);
   prof_mark(c, 2, s);
   GemmArgs dn = tiled_args(c, c->d_H, f, c->d_order_down, nt_down, f, d, y_packed);
   launch_down(c, dn, nt_down, s);

@@ -90,7 +90,8 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(const T* __restrict__ 
 }
 
 // ---- forward ------------------------------------------------------------------------
-// H = silu(X W1^T) * (X W3^T) for one (expert, row block) x 64 columns of f.
+// H = silu(X W1^T) * (X W3^T) for one (expert, row block) x 64 columns of f; with
+// W3t == nullptr the two-matrix expert: H = max(X W1^T, 0).
 template <typename T>
 __global__ __launch_bounds__(256) void ffn_gate_up_kernel(
     const T* __restrict__ xp, const TileSched* __restrict__ sched, const MTile* __restrict__ mt,
@@ -100,14 +101,15 @@ __global__ __launch_bounds__(256) void ffn_gate_up_kernel(
   if ((int)blockIdx.y >= sched->n_mtiles) return;
   const MTile tl = mt[blockIdx.y];
   const T* W1 = (const T*)W1t[tl.expert];
-  const T* W3 = (const T*)W3t[tl.expert];
+  const bool gated = W3t != nullptr;
+  const T* W3 = gated ? (const T*)W3t[tl.expert] : nullptr;
   const int n0 = blockIdx.x * BN;
   float g[4][4], u[4][4];
   zero(g);
   zero(u);
   const T* A = xp + (size_t)tl.row0 * d;
   tile_mac(g, A, d, 1, tl.rows, W1 + (size_t)n0 * d, 1, d, f - n0, d, sm);
-  tile_mac(u, A, d, 1, tl.rows, W3 + (size_t)n0 * d, 1, d, f - n0, d, sm);
+  if (gated) tile_mac(u, A, d, 1, tl.rows, W3 + (size_t)n0 * d, 1, d, f - n0, d, sm);
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -119,10 +121,10 @@ __global__ __launch_bounds__(256) void ffn_gate_up_kernel(
       if (n >= f) continue;
       const size_t o = (size_t)(tl.row0 + r) * f + n;
       const float gv = g[i][j], uv = u[i][j];
-      H[o] = from_f32<T>(gv / (1.f + expf(-gv)) * uv);
+      H[o] = from_f32<T>(gated ? gv / (1.f + expf(-gv)) * uv : fmaxf(gv, 0.f));
       if (Gs) {
         Gs[o] = from_f32<T>(gv);
-        Us[o] = from_f32<T>(uv);
+        if (gated) Us[o] = from_f32<T>(uv);
       }
     }
   }
@@ -201,7 +203,8 @@ __global__ __launch_bounds__(256) void ffn_bwd_dx_kernel(
   if ((int)blockIdx.y >= sched->n_mtiles) return;
   const MTile tl = mt[blockIdx.y];
   const T* W1 = (const T*)W1t[tl.expert];  // [f,d]: B(k=n_f, n=c) = W1[n_f*d + c]
-  const T* W3 = (const T*)W3t[tl.expert];
+  const bool gated = W3t != nullptr;
+  const T* W3 = gated ? (const T*)W3t[tl.expert] : nullptr;
   const int n0 = blockIdx.x * BN;
   float acc[4][4];
   zero(acc);
@@ -287,11 +290,12 @@ __global__ __launch_bounds__(256) void build_sched_kernel(const int32_t* __restr
 }
 
 template <typename T>
-int ffn_generic_t(moe_ctx* c, const void* xp, void* y, void* G, void* U, void* H, hipStream_t s) {
+int ffn_generic_t(moe_ctx* c, bool gated, const void* xp, void* y, void* G, void* U, void* H,
+                  hipStream_t s) {
   const int d = c->cfg.d, f = c->cfg.f;
   const int mtiles = c->max_mtiles[0];
   const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
-  const void* const* W3 = c->d_wtab + 1 * MOE_MAX_EXPERTS;
+  const void* const* W3 = gated ? c->d_wtab + 1 * MOE_MAX_EXPERTS : nullptr;
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
   hipLaunchKernelGGL((ffn_gate_up_kernel<T>), dim3((f + BN - 1) / BN, mtiles), dim3(256), 0, s,
                      (const T*)xp, c->d_sched[0], c->d_mtiles[0], W1, W3, d, f, (T*)H, (T*)G,
@@ -357,10 +361,11 @@ int launch_build_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 
-int launch_ffn_generic(moe_ctx* c, const void* x_packed, void* y_packed, void* G, void* U,
-                       void* H_tmp, hipStream_t s) {
-  return c->cfg.dtype == MOE_BF16 ? ffn_generic_t<uint16_t>(c, x_packed, y_packed, G, U, H_tmp, s)
-                                  : ffn_generic_t<float>(c, x_packed, y_packed, G, U, H_tmp, s);
+int launch_ffn_generic(moe_ctx* c, bool gated, const void* x_packed, void* y_packed, void* G,
+                       void* U, void* H_tmp, hipStream_t s) {
+  return c->cfg.dtype == MOE_BF16
+             ? ffn_generic_t<uint16_t>(c, gated, x_packed, y_packed, G, U, H_tmp, s)
+             : ffn_generic_t<float>(c, gated, x_packed, y_packed, G, U, H_tmp, s);
 }
 
 int launch_ffn_bwd_generic(moe_ctx* c, const void* dy, const void* xp, const void* G,

@@ -69,13 +69,17 @@ int sync_tables(moe_ctx* c, const void* const* const tabs[MOE_WTAB_ROWS], hipStr
   return MOE_OK;
 }
 
+// W3 == nullptr (the whole table): two-matrix experts, present with both matrices or none.
 int check_weight_tables(const moe_ctx* c, const void* const* W1, const void* const* W3,
-                        const void* const* W2) {
-  if (W1 == nullptr || W3 == nullptr || W2 == nullptr) return MOE_EINVAL;
+                        const void* const* W2, bool allow_two_matrix = false) {
+  if (W1 == nullptr || W2 == nullptr) return MOE_EINVAL;
+  if (W3 == nullptr && !allow_two_matrix) return MOE_EINVAL;
+  const int want = W3 != nullptr ? 3 : 2;
   for (int e = 0; e < c->cfg.E; ++e) {
-    const int n = (W1[e] != nullptr) + (W3[e] != nullptr) + (W2[e] != nullptr);
-    if (n != 0 && n != 3) return MOE_EINVAL;  // an expert is present with all three or none
-    if (!aligned16(W1[e]) || !aligned16(W3[e]) || !aligned16(W2[e])) return MOE_EINVAL;
+    const void* w3 = W3 != nullptr ? W3[e] : nullptr;
+    const int n = (W1[e] != nullptr) + (w3 != nullptr) + (W2[e] != nullptr);
+    if (n != 0 && n != want) return MOE_EINVAL;  // an expert is present with all or none
+    if (!aligned16(W1[e]) || !aligned16(w3) || !aligned16(W2[e])) return MOE_EINVAL;
   }
   return MOE_OK;
 }
@@ -336,27 +340,30 @@ int moe_expert_ffn(moe_ctx* c, const void* x_packed, const int32_t* expert_count
                    void* stream) {
   int st = check_ctx_T(c, T);
   if (st != MOE_OK) return st;
-  st = check_weight_tables(c, W1, W3, W2);
+  const bool gated = W3 != nullptr;
+  st = check_weight_tables(c, W1, W3, W2, /*allow_two_matrix=*/true);
   if (st != MOE_OK) return st;
   if (T == 0) return MOE_OK;
   if (x_packed == nullptr || y_packed == nullptr || expert_counts == nullptr ||
       expert_offsets == nullptr)
     return MOE_EINVAL;
-  if ((G_save == nullptr) != (U_save == nullptr)) return MOE_EINVAL;
+  if (gated && (G_save == nullptr) != (U_save == nullptr)) return MOE_EINVAL;
+  if (!gated && U_save != nullptr) return MOE_EINVAL;
   if (!aligned16(x_packed) || !aligned16(y_packed) || !aligned16(G_save) || !aligned16(U_save))
     return MOE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
   const void* const* tabs[MOE_WTAB_ROWS] = {W1, W3, W2, nullptr, nullptr, nullptr, nullptr, nullptr};
   st = sync_tables(c, tabs, s);
   if (st != MOE_OK) return st;
-  if (c->ffn_path == MOE_FFN_AUTO && ffn_mfma_supported(c)) {
-    st = launch_ffn_mfma(c, expert_counts, expert_offsets, x_packed, y_packed, G_save, U_save, s);
+  if (c->ffn_path == MOE_FFN_AUTO && (gated ? ffn_mfma_supported(c) : ffn_mfma_supported_2mat(c))) {
+    st = launch_ffn_mfma(c, gated, expert_counts, expert_offsets, x_packed, y_packed, G_save, U_save,
+                         s);
   } else {
     prof_mark(c, 0, s);
     st = launch_build_sched(c, expert_counts, expert_offsets, 0, s);
     if (st != MOE_OK) return st;
     prof_mark(c, 1, s);
-    st = launch_ffn_generic(c, x_packed, y_packed, G_save, U_save, c->d_H, s);
+    st = launch_ffn_generic(c, gated, x_packed, y_packed, G_save, U_save, c->d_H, s);
   }
   if (c->prof_calls > 0 && c->prof_n < c->prof_calls) c->prof_n++;
   return st;

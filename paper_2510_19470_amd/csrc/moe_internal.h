@@ -119,12 +119,13 @@ int launch_dispatch_bwd(const moe_ctx* c, const void* dx_packed, const int32_t* 
                         void* dx, hipStream_t s);
 int launch_build_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets, int which,
                        hipStream_t s);
-int launch_ffn_generic(moe_ctx* c, const void* x_packed, void* y_packed, void* G, void* U,
-                       void* H_tmp, hipStream_t s);
+int launch_ffn_generic(moe_ctx* c, bool gated, const void* x_packed, void* y_packed, void* G,
+                       void* U, void* H_tmp, hipStream_t s);
 bool ffn_mfma_supported(const moe_ctx* c);
 size_t ffn_mfma_order_entries(const moe_ctx* c);
-int launch_ffn_mfma(moe_ctx* c, const int32_t* counts, const int32_t* offsets, const void* x_packed,
-                    void* y_packed, void* G, void* U, hipStream_t s);
+bool ffn_mfma_supported_2mat(const moe_ctx* c);
+int launch_ffn_mfma(moe_ctx* c, bool gated, const int32_t* counts, const int32_t* offsets,
+                    const void* x_packed, void* y_packed, void* G, void* U, hipStream_t s);
 bool ffn_bwd_mfma_supported(const moe_ctx* c);
 int ffn_bwd_ktot(const moe_ctx* c);
 int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* G, const void* U,

@@ -57,9 +57,13 @@ class MoELayer:
         self.Wg = to_device(Wg, self.dtype, self.device)
         self.bias = None if bias is None else torch.from_numpy(bias.astype(np.float32)).to(self.device)
 
-    def set_expert(self, e: int, W1: np.ndarray, W3: np.ndarray, W2: np.ndarray):
+    def set_expert(self, e: int, W1: np.ndarray, W3: Optional[np.ndarray], W2: np.ndarray):
+        """W3 = None for every expert makes the layer use the two-matrix expert."""
         self.W1[e] = to_device(W1, self.dtype, self.device)
-        self.W3[e] = to_device(W3, self.dtype, self.device)
+        if W3 is None:
+            self.W3 = None
+        else:
+            self.W3[e] = to_device(W3, self.dtype, self.device)
         self.W2[e] = to_device(W2, self.dtype, self.device)
 
     # ---- forward ---------------------------------------------------------------

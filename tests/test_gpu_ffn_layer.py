@@ -330,3 +330,46 @@ def test_train_config_full_size_backward_sampled():
                          for t in tok])
         assert nerr(to_host_f32(bwd["dx"])[tok], want) <= 2.0 ** -7
     lay.close()
+
+
+# ------------------------------------------------------------------ two-matrix expert
+@pytest.mark.parametrize("path", ["mfma", "valu"])
+@pytest.mark.parametrize("dtype,T,d,E,k,f,skew", [
+    ("bf16", 900, 512, 4, 2, 1024, 0.5),     # MFMA shapes (f % 256 == 0)
+    ("bf16", 515, 256, 6, 3, 384, 1.5),      # f % 256 != 0: vector-ALU kernels on both paths
+    ("f32", 300, 128, 8, 2, 256, 0.0),
+    ("bf16", 8192, 1024, 32, 2, 4096, 0.0),  # a shape of the paper's Table 3 (H=1024, M=4096, K=2)
+])
+def test_two_matrix_expert_forward(path, dtype, T, d, E, k, f, skew):
+    from gpu_common import DEV, TOL, moe, nerr, vals, to_device, to_host_f32, layer_from_inputs, say
+    say(f"[ffn2] {dtype} path={path} T={T} d={d} E={E} k={k} f={f}")
+    present = list(range(0, E, 4)) if E == 32 else None     # the resident quarter only
+    cfg = wl.MoEConfig("ffn2", 777 + T, dtype, T=T, d=d, E=E, k=k, f=f, R=1)
+    inp = wl.make_inputs(cfg)
+    if present is not None:
+        for e in range(E):
+            if e not in present:
+                inp.W1[e] = inp.W3[e] = inp.W2[e] = None
+    lay = layer_from_inputs(inp)
+    moe.moe_set_ffn_path(lay.ctx, moe.MOE_FFN_AUTO if path == "mfma" else moe.MOE_FFN_VALU)
+    idx = wl.random_routing(T, E, k, seed=T + 3, skew=skew)
+    cnt, off, _, _, s2r, r2s = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
+    xp_st = orc.pack_rows(inp.x, r2s, k)
+    xp = to_device(xp_st, dtype)
+    y0 = torch.full((cfg.S, d), 3.0, dtype=xp.dtype, device=DEV)
+    y, G, U = moe.moe_expert_ffn(lay.ctx, xp, torch.from_numpy(cnt).to(DEV),
+                                 torch.from_numpy(off).to(DEV), lay.W1, None, lay.W2,
+                                 y_packed=y0, save=True)
+    torch.cuda.synchronize()
+    assert U is None
+    yo, Go = orc.expert_ffn2(vals(xp_st, dtype), cnt, off, _f64_list(inp.W1, dtype),
+                             _f64_list(inp.W2, dtype))
+    done = np.zeros(cfg.S, bool)
+    for e in range(E):
+        if inp.W1[e] is not None:
+            done[off[e]:off[e] + cnt[e]] = True
+    yg = to_host_f32(y).astype(np.float64)
+    assert nerr(yg[done], yo[done]) <= TOL[dtype]
+    assert np.all(yg[~done] == 3.0)
+    assert nerr(to_host_f32(G)[done], Go[done]) <= TOL[dtype]
+    lay.close()
