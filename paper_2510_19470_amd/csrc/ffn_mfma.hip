@@ -32,6 +32,8 @@
 #include "moe_internal.h"
 #include "numeric.h"
 
+#include <algorithm>
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -81,13 +83,14 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
   if (blockIdx.x == 0 && tid == 0) {
     sched->n_mtiles = total_m;
     // Down GEMM: when the last round of tiles fills at most half of the compute units, its
-    // tiles are cut along the contraction into `split` parts (2, 4 or 8; every part an even
-    // number >= 8 of k-steps; all parts together still one round), summed afterwards.
+    // tiles are cut along the contraction into `split` parts (2, 4 or 8; every part a whole
+    // number >= 4 of k-step pairs, the first parts one pair longer when the pairs do not
+    // divide evenly; all parts together still one round), summed afterwards.
     const int total = total_m * nt_down;
     const int tail = total % n_cu;
+    const int pairs = kt_down / 2;
     int split = 1;
-    while (tail > 0 && split < 8 && tail * (split * 2) <= n_cu && kt_down % (4 * split) == 0 &&
-           kt_down / (2 * split) >= 8)
+    while (tail > 0 && split < 8 && tail * (split * 2) <= n_cu && pairs / (split * 2) >= 4)
       split *= 2;
     sched->down_split = split;
     sched->down_split_tiles = split > 1 ? tail : 0;
@@ -212,7 +215,7 @@ __device__ __forceinline__ Unit fetch_unit(const GemmArgs& p, int idx) {
   const int ns = max(0, min(per_xcd_s, n_units - x * per_xcd_s));
   const int q = (int)(blockIdx.x >> 3) + idx * (int)(gridDim.x >> 3);
   if (q >= nf + ns) return u;
-  int L, part = 0;
+  int L, part = 0, kstart = 0;   // kstart: first k-step of a K-split part
   if (q < nf) {
     L = x * per_xcd + q;
     u.KT = p.K / BK;
@@ -220,7 +223,10 @@ __device__ __forceinline__ Unit fetch_unit(const GemmArgs& p, int idx) {
     const int su = x * per_xcd_s + (q - nf);
     L = n_full + su / split;
     part = su % split;
-    u.KT = p.K / BK / split;
+    // pairs of k-steps of this part: the first `rem` parts take one pair more
+    const int pairs = p.K / BK / 2, base = pairs / split, rem = pairs % split;
+    u.KT = 2 * (base + (part < rem ? 1 : 0));
+    kstart = 2 * (part * base + min(part, rem));
     u.ws_unit = su;
   }
   const TileDesc td = p.order[L];
@@ -228,7 +234,7 @@ __device__ __forceinline__ Unit fetch_unit(const GemmArgs& p, int idx) {
   u.row0 = td.row0;
   u.rows = td.rows;
   u.nblk = td.nblk;
-  const size_t kbeg = (size_t)part * u.KT * (BK * 2);  // bytes into a row
+  const size_t kbeg = (size_t)kstart * (BK * 2);  // bytes into a row
   u.abase = (const char*)p.A + (size_t)td.row0 * p.lda * 2 + kbeg;
   if (MODE == MODE_UP) {
     u.bbase0 = (const char*)td.b0 + (size_t)td.nblk * 128 * p.K * 2 + kbeg;
@@ -707,7 +713,7 @@ static int run_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets, 
 
 // One block per compute unit (a block takes all of a unit's LDS), a multiple of 8 so that
 // every XCD gets the same number of blocks.
-static int persistent_grid(const moe_ctx* c) { return (c->n_cu / 8) * 8; }
+static int persistent_grid(const moe_ctx* c) { return std::max(8, (c->n_cu / 8) * 8); }
 
 // Down-type GEMM (plain epilogue) with the K-split tail: the GEMM, then the sum of the parts.
 static void launch_down(moe_ctx* c, GemmArgs& a, int nt, hipStream_t s) {

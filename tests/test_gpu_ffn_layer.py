@@ -80,6 +80,7 @@ def test_ffn_bf16_reduced_shapes(path, T, d, E, k, f, skew, present):
     (600, 256, 4, 2, 1024),     # 16 k-steps: the tail of the down GEMM is cut in 2
     (900, 512, 4, 2, 2048),     # 32 k-steps: cut in 4
     (700, 256, 3, 2, 4096),     # 64 k-steps: cut in 8
+    (700, 256, 3, 2, 1408),     # 22 k-steps: cut in 2 uneven parts (12 + 10)
     (16600, 512, 2, 2, 4096),   # 260 tiles: one full round of whole tiles + 4 tiles cut in 8
 ])
 def test_ffn_down_gemm_k_split_tail(T, d, E, k, f):
