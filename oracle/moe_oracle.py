@@ -280,6 +280,30 @@ def expert_ffn_bwd(dy_packed, x_packed, G, U, counts, offsets, W1, W3, W2, dtype
     return dx, dW1, dW3, dW2
 
 
+def expert_ffn2_bwd(dy_packed, x_packed, G, counts, offsets, W1, W2, dtype=F64):
+    """O10b'.  Backward of the two-matrix expert (O8'): dH = dY W2; dG = dH where g > 0, else 0;
+    dX = dG W1; dW2 = dY^T max(G, 0); dW1 = dG^T X.
+    Returns (dx_packed [S,d], dW1 list, dW2 list) -- None where no weights."""
+    S, d = x_packed.shape
+    E = len(W1)
+    dx = np.zeros((S, d), dtype=dtype)
+    dW1: List[Optional[np.ndarray]] = [None] * E
+    dW2: List[Optional[np.ndarray]] = [None] * E
+    for e in range(E):
+        if W1[e] is None:
+            continue
+        lo, n = int(offsets[e]), int(counts[e])
+        w1, w2 = W1[e].astype(dtype), W2[e].astype(dtype)
+        xe = x_packed[lo:lo + n].astype(dtype)
+        g = G[lo:lo + n].astype(dtype)
+        dy = dy_packed[lo:lo + n].astype(dtype)
+        dg = (dy @ w2) * (g > 0)
+        dx[lo:lo + n] = dg @ w1
+        dW2[e] = dy.T @ np.maximum(g, 0.0)
+        dW1[e] = dg.T @ xe
+    return dx, dW1, dW2
+
+
 def dispatch_bwd(dx_packed: np.ndarray, slot_to_row: np.ndarray, T: int, k: int,
                  dtype=F64) -> np.ndarray:
     """O10c.  dx[t] = sum_j dx_packed[slot_to_row[t*k+j]] (transpose of the pack)."""

@@ -179,3 +179,38 @@ def test_route_bwd_closed_forms():
         fp = np.sum(orc.topk_weights(Lp, idx, renorm) * dw)
         fm = np.sum(orc.topk_weights(Lm, idx, renorm) * dw)
         assert abs((fp - fm) / (2 * h) - dL[t, e]) < 1e-7
+
+
+# ------------------------------------------------------------------ two-matrix expert (O10b')
+def test_two_matrix_expert_backward_against_torch_autograd():
+    rng = np.random.default_rng(93)
+    d, f, E = 10, 14, 3
+    counts = np.array([6, 0, 9], dtype=np.int32)
+    offsets = np.array([0, 6, 6], dtype=np.int32)
+    S = int(counts.sum())
+    x = rng.standard_normal((S, d))
+    W1 = [rng.standard_normal((f, d)) for _ in range(E)]
+    W2 = [rng.standard_normal((d, f)) for _ in range(E)]
+    dy = rng.standard_normal((S, d))
+    y, G = orc.expert_ffn2(x, counts, offsets, W1, W2)
+    dx, dW1, dW2 = orc.expert_ffn2_bwd(dy, x, G, counts, offsets, W1, W2)
+    xt = torch.tensor(x, requires_grad=True)
+    w1t = [torch.tensor(w, requires_grad=True) for w in W1]
+    w2t = [torch.tensor(w, requires_grad=True) for w in W2]
+    loss = 0
+    for e in range(E):
+        lo, n = int(offsets[e]), int(counts[e])
+        ye = F.linear(F.relu(F.linear(xt[lo:lo + n], w1t[e])), w2t[e])
+        loss = loss + (ye * torch.tensor(dy[lo:lo + n])).sum()
+    loss.backward()
+    assert np.allclose(dx, xt.grad.numpy(), atol=1e-11)
+    for e in range(E):
+        want1 = w1t[e].grad.numpy() if w1t[e].grad is not None else np.zeros((f, d))
+        want2 = w2t[e].grad.numpy() if w2t[e].grad is not None else np.zeros((d, f))
+        assert np.allclose(dW1[e], want1, atol=1e-11)
+        assert np.allclose(dW2[e], want2, atol=1e-11)
+    # an expert without rows has zero gradients; units whose pre-activation is negative pass none
+    assert np.all(dW1[1] == 0) and np.all(dW2[1] == 0)
+    Gneg = -np.abs(G)
+    dx0, dW10, dW20 = orc.expert_ffn2_bwd(dy, x, Gneg, counts, offsets, W1, W2)
+    assert np.all(dx0 == 0) and all(np.all(w == 0) for w in dW10) and all(np.all(w == 0) for w in dW20)
