@@ -52,8 +52,12 @@ def cpu_baseline(cfg, inp, sample_tokens: int):
     if cfg.backward:
         dout = f32(inp.dOut)[:T]
         dy, _ = orc.combine_bwd(dout, res["y_packed"], res["slot_to_row"], res["topk_w"])
-        dxp, _, _, _ = orc.expert_ffn_bwd(dy, res["x_packed"], res["G"], res["U"],
-                                          res["expert_counts"], res["expert_offsets"], W1, W3, W2)
+        if cfg.gated:
+            dxp = orc.expert_ffn_bwd(dy, res["x_packed"], res["G"], res["U"], res["expert_counts"],
+                                     res["expert_offsets"], W1, W3, W2)[0]
+        else:
+            dxp = orc.expert_ffn2_bwd(dy, res["x_packed"], res["G"], res["expert_counts"],
+                                      res["expert_offsets"], W1, W2)[0]
         orc.dispatch_bwd(dxp, res["slot_to_row"], T, cfg.k)
     dt = time.perf_counter() - t0
     try:
@@ -116,7 +120,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="mixtral",
                     help="workload: tiny | small | mixtral | finegrained | train | paper (a layer "
-                         "of the paper's own sweep with its two-matrix expert)")
+                         "of the paper's own sweep with its two-matrix expert) | paper_train "
+                         "(the same layer, forward + backward)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0,
                     help="tokens of the oracle baseline sample (0 = sized for ~10-30 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -171,14 +176,14 @@ def main() -> int:
     dW1 = dW3 = dW2 = None
     if cfg.backward:
         G = torch.zeros((S, f), dtype=tdt, device=dev)
-        U = torch.zeros((S, f), dtype=tdt, device=dev)
+        U = torch.zeros((S, f), dtype=tdt, device=dev) if cfg.gated else None
         dy = torch.empty((S, d), dtype=tdt, device=dev)
         dw = torch.empty((T, k), dtype=torch.float32, device=dev)
         dxp = torch.zeros((S, d), dtype=tdt, device=dev)
         dx = torch.empty((T, d), dtype=tdt, device=dev)
         mk = lambda ws: [None if w is None else torch.empty(w.shape, dtype=torch.float32, device=dev)
                          for w in ws]
-        dW1, dW3, dW2 = mk(lay.W1), mk(lay.W3), mk(lay.W2)
+        dW1, dW3, dW2 = mk(lay.W1), (mk(lay.W3) if cfg.gated else None), mk(lay.W2)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     names = ["route", "dispatch", "expert_ffn", "combine"] + \
@@ -313,7 +318,7 @@ def main() -> int:
                             "note": "dlogits, dWg and dx += dlogits Wg; x read once, dx read and "
                                     "written; not part of the timed step"}
     if not args.no_cpu_baseline:
-        flops_tok = 6.0 * d * f * k * (3 if cfg.backward else 1) + 2.0 * d * E
+        flops_tok = 2.0 * (n_up + 1) * d * f * k * (3 if cfg.backward else 1) + 2.0 * d * E
         sample = args.cpu_sample_tokens or int(max(16, min(cfg.T, 8e12 / flops_tok)))
         rec["cpu_baseline"] = cpu_baseline(cfg, inp, sample)
     print(json.dumps(rec))

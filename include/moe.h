@@ -143,8 +143,7 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int32_t T
  * (Sec. 2.1; Table 2 counts 2*H*M parameters per expert):
  *   g = x_r W1[e]^T, y_r = max(g, 0) W2[e]^T
  * (the paper does not name the activation; ReLU, as in the Transformer FFN it cites).
- * U_save must then be NULL, G_save may receive g.  Forward only: moe_expert_ffn_bwd
- * requires W3. */
+ * U_save must then be NULL, G_save may receive g. */
 int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* expert_counts,
                    const int32_t* expert_offsets, const void* const* W1, const void* const* W3,
                    const void* const* W2, int32_t T, void* y_packed, void* G_save, void* U_save,
@@ -170,7 +169,13 @@ int moe_combine_bwd(moe_ctx* ctx, const void* dout, const void* y_packed,
  * dy_packed,x_packed [dev][S,d]; G_save,U_save [dev][S,f] from the forward;
  * dx_packed [dev][S,d] out (rows of experts not computed are left untouched);
  * dW1,dW3,dW2: [host][E] tables of device pointers to fp32 [f,d],[f,d],[d,f],
- * overwritten (not accumulated); NULL entry = that gradient is not wanted. */
+ * overwritten (not accumulated); NULL entry = that gradient is not wanted.
+ * W3 == NULL (the table pointer) is the backward of the two-matrix expert:
+ *   dH = dY W2; dG = dH where g > 0, else 0; dX = dG W1; dW2 = dY^T max(G,0); dW1 = dG^T X
+ * (g > 0 is decided on the stored G_save); U_save and dW3 must then be NULL as well.
+ * Errors: MOE_EINVAL for a NULL or misaligned pointer, tables that disagree about which
+ * experts are present, or U_save/dW3 not matching W3; MOE_ENOMEM when the first call
+ * cannot allocate the backward workspace. */
 int moe_expert_ffn_bwd(moe_ctx* ctx, const void* dy_packed, const void* x_packed,
                        const void* G_save, const void* U_save, const int32_t* expert_counts,
                        const int32_t* expert_offsets, const void* const* W1,

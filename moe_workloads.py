@@ -71,6 +71,8 @@ CONFIGS: Dict[str, MoEConfig] = {
 # (Table 3: E = 32, H = 1024, M = 4096, K = 2, B*L = 16*512 tokens) with its two-matrix expert.
 CONFIGS["paper"] = MoEConfig("paper", 1006, "bf16", T=8192, d=1024, E=32, k=2, f=4096, R=8,
                              migrated=(4, 5, 6, 7), gated=False)
+# ... and its training step (forward + backward of the same layer)
+CONFIGS["paper_train"] = replace(CONFIGS["paper"], name="paper_train", backward=True)
 CONFIG_ORDER = ["tiny", "small", "mixtral", "finegrained", "train"]
 
 

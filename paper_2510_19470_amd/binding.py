@@ -260,7 +260,7 @@ def moe_combine_bwd(ctx, dout, y_packed, slot_to_row, topk_w, dy_packed=None, dt
 def moe_expert_ffn_bwd(ctx, dy_packed, x_packed, G_save, U_save, expert_counts, expert_offsets,
                        W1, W3, W2, dx_packed=None, dW1=None, dW3=None, dW2=None):
     """dW1/dW3/dW2: lists of fp32 tensors (or None per expert); allocated for every expert
-    with weights when not given."""
+    with weights when not given.  W3 = None: the two-matrix expert (U_save and dW3 are None)."""
     S = x_packed.shape[0]
     T = S // ctx.cfg.k
     dev = x_packed.device
@@ -271,12 +271,16 @@ def moe_expert_ffn_bwd(ctx, dy_packed, x_packed, G_save, U_save, expert_counts, 
         return [None if w is None else torch.empty(w.shape, dtype=torch.float32, device=dev)
                 for w in ws]
     dW1 = grads(W1) if dW1 is None else dW1
-    dW3 = grads(W3) if dW3 is None else dW3
     dW2 = grads(W2) if dW2 is None else dW2
+    if W3 is None:
+        dW3, t3, tg3 = None, None, None
+    else:
+        dW3 = grads(W3) if dW3 is None else dW3
+        t3, tg3 = _table(W3), _table(dW3)
     _check(load_library().moe_expert_ffn_bwd(
         ctx.handle, _ptr(dy_packed), _ptr(x_packed), _ptr(G_save), _ptr(U_save),
-        _ptr(expert_counts), _ptr(expert_offsets), _table(W1), _table(W3), _table(W2), T,
-        _ptr(dx_packed), _table(dW1), _table(dW3), _table(dW2), _stream()), "moe_expert_ffn_bwd")
+        _ptr(expert_counts), _ptr(expert_offsets), _table(W1), t3, _table(W2), T,
+        _ptr(dx_packed), _table(dW1), tg3, _table(dW2), _stream()), "moe_expert_ffn_bwd")
     return dx_packed, dW1, dW3, dW2
 
 

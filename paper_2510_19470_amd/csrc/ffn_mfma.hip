@@ -157,7 +157,7 @@ __device__ __forceinline__ void dma16(uint32_t off, const char* base, uint32_t l
                : "memory", "m0");
 }
 
-enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_WGRAD = 3, MODE_UP1 = 4 };
+enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_WGRAD = 3, MODE_UP1 = 4, MODE_DH1 = 5 };
 
 struct GemmArgs {
   const uint16_t* A;    // token-role operand: [rows, lda]
@@ -172,8 +172,9 @@ struct GemmArgs {
   float* split_ws;         // DOWN: fp32 partial tiles of the K-split tail
   uint16_t* Gs;            // UP: optional save (out); DH: saved G (in)
   uint16_t* Us;
-  // MODE_WGRAD: up to three products dW[e][Mo,No] = AT_e * BT_e^T over the expert's padded
+  // MODE_WGRAD: n_jobs (<= 3) products dW[e][Mo,No] = AT_e * BT_e^T over the expert's padded
   // row range in one launch (blocks [j * tiles, (j+1) * tiles) belong to job j)
+  int n_jobs;
   struct WJob {
     const uint16_t* AT;      // [rows >= a_row0 + Mo][lda]
     const uint16_t* BT;      // [No][lda]
@@ -294,6 +295,7 @@ __device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][
 // MODE_UP1  : H = max(A W1^T, 0)                      (first GEMM of the two-matrix expert)
 // MODE_DOWN : C = A B^T                               (down projection; also dX = [dG|dU][W1^T|W3^T]^T)
 // MODE_DH   : dH = A B^T, then dG = dH*u*silu'(g), dU = dH*silu(g), H = silu(g)*u
+// MODE_DH1  : dH = A B^T, then dG = dH where g > 0 (else 0), H = max(g, 0)   (two-matrix expert)
 // MODE_WGRAD: fp32 dW = AT BT^T, both operands transposed activations (contraction = rows)
 //
 // Tiled modes run persistent blocks (one per compute unit) over a static share of the tile
@@ -331,7 +333,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   if (MODE == MODE_WGRAD) {
     // all jobs have the same number of tiles per expert: (d/256) * (f/256)
     const int tiles = (p.wj[0].Mo >> 8) * (p.wj[0].No >> 8);
-    const int per_job = (int)gridDim.x / 3;
+    const int per_job = (int)gridDim.x / p.n_jobs;
     const int job = blockIdx.x / per_job;
     const int jb = blockIdx.x % per_job;
     const GemmArgs::WJob& J = p.wj[job];
@@ -445,6 +447,21 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
                 *reinterpret_cast<uint2*>(p.Gs + row * p.N + col) =
                     make_uint2(pack_bf16x2(acc[j][i][g * 4], acc[j][i][g * 4 + 1]),
                                pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]));
+            } else if (MODE == MODE_DH1) {
+              // two-matrix expert: dG = dH where g > 0, H = max(g, 0)
+              const uint2 gq = *reinterpret_cast<const uint2*>(p.Gs + row * p.N + col);
+              const uint32_t gw[2] = {gq.x, gq.y};
+              float dg[4], hh[4];
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const float gv = __uint_as_float((r & 1) ? (gw[r >> 1] & 0xffff0000u) : (gw[r >> 1] << 16));
+                dg[r] = gv > 0.f ? acc[j][i][g * 4 + r] : 0.f;
+                hh[r] = fmaxf(gv, 0.f);
+              }
+              *reinterpret_cast<uint2*>(p.C + row * p.N + col) =
+                  make_uint2(pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3]));
+              *reinterpret_cast<uint2*>(p.C2 + row * p.N + col) =
+                  make_uint2(pack_bf16x2(hh[0], hh[1]), pack_bf16x2(hh[2], hh[3]));
             } else {  // MODE_DH
               const uint2 gq = *reinterpret_cast<const uint2*>(p.Gs + row * p.N + col);
               const uint2 uq = *reinterpret_cast<const uint2*>(p.Us + row * p.N + col);
@@ -772,9 +789,11 @@ int ffn_bwd_ktot(const moe_ctx* c) { return ((c->S_max + 127 * c->cfg.E + 127) /
 
 // dy, xp: [S,d]; G, U: [S,f] (forward saves); dxp out.  Workspace (context): d_H [S,f],
 // d_dGU [S,2f], d_actT: dY^T [d,Kt] | X^T [d,Kt] | H^T [f,Kt] | [dG|dU]^T [2f,Kt];
-// table rows 6 (W2^T) and 7 ([W1^T|W3^T]) point into d_wT.
-int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* G, const void* U,
-                        const int32_t* counts, const int32_t* offsets, void* dxp, hipStream_t s) {
+// table rows 6 (W2^T) and 7 ([W1^T|W3^T]) point into d_wT.  Two-matrix expert (!gated):
+// no U, no W3: d_dGU holds dG [S,f], row 7 points to W1^T [d,f], two weight gradients.
+int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, const void* G,
+                        const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
+                        hipStream_t s) {
   const int d = c->cfg.d, f = c->cfg.f, E = c->cfg.E;
   const int Kt = ffn_bwd_ktot(c);
   const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
@@ -786,24 +805,28 @@ int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* 
   const void* const* W2T = c->d_wtab + 6 * MOE_MAX_EXPERTS;
   const void* const* W13T = c->d_wtab + 7 * MOE_MAX_EXPERTS;
   const int nt_f = f / 256, nt_d = d / 256;
-  const int max_mt = c->max_mtiles[1];
-  int st = run_sched(c, counts, offsets, nt_f, nt_d, 2 * f / BK, W2T, nullptr, W13T, c->d_koff, s);
+  const int gw = gated ? 2 * f : f;   // elements per row of [dG|dU] and of [W1^T|W3^T]
+  int st = run_sched(c, counts, offsets, nt_f, nt_d, gw / BK, W2T, nullptr, W13T, c->d_koff, s);
   if (st != MOE_OK) return st;
   // weights: W2 [d,f] -> W2^T [f,d];  W1, W3 [f,d] -> [W1^T | W3^T] [d,2f]
   hipLaunchKernelGGL(transpose_weights_kernel, dim3(f / 64, d / 64, E), dim3(256), 0, s, W2, W2T, d,
                      f, d, 0);
   hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, s, W1, W13T, f,
-                     d, 2 * f, 0);
-  hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, s, W3, W13T, f,
-                     d, 2 * f, f);
-  // dH = dY W2 with the SwiGLU derivative in the epilogue -> [dG|dU], H
+                     d, gw, 0);
+  if (gated)
+    hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, s, W3, W13T,
+                       f, d, gw, f);
+  // dH = dY W2 with the activation's derivative in the epilogue -> [dG|dU], H
   GemmArgs dh = tiled_args(c, dy, d, c->d_order_up, nt_f, d, f, c->d_dGU);
   dh.C2 = (uint16_t*)c->d_H;
   dh.Gs = (uint16_t*)const_cast<void*>(G);
   dh.Us = (uint16_t*)const_cast<void*>(U);
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
-  // dX = [dG|dU] [W1^T|W3^T]^T  (one GEMM with contraction length 2f)
-  GemmArgs dx = tiled_args(c, c->d_dGU, 2 * f, c->d_order_down, nt_d, 2 * f, d, dxp);
+  if (gated)
+    hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
+  else
+    hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH1>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
+  // dX = [dG|dU] [W1^T|W3^T]^T  (one GEMM with contraction length 2f; f without U)
+  GemmArgs dx = tiled_args(c, c->d_dGU, gw, c->d_order_down, nt_d, gw, d, dxp);
   launch_down(c, dx, nt_d, s);
   // activations transposed per expert segment (zero padded to x128 rows)
   uint16_t* dYT = (uint16_t*)c->d_actT;
@@ -817,17 +840,18 @@ int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* 
                      (const uint16_t*)xp, d, d, counts, offsets, c->d_koff, E, XT, Kt);
   hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, f / 64), dim3(256), 0, s,
                      (const uint16_t*)c->d_H, f, f, counts, offsets, c->d_koff, E, HT, Kt);
-  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, 2 * f / 64), dim3(256), 0, s,
-                     (const uint16_t*)c->d_dGU, 2 * f, 2 * f, counts, offsets, c->d_koff, E, dGUT,
-                     Kt);
+  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, gw / 64), dim3(256), 0, s,
+                     (const uint16_t*)c->d_dGU, gw, gw, counts, offsets, c->d_koff, E, dGUT, Kt);
   // weight gradients, fp32
   GemmArgs w{};
   w.lda = Kt;
   w.koff = c->d_koff;
   w.present = W1;
+  w.n_jobs = gated ? 3 : 2;
   w.wj[0] = {dYT, HT, dW2, d, f, 0};     // dW2 [d,f] = dY^T H
   w.wj[1] = {dGUT, XT, dW1, f, d, 0};    // dW1 [f,d] = dG^T X
   w.wj[2] = {dGUT, XT, dW3, f, d, f};    // dW3 [f,d] = dU^T X
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_WGRAD>), dim3(3 * E * nt_d * nt_f), dim3(NT), 0, s, w);
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_WGRAD>), dim3(w.n_jobs * E * nt_d * nt_f), dim3(NT), 0, s,
+                     w);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }

@@ -160,6 +160,7 @@ __global__ __launch_bounds__(256) void ffn_down_kernel(const T* __restrict__ H,
 
 // ---- backward -----------------------------------------------------------------------
 // dH = dY W2, then dG = dH*u*silu'(g), dU = dH*silu(g), H = silu(g)*u (kept for dW2).
+// Two-matrix expert (Us == nullptr): dG = dH where g > 0, else 0; H = max(g, 0).
 template <typename T>
 __global__ __launch_bounds__(256) void ffn_bwd_dh_kernel(
     const T* __restrict__ dy, const T* __restrict__ Gs, const T* __restrict__ Us,
@@ -184,7 +185,13 @@ __global__ __launch_bounds__(256) void ffn_bwd_dh_kernel(
       const int n = n0 + tx + 16 * j;
       if (n >= f) continue;
       const size_t o = (size_t)(tl.row0 + r) * f + n;
-      const float g = to_f32(Gs[o]), u = to_f32(Us[o]), dh = acc[i][j];
+      const float g = to_f32(Gs[o]), dh = acc[i][j];
+      if (Us == nullptr) {
+        dG[o] = from_f32<T>(g > 0.f ? dh : 0.f);
+        H[o] = from_f32<T>(fmaxf(g, 0.f));
+        continue;
+      }
+      const float u = to_f32(Us[o]);
       const float sg = 1.f / (1.f + expf(-g));
       dG[o] = from_f32<T>(dh * u * sg * (1.f + g * (1.f - sg)));
       dU[o] = from_f32<T>(dh * g * sg);
@@ -193,7 +200,7 @@ __global__ __launch_bounds__(256) void ffn_bwd_dh_kernel(
   }
 }
 
-// dX = dG W1 + dU W3
+// dX = dG W1 + dU W3   (two-matrix expert, W3t == nullptr: dX = dG W1)
 template <typename T>
 __global__ __launch_bounds__(256) void ffn_bwd_dx_kernel(
     const T* __restrict__ dG, const T* __restrict__ dU, const TileSched* __restrict__ sched,
@@ -209,7 +216,7 @@ __global__ __launch_bounds__(256) void ffn_bwd_dx_kernel(
   float acc[4][4];
   zero(acc);
   tile_mac(acc, dG + (size_t)tl.row0 * f, f, 1, tl.rows, W1 + n0, d, 1, d - n0, f, sm);
-  tile_mac(acc, dU + (size_t)tl.row0 * f, f, 1, tl.rows, W3 + n0, d, 1, d - n0, f, sm);
+  if (gated) tile_mac(acc, dU + (size_t)tl.row0 * f, f, 1, tl.rows, W3 + n0, d, 1, d - n0, f, sm);
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -308,20 +315,20 @@ int ffn_generic_t(moe_ctx* c, bool gated, const void* xp, void* y, void* G, void
 }
 
 template <typename T>
-int ffn_bwd_generic_t(moe_ctx* c, const void* dy, const void* xp, const void* G, const void* U,
-                      const int32_t* counts, const int32_t* offsets, void* dxp, void* dG, void* dU,
-                      void* H, hipStream_t s) {
+int ffn_bwd_generic_t(moe_ctx* c, bool gated, const void* dy, const void* xp, const void* G,
+                      const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
+                      void* dG, void* dU, void* H, hipStream_t s) {
   const int d = c->cfg.d, f = c->cfg.f, E = c->cfg.E;
   const int mtiles = c->max_mtiles[0];
   const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
-  const void* const* W3 = c->d_wtab + 1 * MOE_MAX_EXPERTS;
+  const void* const* W3 = gated ? c->d_wtab + 1 * MOE_MAX_EXPERTS : nullptr;
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
   const void* const* dW1 = c->d_wtab + 3 * MOE_MAX_EXPERTS;
   const void* const* dW3 = c->d_wtab + 4 * MOE_MAX_EXPERTS;
   const void* const* dW2 = c->d_wtab + 5 * MOE_MAX_EXPERTS;
   hipLaunchKernelGGL((ffn_bwd_dh_kernel<T>), dim3((f + BN - 1) / BN, mtiles), dim3(256), 0, s,
-                     (const T*)dy, (const T*)G, (const T*)U, c->d_sched[0], c->d_mtiles[0], W2, d,
-                     f, (T*)dG, (T*)dU, (T*)H);
+                     (const T*)dy, (const T*)G, gated ? (const T*)U : nullptr, c->d_sched[0],
+                     c->d_mtiles[0], W2, d, f, (T*)dG, (T*)dU, (T*)H);
   hipLaunchKernelGGL((ffn_bwd_dx_kernel<T>), dim3((d + BN - 1) / BN, mtiles), dim3(256), 0, s,
                      (const T*)dG, (const T*)dU, c->d_sched[0], c->d_mtiles[0], W1, W3, d, f,
                      (T*)dxp);
@@ -331,8 +338,9 @@ int ffn_bwd_generic_t(moe_ctx* c, const void* dy, const void* xp, const void* G,
                      counts, offsets, W2, dW2, d, f);
   hipLaunchKernelGGL((ffn_bwd_dw_kernel<T>), g_fd, dim3(256), 0, s, (const T*)dG, (const T*)xp,
                      counts, offsets, W1, dW1, f, d);
-  hipLaunchKernelGGL((ffn_bwd_dw_kernel<T>), g_fd, dim3(256), 0, s, (const T*)dU, (const T*)xp,
-                     counts, offsets, W3, dW3, f, d);
+  if (gated)
+    hipLaunchKernelGGL((ffn_bwd_dw_kernel<T>), g_fd, dim3(256), 0, s, (const T*)dU, (const T*)xp,
+                       counts, offsets, W3, dW3, f, d);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 
@@ -368,12 +376,12 @@ int launch_ffn_generic(moe_ctx* c, bool gated, const void* x_packed, void* y_pac
              : ffn_generic_t<float>(c, gated, x_packed, y_packed, G, U, H_tmp, s);
 }
 
-int launch_ffn_bwd_generic(moe_ctx* c, const void* dy, const void* xp, const void* G,
+int launch_ffn_bwd_generic(moe_ctx* c, bool gated, const void* dy, const void* xp, const void* G,
                            const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
                            void* dG_tmp, void* dU_tmp, void* H_tmp, hipStream_t s) {
   return c->cfg.dtype == MOE_BF16
-             ? ffn_bwd_generic_t<uint16_t>(c, dy, xp, G, U, counts, offsets, dxp, dG_tmp, dU_tmp,
-                                           H_tmp, s)
-             : ffn_bwd_generic_t<float>(c, dy, xp, G, U, counts, offsets, dxp, dG_tmp, dU_tmp,
-                                        H_tmp, s);
+             ? ffn_bwd_generic_t<uint16_t>(c, gated, dy, xp, G, U, counts, offsets, dxp, dG_tmp,
+                                           dU_tmp, H_tmp, s)
+             : ffn_bwd_generic_t<float>(c, gated, dy, xp, G, U, counts, offsets, dxp, dG_tmp,
+                                        dU_tmp, H_tmp, s);
 }

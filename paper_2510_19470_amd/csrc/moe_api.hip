@@ -401,13 +401,16 @@ int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, 
                        float* const* dW3, float* const* dW2, void* stream) {
   int st = check_ctx_T(c, T);
   if (st != MOE_OK) return st;
-  st = check_weight_tables(c, W1, W3, W2);
+  const bool gated = W3 != nullptr;   // no W3 table: the two-matrix expert
+  st = check_weight_tables(c, W1, W3, W2, /*allow_two_matrix=*/true);
   if (st != MOE_OK) return st;
-  if (dW1 == nullptr || dW3 == nullptr || dW2 == nullptr) return MOE_EINVAL;
+  if (dW1 == nullptr || dW2 == nullptr || (dW3 == nullptr) == gated) return MOE_EINVAL;
+  if ((U_save == nullptr) == gated && T > 0) return MOE_EINVAL;
   for (int e = 0; e < c->cfg.E; ++e)
-    if (!aligned16(dW1[e]) || !aligned16(dW3[e]) || !aligned16(dW2[e])) return MOE_EINVAL;
+    if (!aligned16(dW1[e]) || (gated && !aligned16(dW3[e])) || !aligned16(dW2[e]))
+      return MOE_EINVAL;
   if (T == 0) return MOE_OK;
-  if (dy_packed == nullptr || x_packed == nullptr || G_save == nullptr || U_save == nullptr ||
+  if (dy_packed == nullptr || x_packed == nullptr || G_save == nullptr ||
       expert_counts == nullptr || expert_offsets == nullptr || dx_packed == nullptr)
     return MOE_EINVAL;
   if (!aligned16(dy_packed) || !aligned16(x_packed) || !aligned16(G_save) || !aligned16(U_save) ||
@@ -472,7 +475,7 @@ int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, 
                                               w13t};
     st = sync_tables(c, tabs, s);
     if (st != MOE_OK) return st;
-    return launch_ffn_bwd_mfma(c, dy_packed, x_packed, G_save, U_save, expert_counts,
+    return launch_ffn_bwd_mfma(c, gated, dy_packed, x_packed, G_save, U_save, expert_counts,
                                expert_offsets, dx_packed, s);
   }
   if (c->d_dG == nullptr) {  // first backward call on this path: allocate the temporaries
@@ -495,7 +498,7 @@ int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, 
   if (st != MOE_OK) return st;
   st = launch_build_sched(c, expert_counts, expert_offsets, 0, s);
   if (st != MOE_OK) return st;
-  return launch_ffn_bwd_generic(c, dy_packed, x_packed, G_save, U_save, expert_counts,
+  return launch_ffn_bwd_generic(c, gated, dy_packed, x_packed, G_save, U_save, expert_counts,
                                 expert_offsets, dx_packed, c->d_dG, c->d_dU, c->d_H, s);
 }
 

@@ -128,8 +128,9 @@ int launch_ffn_mfma(moe_ctx* c, bool gated, const int32_t* counts, const int32_t
                     const void* x_packed, void* y_packed, void* G, void* U, hipStream_t s);
 bool ffn_bwd_mfma_supported(const moe_ctx* c);
 int ffn_bwd_ktot(const moe_ctx* c);
-int launch_ffn_bwd_mfma(moe_ctx* c, const void* dy, const void* xp, const void* G, const void* U,
-                        const int32_t* counts, const int32_t* offsets, void* dxp, hipStream_t s);
+int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, const void* G,
+                        const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
+                        hipStream_t s);
 size_t route_bwd_workspace_floats(const moe_ctx* c);
 int launch_route_bwd(moe_ctx* c, const void* x, const void* Wg, const float* logits,
                      const int32_t* topk_idx, const float* topk_w, const float* dtopk_w, int T,
@@ -139,6 +140,6 @@ int launch_sr_encode(moe_ctx* c, const void* W, const void* S, int64_t n, int64_
                      int32_t* indices, hipStream_t s);
 int launch_sr_decode(moe_ctx* c, const void* S, const void* values, const int32_t* indices,
                      int64_t n, int64_t k, void* out, hipStream_t s);
-int launch_ffn_bwd_generic(moe_ctx* c, const void* dy, const void* xp, const void* G,
+int launch_ffn_bwd_generic(moe_ctx* c, bool gated, const void* dy, const void* xp, const void* G,
                            const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
                            void* dG_tmp, void* dU_tmp, void* H_tmp, hipStream_t s);

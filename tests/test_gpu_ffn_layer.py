@@ -374,3 +374,57 @@ def test_two_matrix_expert_forward(path, dtype, T, d, E, k, f, skew):
     assert np.all(yg[~done] == 3.0)
     assert nerr(to_host_f32(G)[done], Go[done]) <= TOL[dtype]
     lay.close()
+
+
+@pytest.mark.parametrize("path", ["mfma", "valu"])
+@pytest.mark.parametrize("dtype,T,d,E,k,f,skew", [
+    ("bf16", 900, 512, 4, 2, 1024, 0.5),     # MFMA shapes (f % 256 == 0)
+    ("bf16", 515, 256, 6, 3, 384, 1.5),      # f % 256 != 0: vector-ALU kernels on both paths
+    ("bf16", 300, 512, 16, 1, 256, 2.5),     # experts without tokens
+    ("f32", 300, 128, 8, 2, 256, 0.0),
+])
+def test_two_matrix_expert_backward(path, dtype, T, d, E, k, f, skew):
+    """Backward of the two-matrix expert.  The ReLU mask is a yes/no decision taken on the
+    stored pre-activation, so the oracle gets the GPU's saved G (itself checked against the
+    oracle's own G) and everything downstream is compared to tolerance."""
+    from gpu_common import DEV, TOL, moe, nerr, vals, to_device, to_host_f32, layer_from_inputs, say
+    say(f"[ffn2 bwd] {dtype} path={path} T={T} d={d} E={E} k={k} f={f}")
+    cfg = wl.MoEConfig("ffn2b", 991 + T, dtype, T=T, d=d, E=E, k=k, f=f, R=1)
+    inp = wl.make_inputs(cfg)
+    lay = layer_from_inputs(inp)
+    moe.moe_set_ffn_path(lay.ctx, moe.MOE_FFN_AUTO if path == "mfma" else moe.MOE_FFN_VALU)
+    idx = wl.random_routing(T, E, k, seed=T + 5, skew=skew)
+    cnt, off, _, _, s2r, r2s = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
+    xp_st = orc.pack_rows(inp.x, r2s, k)
+    xp = to_device(xp_st, dtype)
+    rng = np.random.default_rng(T)
+    dy_st = wl.store(rng.standard_normal((cfg.S, d)).astype(np.float32), dtype)
+    dy = to_device(dy_st, dtype)
+    cnt_d, off_d = torch.from_numpy(cnt).to(DEV), torch.from_numpy(off).to(DEV)
+    y, G, U = moe.moe_expert_ffn(lay.ctx, xp, cnt_d, off_d, lay.W1, None, lay.W2, save=True)
+    dxp, dW1, dW3, dW2 = moe.moe_expert_ffn_bwd(lay.ctx, dy, xp, G, None, cnt_d, off_d,
+                                                lay.W1, None, lay.W2)
+    torch.cuda.synchronize()
+    assert dW3 is None
+    W1, W2 = _f64_list(inp.W1, dtype), _f64_list(inp.W2, dtype)
+    tol = TOL[dtype]
+    _, Go = orc.expert_ffn2(vals(xp_st, dtype), cnt, off, W1, W2)
+    Gg = to_host_f32(G).astype(np.float64)
+    assert nerr(Gg, Go) <= tol
+    dxp_o, dW1_o, dW2_o = orc.expert_ffn2_bwd(vals(dy_st, dtype), vals(xp_st, dtype), Gg, cnt, off,
+                                              W1, W2)
+    errs = dict(dxp=nerr(to_host_f32(dxp), dxp_o))
+    scale = max(np.max(np.abs(dW2_o[e])) for e in range(E))
+    for e in range(E):
+        for nm, got, want in (("dW1", dW1[e], dW1_o[e]), ("dW2", dW2[e], dW2_o[e])):
+            g = got.cpu().numpy().astype(np.float64)
+            if cnt[e] == 0:
+                assert np.all(g == 0), (nm, e)
+            errs[f"{nm}[{e}]"] = float(np.max(np.abs(g - want)) / max(np.max(np.abs(want)), 1e-3 * scale))
+    say("    " + ", ".join(f"{k_}={v:.2e}" for k_, v in list(errs.items())[:5]))
+    bad = {k_: v for k_, v in errs.items() if not v <= tol}
+    assert not bad, bad
+    # the wrong combinations are refused on the host
+    with pytest.raises(moe.MoEError):
+        moe.moe_expert_ffn_bwd(lay.ctx, dy, xp, G, G, cnt_d, off_d, lay.W1, None, lay.W2)
+    lay.close()
