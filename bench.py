@@ -128,6 +128,10 @@ def main() -> int:
     ap.add_argument("--no-sr", action="store_true",
                     help="skip the shared/residual compression measurement (one expert matrix, "
                          "outside the timed steps)")
+    ap.add_argument("--chunks", type=int, default=0,
+                    help="also time the chunked overlap schedule (moe_pipeline_forward) with this "
+                         "many chunks on --chunk-streams streams, outside the timed steps")
+    ap.add_argument("--chunk-streams", type=int, default=2)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -317,6 +321,29 @@ def main() -> int:
                             "gbs": by / (t_rb * 1e-3) / 1e9,
                             "note": "dlogits, dWg and dx += dlogits Wg; x read once, dx read and "
                                     "written; not part of the timed step"}
+    if args.chunks > 0:
+        # chunked overlap schedule: the same forward, cut into chunks on several streams
+        pipe = moe.MoEPipeline(T_max=T, d=d, E=E, k=k, f=f, R=R, local_rank=cfg.local_rank,
+                               dtype=lay.ctx.cfg.dtype, n_chunks=args.chunks,
+                               n_streams=args.chunk_streams)
+        pipe.set_placement(inp.dest_rank)
+        pb = pipe.alloc_outputs(T, dev)
+        for _ in range(max(args.warmup, 1)):
+            pipe.forward(x, lay.Wg, lay.bias, lay.W1, lay.W3, lay.W2, pb)
+        e0, e1 = ev(), ev()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            pipe.forward(x, lay.Wg, lay.bias, lay.W1, lay.W3, lay.W2, pb)
+        e1.record()
+        torch.cuda.synchronize()
+        t_pipe = e0.elapsed_time(e1) / args.steps
+        t_seq = sum(call_ms[n] for n in ("route", "dispatch", "expert_ffn", "combine"))
+        rec["chunked_overlap"] = {"n_chunks": args.chunks, "n_streams": args.chunk_streams,
+                                  "ms_per_forward": t_pipe, "unchunked_forward_ms": t_seq,
+                                  "speedup": t_seq / t_pipe,
+                                  "tokens_per_s": T / (t_pipe * 1e-3)}
+        pipe.close()
     if not args.no_cpu_baseline:
         flops_tok = 2.0 * (n_up + 1) * d * f * k * (3 if cfg.backward else 1) + 2.0 * d * E
         sample = args.cpu_sample_tokens or int(max(16, min(cfg.T, 8e12 / flops_tok)))

@@ -270,6 +270,44 @@ int moe_sr_encode(moe_ctx* ctx, const void* expert, const void* shared, int64_t 
 int moe_sr_decode(moe_ctx* ctx, const void* shared, const void* values, const int32_t* indices,
                   int64_t n, int64_t k, void* expert_out, void* stream);
 
+/* ---- Chunked overlap schedule of the forward path --------------------------------------
+ * (Sec. 3.2, stream model: the computation stream and the communication streams work on
+ * different chunks of a layer's data at the same time; Fig. "overlap".)  The T tokens of a
+ * call are cut into n_chunks contiguous chunks of chunk_tokens = the next multiple of 4 of
+ * ceil(T / n_chunks) tokens (the last chunk takes the rest, possibly none); chunk c runs
+ * moe_route -> moe_dispatch -> moe_expert_ffn -> moe_combine on internal stream
+ * c mod n_streams, which has a context of its own.  On one GPU there are no transfers: what
+ * overlaps is the HBM-bound work of one chunk with the expert GEMMs of another.  The result
+ * is that of the four calls made per chunk: every chunk has its own packed layout.
+ *
+ * moe_pipeline_create: cfg as for moe_create with cfg->T_max = most tokens of one call;
+ * 1 <= n_chunks <= 64, 1 <= n_streams <= 8 (streams of default priority, created here).
+ * moe_pipeline_chunk_range: [host] the token range [*t_begin, *t_end) of a chunk for a call
+ * with T tokens.
+ * moe_pipeline_forward: x [dev][T,d], Wg, bias, W1/W3/W2 as in moe_route / moe_expert_ffn
+ * (W3 == NULL: two-matrix expert).  Outputs, all [dev], caller-owned, chunk c at token
+ * offset t_begin(c) (slot / packed-row offset t_begin(c)*k), row numbers relative to the
+ * chunk: topk_idx, topk_w [T,k]; x_packed, y_packed [T*k,d]; slot_to_row, row_to_slot [T*k];
+ * expert_counts, expert_offsets [n_chunks][E]; rank_counts [n_chunks][R]; rank_offsets
+ * [n_chunks][R+1]; out [T,d].  y_packed rows of experts without weights are left as the
+ * caller filled them (rows "received back").  The work is ordered after everything queued
+ * on `stream` before the call, and `stream` waits for it: no host synchronisation.  Calls
+ * on one pipeline must not overlap each other.  Errors as for the four calls; after an
+ * error the streams are still joined. */
+typedef struct moe_pipeline moe_pipeline;
+int moe_pipeline_create(moe_pipeline** out, const moe_config* cfg, int32_t n_chunks,
+                        int32_t n_streams);
+int moe_pipeline_destroy(moe_pipeline* pipe);
+int moe_pipeline_set_placement(moe_pipeline* pipe, const int32_t* expert_dest_rank /*[host][E]*/);
+int moe_pipeline_chunk_range(const moe_pipeline* pipe, int32_t T, int32_t chunk,
+                             int32_t* t_begin, int32_t* t_end);
+int moe_pipeline_forward(moe_pipeline* pipe, const void* x, const void* Wg, const float* bias,
+                         int32_t T, const void* const* W1, const void* const* W3,
+                         const void* const* W2, int32_t* topk_idx, float* topk_w, void* x_packed,
+                         int32_t* slot_to_row, int32_t* row_to_slot, int32_t* expert_counts,
+                         int32_t* expert_offsets, int32_t* rank_counts, int32_t* rank_offsets,
+                         void* y_packed, void* out, void* stream);
+
 /* Measurement aid.  moe_profile_ffn(ctx, n_calls) makes the next n_calls calls of
  * moe_expert_ffn record HIP events on their stream around each internal launch
  * (n_calls = 0 switches it off and frees the events; creates events, so not for use

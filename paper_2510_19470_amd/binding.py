@@ -63,6 +63,11 @@ def load_library(build_if_missing: bool = True):
     lib.moe_combine_bwd.argtypes = [P, P, P, P, P, c_int32, P, P, P]
     lib.moe_expert_ffn_bwd.argtypes = [P, P, P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P]
     lib.moe_dispatch_bwd.argtypes = [P, P, P, c_int32, P, P]
+    lib.moe_pipeline_create.argtypes = [POINTER(c_void_p), POINTER(MoEConfigC), c_int32, c_int32]
+    lib.moe_pipeline_destroy.argtypes = [P]
+    lib.moe_pipeline_set_placement.argtypes = [P, POINTER(c_int32)]
+    lib.moe_pipeline_chunk_range.argtypes = [P, c_int32, c_int32, POINTER(c_int32), POINTER(c_int32)]
+    lib.moe_pipeline_forward.argtypes = [P, P, P, P, c_int32, P, P, P] + [P] * 12
     I32P = POINTER(c_int32)
     lib.moe_plan_location.argtypes = [c_int32, c_int32, I32P, I32P]
     lib.moe_plan_comm_type.argtypes = [c_int32, c_int32, c_int32, c_int32, I32P, I32P, I32P]
@@ -397,3 +402,67 @@ def moe_plan_model(D: float, P_E: float, B: float, lat_pe: float, G: int):
     _check(load_library().moe_plan_model(D, P_E, B, lat_pe, G, ctypes.byref(p), ctypes.byref(case),
                                          ctypes.byref(best)), "moe_plan_model")
     return float(p.value), int(case.value), int(best.value)
+
+
+class MoEPipeline:
+    """Owns a moe_pipeline* (chunked overlap schedule of the forward path)."""
+
+    def __init__(self, T_max: int, d: int, E: int, k: int, f: int, R: int, local_rank: int = 0,
+                 dtype: int = MOE_BF16, renormalize: int = 1, n_chunks: int = 2,
+                 n_streams: int = 2):
+        self.cfg = MoEConfigC(T_max, d, E, k, f, R, local_rank, dtype, renormalize)
+        self.n_chunks = n_chunks
+        self.handle = c_void_p()
+        _check(load_library().moe_pipeline_create(ctypes.byref(self.handle), ctypes.byref(self.cfg),
+                                                  n_chunks, n_streams), "moe_pipeline_create")
+        self.torch_dtype = torch.bfloat16 if dtype == MOE_BF16 else torch.float32
+
+    def set_placement(self, dest_rank) -> None:
+        arr = (c_int32 * self.cfg.E)(*[int(v) for v in dest_rank])
+        _check(load_library().moe_pipeline_set_placement(self.handle, arr),
+               "moe_pipeline_set_placement")
+
+    def chunk_range(self, T: int, chunk: int):
+        a, b = c_int32(), c_int32()
+        _check(load_library().moe_pipeline_chunk_range(self.handle, T, chunk, ctypes.byref(a),
+                                                       ctypes.byref(b)), "moe_pipeline_chunk_range")
+        return a.value, b.value
+
+    def alloc_outputs(self, T: int, device) -> dict:
+        """Caller-owned output buffers of moe_pipeline_forward for T tokens."""
+        c = self.cfg
+        i32 = dict(dtype=torch.int32, device=device)
+        S = T * c.k
+        return dict(
+            topk_idx=torch.empty((T, c.k), **i32),
+            topk_w=torch.empty((T, c.k), dtype=torch.float32, device=device),
+            x_packed=torch.empty((S, c.d), dtype=self.torch_dtype, device=device),
+            slot_to_row=torch.empty(S, **i32), row_to_slot=torch.empty(S, **i32),
+            expert_counts=torch.empty((self.n_chunks, c.E), **i32),
+            expert_offsets=torch.empty((self.n_chunks, c.E), **i32),
+            rank_counts=torch.empty((self.n_chunks, c.R), **i32),
+            rank_offsets=torch.empty((self.n_chunks, c.R + 1), **i32),
+            y_packed=torch.zeros((S, c.d), dtype=self.torch_dtype, device=device),
+            out=torch.empty((T, c.d), dtype=self.torch_dtype, device=device))
+
+    def forward(self, x, Wg, bias, W1, W3, W2, bufs: dict):
+        T = x.shape[0]
+        t3 = None if W3 is None else _table(W3)
+        _check(load_library().moe_pipeline_forward(
+            self.handle, _ptr(x), _ptr(Wg), _ptr(bias), T, _table(W1), t3, _table(W2),
+            _ptr(bufs["topk_idx"]), _ptr(bufs["topk_w"]), _ptr(bufs["x_packed"]),
+            _ptr(bufs["slot_to_row"]), _ptr(bufs["row_to_slot"]), _ptr(bufs["expert_counts"]),
+            _ptr(bufs["expert_offsets"]), _ptr(bufs["rank_counts"]), _ptr(bufs["rank_offsets"]),
+            _ptr(bufs["y_packed"]), _ptr(bufs["out"]), _stream()), "moe_pipeline_forward")
+        return bufs
+
+    def close(self) -> None:
+        if self.handle:
+            load_library().moe_pipeline_destroy(self.handle)
+            self.handle = c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -231,8 +231,8 @@ int moe_sr_encode(moe_ctx* c, const void* expert, const void* shared, int64_t n,
   if (!aligned16(expert) || !aligned16(shared)) return MOE_EINVAL;
   const size_t need = sr_workspace_ints(n);
   if (need > c->sr_ws_ints) {   // grow the workspace (synchronises: earlier calls may use it)
+    (void)hipStreamSynchronize((hipStream_t)stream);
     (void)hipFree(c->d_sr_ws);
-  (void)hipFree(c->d_rbwd_ws);
     c->d_sr_ws = nullptr;
     c->sr_ws_ints = 0;
     if (hipMalloc(reinterpret_cast<void**>(&c->d_sr_ws), need * sizeof(int32_t)) != hipSuccess) {

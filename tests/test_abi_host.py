@@ -63,3 +63,15 @@ def test_binding_has_no_cpu_fallback():
             ctx_cls(T_max=8, d=64, E=4, k=2, f=64, R=2)
     with pytest.raises(ValueError):
         moe.binding._ptr(torch.zeros(4))          # CPU tensors are refused
+
+
+def test_pipeline_create_rejects_invalid_arguments_on_the_host():
+    import ctypes
+    lib = moe.load_library()
+    cfg = moe.MoEConfigC(64, 64, 8, 2, 64, 2, 0, moe.MOE_BF16, 1)
+    h = ctypes.c_void_p()
+    for n_chunks, n_streams in ((0, 1), (65, 1), (2, 0), (2, 9)):
+        assert lib.moe_pipeline_create(ctypes.byref(h), ctypes.byref(cfg), n_chunks, n_streams) == -1
+        assert not h
+    assert lib.moe_pipeline_create(None, ctypes.byref(cfg), 2, 2) == -1
+    assert lib.moe_pipeline_destroy(None) == 0
