@@ -808,14 +808,34 @@ int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, 
   const int gw = gated ? 2 * f : f;   // elements per row of [dG|dU] and of [W1^T|W3^T]
   int st = run_sched(c, counts, offsets, nt_f, nt_d, gw / BK, W2T, nullptr, W13T, c->d_koff, s);
   if (st != MOE_OK) return st;
-  // weights: W2 [d,f] -> W2^T [f,d];  W1, W3 [f,d] -> [W1^T | W3^T] [d,2f]
-  hipLaunchKernelGGL(transpose_weights_kernel, dim3(f / 64, d / 64, E), dim3(256), 0, s, W2, W2T, d,
-                     f, d, 0);
-  hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, s, W1, W13T, f,
+  // The transposes are HBM-bound and the two data-gradient GEMMs leave compute units idle
+  // (few tiles), so everything the first GEMM does not wait for runs beside the GEMMs on the
+  // context's second stream x:
+  //   s: W2^T, dH GEMM ............., dX GEMM ........., weight gradients
+  //   x: [W1^T|W3^T], dY^T, X^T ....| H^T, [dG|dU]^T ..|
+  hipStream_t x = c->aux_stream;
+  hipEvent_t ev_fork = c->aux_ev[0], ev_w13 = c->aux_ev[1], ev_dh = c->aux_ev[2], ev_tr = c->aux_ev[3];
+  uint16_t* dYT = (uint16_t*)c->d_actT;
+  uint16_t* XT = dYT + (size_t)d * Kt;
+  uint16_t* HT = XT + (size_t)d * Kt;
+  uint16_t* dGUT = HT + (size_t)f * Kt;
+  const int kblocks = Kt / 64;
+  bool ok = hipEventRecord(ev_fork, s) == hipSuccess && hipStreamWaitEvent(x, ev_fork, 0) == hipSuccess;
+  if (!ok) return MOE_EHIP;
+  // weights: W1, W3 [f,d] -> [W1^T | W3^T] [d,2f] (second stream); W2 [d,f] -> W2^T [f,d]
+  hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, x, W1, W13T, f,
                      d, gw, 0);
   if (gated)
-    hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, s, W3, W13T,
+    hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, x, W3, W13T,
                        f, d, gw, f);
+  ok = ok && hipEventRecord(ev_w13, x) == hipSuccess;
+  // activations transposed per expert segment (zero padded to x128 rows)
+  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, d / 64), dim3(256), 0, x,
+                     (const uint16_t*)dy, d, d, counts, offsets, c->d_koff, E, dYT, Kt);
+  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, d / 64), dim3(256), 0, x,
+                     (const uint16_t*)xp, d, d, counts, offsets, c->d_koff, E, XT, Kt);
+  hipLaunchKernelGGL(transpose_weights_kernel, dim3(f / 64, d / 64, E), dim3(256), 0, s, W2, W2T, d,
+                     f, d, 0);
   // dH = dY W2 with the activation's derivative in the epilogue -> [dG|dU], H
   GemmArgs dh = tiled_args(c, dy, d, c->d_order_up, nt_f, d, f, c->d_dGU);
   dh.C2 = (uint16_t*)c->d_H;
@@ -825,23 +845,19 @@ int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, 
     hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
   else
     hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH1>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
+  ok = ok && hipEventRecord(ev_dh, s) == hipSuccess && hipStreamWaitEvent(x, ev_dh, 0) == hipSuccess;
+  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, f / 64), dim3(256), 0, x,
+                     (const uint16_t*)c->d_H, f, f, counts, offsets, c->d_koff, E, HT, Kt);
+  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, gw / 64), dim3(256), 0, x,
+                     (const uint16_t*)c->d_dGU, gw, gw, counts, offsets, c->d_koff, E, dGUT, Kt);
+  ok = ok && hipEventRecord(ev_tr, x) == hipSuccess;
   // dX = [dG|dU] [W1^T|W3^T]^T  (one GEMM with contraction length 2f; f without U)
+  ok = ok && hipStreamWaitEvent(s, ev_w13, 0) == hipSuccess;
   GemmArgs dx = tiled_args(c, c->d_dGU, gw, c->d_order_down, nt_d, gw, d, dxp);
   launch_down(c, dx, nt_d, s);
-  // activations transposed per expert segment (zero padded to x128 rows)
-  uint16_t* dYT = (uint16_t*)c->d_actT;
-  uint16_t* XT = dYT + (size_t)d * Kt;
-  uint16_t* HT = XT + (size_t)d * Kt;
-  uint16_t* dGUT = HT + (size_t)f * Kt;
-  const int kblocks = Kt / 64;
-  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, d / 64), dim3(256), 0, s,
-                     (const uint16_t*)dy, d, d, counts, offsets, c->d_koff, E, dYT, Kt);
-  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, d / 64), dim3(256), 0, s,
-                     (const uint16_t*)xp, d, d, counts, offsets, c->d_koff, E, XT, Kt);
-  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, f / 64), dim3(256), 0, s,
-                     (const uint16_t*)c->d_H, f, f, counts, offsets, c->d_koff, E, HT, Kt);
-  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, gw / 64), dim3(256), 0, s,
-                     (const uint16_t*)c->d_dGU, gw, gw, counts, offsets, c->d_koff, E, dGUT, Kt);
+  // join: the weight gradients read all four transposed activation arrays
+  ok = ok && hipStreamWaitEvent(s, ev_tr, 0) == hipSuccess;
+  if (!ok) return MOE_EHIP;
   // weight gradients, fp32
   GemmArgs w{};
   w.lda = Kt;

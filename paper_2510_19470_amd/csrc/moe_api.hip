@@ -39,6 +39,9 @@ void free_all(moe_ctx* c) {
   (void)hipFree(c->d_actT);
   (void)hipFree(c->d_koff);
   (void)hipFree(c->d_wT);
+  if (c->aux_stream != nullptr) (void)hipStreamDestroy(c->aux_stream);
+  for (hipEvent_t e : c->aux_ev)
+    if (e != nullptr) (void)hipEventDestroy(e);
 }
 
 int check_ctx_T(const moe_ctx* c, int32_t T) {
@@ -437,6 +440,21 @@ int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, 
         c->d_dGU = c->d_actT = nullptr;
         c->d_koff = nullptr;
         return MOE_ENOMEM;
+      }
+    }
+    if (c->aux_stream == nullptr) {
+      bool ok = hipStreamCreateWithFlags(&c->aux_stream, hipStreamNonBlocking) == hipSuccess;
+      for (int i = 0; i < 4 && ok; ++i)
+        ok = hipEventCreateWithFlags(&c->aux_ev[i], hipEventDisableTiming) == hipSuccess;
+      if (!ok) {
+        (void)hipGetLastError();
+        if (c->aux_stream != nullptr) (void)hipStreamDestroy(c->aux_stream);
+        c->aux_stream = nullptr;
+        for (hipEvent_t& e : c->aux_ev) {
+          if (e != nullptr) (void)hipEventDestroy(e);
+          e = nullptr;
+        }
+        return MOE_EHIP;
       }
     }
     if (n_present > c->wT_experts) {

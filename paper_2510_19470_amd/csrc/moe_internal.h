@@ -77,6 +77,10 @@ struct moe_ctx {
   int32_t* d_koff;        // [E+1] padded row offsets of the experts in d_actT
   void* d_wT;             // transposed weights of the MFMA backward
   size_t wT_experts;      // experts d_wT has room for
+  // MFMA backward: the transposes run on a second stream (default priority) beside the
+  // GEMMs; events fork it from / join it into the caller's stream
+  hipStream_t aux_stream;
+  hipEvent_t aux_ev[4];   // fork, [W1^T|W3^T] ready, dH done, transposes done
   // gate backward: per-chunk partial sums of dWg, [T_max/128][E][d] (first call allocates)
   float* d_rbwd_ws;
   // shared/residual compression: selection state, histogram, per-chunk counts
