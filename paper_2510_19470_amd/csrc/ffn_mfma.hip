@@ -26,9 +26,10 @@
 // weight rows as soon as both groups have read them (first cluster of a step), each with
 // the data of two steps ahead: copies are spread evenly over the step and have more
 // than one step to land.
-// Tile order: tiles of one expert that share a weight panel (same column block) are
-// consecutive, and the block index is remapped so that each of the 8 XCDs (private L2)
-// works on a contiguous range of that order.
+// Tile order: an expert's row blocks in groups of 8; inside a group the tiles that share a
+// weight panel (same column block) are consecutive, and the block index is remapped so that
+// each of the 8 XCDs (private L2) works on a contiguous range of that order: the 32 tiles an
+// XCD has in flight are 8 row blocks x 4 column blocks.
 #include "moe_internal.h"
 #include "numeric.h"
 
@@ -44,6 +45,7 @@ constexpr int BNW = 256;          // weight rows per block tile
 constexpr int BK = 64;            // k per stage
 constexpr int NT = 512;           // threads
 constexpr int STAGE_VEC = 2048;   // uint4 per operand per stage (256 rows x 8 chunks)
+constexpr int ORDER_GROUP_M = 8;  // row blocks per group of the tile order
 
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
 
@@ -117,8 +119,8 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
   }
   const int gsz = gridDim.x * blockDim.x;
   const int gid = blockIdx.x * blockDim.x + tid;
-  // tile order: expert by expert; inside an expert column block by column block, and for
-  // one column block all of the expert's row blocks in a row (they share a weight panel)
+  // tile order: expert by expert; inside an expert in groups of 8 row blocks; inside a group
+  // column block by column block, the group's row blocks in a row (they share a weight panel)
   for (int pass = 0; pass < 2; ++pass) {
     const int nt = pass == 0 ? nt_up : nt_down;
     TileDesc* order = pass == 0 ? order_up : order_down;
@@ -131,7 +133,12 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
       }
       const int me = start[lo + 1] - start[lo];
       const int rel = L - start[lo] * nt;
-      const int n = rel / me, m = rel % me;
+      // groups of up to 8 row blocks: inside a group column block by column block, so that 32
+      // consecutive tiles are 8 row blocks x 4 column blocks (12 panels for 32 tiles)
+      const int per_group = ORDER_GROUP_M * nt;
+      const int mg = rel / per_group, r2 = rel % per_group;
+      const int gm = min(ORDER_GROUP_M, me - mg * ORDER_GROUP_M);
+      const int n = r2 / gm, m = mg * ORDER_GROUP_M + r2 % gm;
       TileDesc t;
       t.row0 = offsets[lo] + m * BM;
       t.rows = min(BM, counts[lo] - m * BM);
@@ -155,6 +162,21 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 __device__ __forceinline__ void dma16(uint32_t off, const char* base, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_addr)
                : "memory", "m0");
+}
+
+// Epilogue stores.  A lane holds, per accumulator, 4 consecutive output columns 8g + 4h + {0..3}
+// (h = lane >> 5) of one token row for g = 0..3: 8-byte pieces.  Swapping between the two
+// half-wavefronts turns the pieces of g and g+1 into one 16-byte piece per lane -- lanes 0-31
+// get columns 8g .. 8g+7, lanes 32-63 columns 8(g+1) .. 8(g+1)+7 of their row -- so that a
+// wavefront stores 32 contiguous bytes per row with one instruction instead of 16 with two.
+__device__ __forceinline__ uint4 pair16(uint2 a /* piece g */, uint2 b /* piece g+1 */) {
+  // v_permlane32_swap: lanes 32-63 of the first operand <-> lanes 0-31 of the second
+  const auto x = __builtin_amdgcn_permlane32_swap(a.x, b.x, false, false);
+  const auto y = __builtin_amdgcn_permlane32_swap(a.y, b.y, false, false);
+  return make_uint4(x[0], y[0], x[1], y[1]);
+}
+__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
+  return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
 }
 
 enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_WGRAD = 3, MODE_UP1 = 4, MODE_DH1 = 5 };
@@ -388,11 +410,10 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
                                                          acc[j][i][q * 4 + 2], acc[j][i][q * 4 + 3]);
       return;
     }
+    if (MODE == MODE_WGRAD) {   // fp32 weight gradient: 16 bytes per lane as the accumulator has them
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m_local = wm * 128 + i * 32 + fr_row;
-      if (m_local >= u.rows) continue;
-      if (MODE == MODE_WGRAD) {
+      for (int i = 0; i < 4; ++i) {
+        const int m_local = wm * 128 + i * 32 + fr_row;
         float* orow = dW + (size_t)(mblk * 256 + m_local) * w_No;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -403,86 +424,111 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
                 make_float4(acc[j][i][g * 4], acc[j][i][g * 4 + 1], acc[j][i][g * 4 + 2],
                             acc[j][i][g * 4 + 3]);
         }
-        continue;
       }
+      return;
+    }
+    // bf16 outputs: every lane takes part in the half-wavefront swaps, only the stores are
+    // predicated on the row being inside the tile; gp = 0, 1 are the column pairs g = (0,1), (2,3)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m_local = wm * 128 + i * 32 + fr_row;
+      const bool live = m_local < u.rows;
       const size_t row = (size_t)(u.row0 + m_local);
       if (MODE == MODE_UP) {
-        const int col0 = u.nblk * 128 + wn * 32 + 4 * fr_half;
+        const int colb = u.nblk * 128 + wn * 32 + 8 * fr_half;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float h[4];
+        for (int gp = 0; gp < 2; ++gp) {
+          uint2 hp[2];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float gv = acc[0][i][g * 4 + r], uv = acc[1][i][g * 4 + r];
-            h[r] = silu_f(gv) * uv;
+          for (int t = 0; t < 2; ++t) {
+            const int g = 2 * gp + t;
+            float h[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) h[r] = silu_f(acc[0][i][g * 4 + r]) * acc[1][i][g * 4 + r];
+            hp[t] = pack4(h[0], h[1], h[2], h[3]);
           }
-          const size_t o = row * p.N + col0 + 8 * g;
-          *reinterpret_cast<uint2*>(p.C + o) =
-              make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+          const size_t o = row * p.N + colb + 16 * gp;
+          const uint4 hv = pair16(hp[0], hp[1]);
+          if (live) *reinterpret_cast<uint4*>(p.C + o) = hv;
           if (p.Gs != nullptr) {
-            *reinterpret_cast<uint2*>(p.Gs + o) =
-                make_uint2(pack_bf16x2(acc[0][i][g * 4], acc[0][i][g * 4 + 1]),
-                           pack_bf16x2(acc[0][i][g * 4 + 2], acc[0][i][g * 4 + 3]));
-            *reinterpret_cast<uint2*>(p.Us + o) =
-                make_uint2(pack_bf16x2(acc[1][i][g * 4], acc[1][i][g * 4 + 1]),
-                           pack_bf16x2(acc[1][i][g * 4 + 2], acc[1][i][g * 4 + 3]));
+            const int g = 2 * gp;
+            const uint4 gv = pair16(pack4(acc[0][i][g * 4], acc[0][i][g * 4 + 1], acc[0][i][g * 4 + 2], acc[0][i][g * 4 + 3]),
+                                    pack4(acc[0][i][g * 4 + 4], acc[0][i][g * 4 + 5], acc[0][i][g * 4 + 6], acc[0][i][g * 4 + 7]));
+            const uint4 uv = pair16(pack4(acc[1][i][g * 4], acc[1][i][g * 4 + 1], acc[1][i][g * 4 + 2], acc[1][i][g * 4 + 3]),
+                                    pack4(acc[1][i][g * 4 + 4], acc[1][i][g * 4 + 5], acc[1][i][g * 4 + 6], acc[1][i][g * 4 + 7]));
+            if (live) {
+              *reinterpret_cast<uint4*>(p.Gs + o) = gv;
+              *reinterpret_cast<uint4*>(p.Us + o) = uv;
+            }
           }
         }
       } else {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          const int col0 = u.nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
+          const int colb = u.nblk * 256 + j * 128 + wn * 32 + 8 * fr_half;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int col = col0 + 8 * g;
+          for (int gp = 0; gp < 2; ++gp) {
+            const int g0 = 2 * gp;
+            const size_t col = colb + 16 * gp;
             if (MODE == MODE_DOWN) {
-              *reinterpret_cast<uint2*>(p.C + row * p.N + col) =
-                  make_uint2(pack_bf16x2(acc[j][i][g * 4], acc[j][i][g * 4 + 1]),
-                             pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]));
+              const uint4 v = pair16(pack4(acc[j][i][g0 * 4], acc[j][i][g0 * 4 + 1], acc[j][i][g0 * 4 + 2], acc[j][i][g0 * 4 + 3]),
+                                     pack4(acc[j][i][g0 * 4 + 4], acc[j][i][g0 * 4 + 5], acc[j][i][g0 * 4 + 6], acc[j][i][g0 * 4 + 7]));
+              if (live) *reinterpret_cast<uint4*>(p.C + row * p.N + col) = v;
             } else if (MODE == MODE_UP1) {
-              *reinterpret_cast<uint2*>(p.C + row * p.N + col) =
-                  make_uint2(pack_bf16x2(fmaxf(acc[j][i][g * 4], 0.f), fmaxf(acc[j][i][g * 4 + 1], 0.f)),
-                             pack_bf16x2(fmaxf(acc[j][i][g * 4 + 2], 0.f), fmaxf(acc[j][i][g * 4 + 3], 0.f)));
-              if (p.Gs != nullptr)
-                *reinterpret_cast<uint2*>(p.Gs + row * p.N + col) =
-                    make_uint2(pack_bf16x2(acc[j][i][g * 4], acc[j][i][g * 4 + 1]),
-                               pack_bf16x2(acc[j][i][g * 4 + 2], acc[j][i][g * 4 + 3]));
-            } else if (MODE == MODE_DH1) {
-              // two-matrix expert: dG = dH where g > 0, H = max(g, 0)
-              const uint2 gq = *reinterpret_cast<const uint2*>(p.Gs + row * p.N + col);
-              const uint32_t gw[2] = {gq.x, gq.y};
-              float dg[4], hh[4];
+              float r[8];
 #pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                const float gv = __uint_as_float((r & 1) ? (gw[r >> 1] & 0xffff0000u) : (gw[r >> 1] << 16));
-                dg[r] = gv > 0.f ? acc[j][i][g * 4 + r] : 0.f;
-                hh[r] = fmaxf(gv, 0.f);
+              for (int q = 0; q < 8; ++q) r[q] = fmaxf(acc[j][i][g0 * 4 + q], 0.f);
+              const uint4 v = pair16(pack4(r[0], r[1], r[2], r[3]), pack4(r[4], r[5], r[6], r[7]));
+              if (live) *reinterpret_cast<uint4*>(p.C + row * p.N + col) = v;
+              if (p.Gs != nullptr) {
+                const uint4 gv = pair16(pack4(acc[j][i][g0 * 4], acc[j][i][g0 * 4 + 1], acc[j][i][g0 * 4 + 2], acc[j][i][g0 * 4 + 3]),
+                                        pack4(acc[j][i][g0 * 4 + 4], acc[j][i][g0 * 4 + 5], acc[j][i][g0 * 4 + 6], acc[j][i][g0 * 4 + 7]));
+                if (live) *reinterpret_cast<uint4*>(p.Gs + row * p.N + col) = gv;
               }
-              *reinterpret_cast<uint2*>(p.C + row * p.N + col) =
-                  make_uint2(pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3]));
-              *reinterpret_cast<uint2*>(p.C2 + row * p.N + col) =
-                  make_uint2(pack_bf16x2(hh[0], hh[1]), pack_bf16x2(hh[2], hh[3]));
-            } else {  // MODE_DH
-              const uint2 gq = *reinterpret_cast<const uint2*>(p.Gs + row * p.N + col);
-              const uint2 uq = *reinterpret_cast<const uint2*>(p.Us + row * p.N + col);
-              const uint32_t gw[2] = {gq.x, gq.y}, uw[2] = {uq.x, uq.y};
-              float dg[4], du[4], hh[4];
+            } else {  // MODE_DH, MODE_DH1: saved G (and U) are read in the accumulator's own layout
+              uint2 dgp[2], dup[2], hhp[2];
 #pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                const float gv = __uint_as_float((r & 1) ? (gw[r >> 1] & 0xffff0000u) : (gw[r >> 1] << 16));
-                const float uv = __uint_as_float((r & 1) ? (uw[r >> 1] & 0xffff0000u) : (uw[r >> 1] << 16));
-                const float dh = acc[j][i][g * 4 + r];
-                const float sg = sigmoid_f(gv);
-                dg[r] = dh * uv * sg * (1.f + gv * (1.f - sg));
-                du[r] = dh * gv * sg;
-                hh[r] = gv * sg * uv;
+              for (int t = 0; t < 2; ++t) {
+                const int g = g0 + t;
+                const size_t cg = (size_t)u.nblk * 256 + j * 128 + wn * 32 + 4 * fr_half + 8 * g;
+                uint2 gq = make_uint2(0, 0), uq = make_uint2(0, 0);
+                if (live) {
+                  gq = *reinterpret_cast<const uint2*>(p.Gs + row * p.N + cg);
+                  if (MODE == MODE_DH) uq = *reinterpret_cast<const uint2*>(p.Us + row * p.N + cg);
+                }
+                const uint32_t gw[2] = {gq.x, gq.y}, uw[2] = {uq.x, uq.y};
+                float dg[4], du[4], hh[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                  const float gv = __uint_as_float((r & 1) ? (gw[r >> 1] & 0xffff0000u) : (gw[r >> 1] << 16));
+                  const float dh = acc[j][i][g * 4 + r];
+                  if (MODE == MODE_DH1) {   // two-matrix expert: dG = dH where g > 0, H = max(g, 0)
+                    dg[r] = gv > 0.f ? dh : 0.f;
+                    du[r] = 0.f;
+                    hh[r] = fmaxf(gv, 0.f);
+                  } else {
+                    const float uv = __uint_as_float((r & 1) ? (uw[r >> 1] & 0xffff0000u) : (uw[r >> 1] << 16));
+                    const float sg = sigmoid_f(gv);
+                    dg[r] = dh * uv * sg * (1.f + gv * (1.f - sg));
+                    du[r] = dh * gv * sg;
+                    hh[r] = gv * sg * uv;
+                  }
+                }
+                dgp[t] = pack4(dg[0], dg[1], dg[2], dg[3]);
+                dup[t] = pack4(du[0], du[1], du[2], du[3]);
+                hhp[t] = pack4(hh[0], hh[1], hh[2], hh[3]);
               }
-              *reinterpret_cast<uint2*>(p.C + row * (2 * (size_t)p.N) + col) =
-                  make_uint2(pack_bf16x2(dg[0], dg[1]), pack_bf16x2(dg[2], dg[3]));
-              *reinterpret_cast<uint2*>(p.C + row * (2 * (size_t)p.N) + p.N + col) =
-                  make_uint2(pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3]));
-              *reinterpret_cast<uint2*>(p.C2 + row * p.N + col) =
-                  make_uint2(pack_bf16x2(hh[0], hh[1]), pack_bf16x2(hh[2], hh[3]));
+              const uint4 dgv = pair16(dgp[0], dgp[1]), hhv = pair16(hhp[0], hhp[1]);
+              if (MODE == MODE_DH) {
+                const uint4 duv = pair16(dup[0], dup[1]);
+                if (live) {
+                  *reinterpret_cast<uint4*>(p.C + row * (2 * (size_t)p.N) + col) = dgv;
+                  *reinterpret_cast<uint4*>(p.C + row * (2 * (size_t)p.N) + p.N + col) = duv;
+                }
+              } else if (live) {
+                *reinterpret_cast<uint4*>(p.C + row * p.N + col) = dgv;
+              }
+              if (live) *reinterpret_cast<uint4*>(p.C2 + row * p.N + col) = hhv;
             }
           }
         }
