@@ -261,13 +261,16 @@ int launch_gate_route_fused(const moe_ctx* c, const void* x, const void* Wg, con
                             int T, float* logits, int32_t* idx, float* w, hipStream_t s) {
   if (T == 0) return MOE_OK;
   const int E = c->cfg.E;
+  // a group of 8 lanes per token (8 tokens per wavefront) up to 64 experts: the selection
+  // costs (experts per lane + 3 butterfly levels) per round instead of 6 butterfly levels,
+  // and the block's 32 tokens are selected in one pass by four wavefronts
   if (E <= 2) return launch_gate<2, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
   if (E <= 4) return launch_gate<4, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
   if (E <= 8) return launch_gate<8, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 16) return launch_gate<16, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 32) return launch_gate<32, 1, 2>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 48) return launch_gate<64, 1, 3>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 64) return launch_gate<64, 1, 4>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 16) return launch_gate<8, 2, 1>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 32) return launch_gate<8, 4, 2>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 48) return launch_gate<8, 6, 3>(c, x, Wg, bias, T, logits, idx, w, s);
+  if (E <= 64) return launch_gate<8, 8, 4>(c, x, Wg, bias, T, logits, idx, w, s);
   if (E <= 128) return launch_gate<64, 2, 4>(c, x, Wg, bias, T, logits, idx, w, s);
   if (E <= 256) return launch_gate<64, 4, 4>(c, x, Wg, bias, T, logits, idx, w, s);
   return MOE_EUNSUPPORTED;
