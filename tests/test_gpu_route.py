@@ -64,3 +64,30 @@ def test_route_gate_projection_and_selection(name, T):
     torch.cuda.synchronize()
     assert torch.equal(idx, idx2) and torch.equal(w, w2)
     ctx.close()
+
+
+@pytest.mark.parametrize("T,E,k,d", [(333, 4, 2, 256), (1000, 24, 3, 512), (515, 48, 6, 256),
+                                     (700, 100, 8, 512), (260, 256, 16, 256), (31, 2, 1, 256)])
+def test_fused_gate_every_expert_count_branch(T, E, k, d):
+    """The fused bf16 gate kernel picks its selection group width and expert blocking from E:
+    one case per branch, ragged T, with a bias; indices exact on the GPU's logits."""
+    from gpu_common import DEV, moe, say, i32, nerr, vals, to_device
+    say(f"[route fused] T={T} E={E} k={k} d={d}")
+    cfg = wl.MoEConfig("gate", 31 + T + E, "bf16", T=T, d=d, E=E, k=k, f=256, R=1, bias_scale=0.7)
+    inp = wl.make_inputs(cfg, experts="none")
+    ctx = moe.moe_create(T_max=T, d=d, E=E, k=k, f=256, R=1, dtype=moe.MOE_BF16)
+    x, Wg = to_device(inp.x, "bf16"), to_device(inp.Wg, "bf16")
+    bias = None if inp.bias is None else torch.from_numpy(inp.bias).to(DEV)
+    idx, w, logits = moe.moe_route(ctx, x, Wg, bias, want_logits=True)
+    torch.cuda.synchronize()
+    Lg = logits.cpu().numpy()
+    assert nerr(Lg, orc.gate_logits(vals(inp.x, "bf16"), vals(inp.Wg, "bf16"), inp.bias)) <= 1e-5
+    want_idx = orc.topk_select(Lg, k)
+    assert np.array_equal(i32(idx), want_idx)
+    assert np.max(np.abs(w.cpu().numpy() - orc.topk_weights(Lg, want_idx, True))) <= 1e-5
+    # moe_route_logits on the same logits selects identically (other group width, same order)
+    idx2, w2 = moe.moe_route_logits(ctx, logits)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2)
+    assert torch.max(torch.abs(w - w2)).item() <= 1e-6
+    ctx.close()
