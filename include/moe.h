@@ -314,9 +314,14 @@ int moe_pipeline_forward(moe_pipeline* pipe, const void* x, const void* Wg, cons
  * under graph capture).  moe_profile_ffn_read synchronises with those events and returns
  * the average duration in milliseconds of each launch over the recorded calls:
  * ms[0] tile schedule, ms[1] gate/up GEMM (+SwiGLU), ms[2] down GEMM; *n_recorded = calls
- * averaged.  ms [host][MOE_PROF_SLOTS]. */
+ * averaged.  ms [host][MOE_PROF_SLOTS].
+ * moe_profile_ffn_launches(ctx, mask) restricts the timing to the launches whose bit is set
+ * (bit 0 schedule, 1 gate/up, 2 down; default all): an event record costs a few microseconds
+ * of idle GPU, so a caller that times a whole step wants only the launch it reports; the
+ * others read as 0.  MOE_EINVAL for an empty mask or while calls are recorded and not read. */
 #define MOE_PROF_SLOTS 3
 int moe_profile_ffn(moe_ctx* ctx, int32_t n_calls);
+int moe_profile_ffn_launches(moe_ctx* ctx, int32_t mask);
 int moe_profile_ffn_read(moe_ctx* ctx, float* ms, int32_t* n_recorded);
 
 #ifdef __cplusplus

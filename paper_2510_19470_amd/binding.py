@@ -63,6 +63,7 @@ def load_library(build_if_missing: bool = True):
     lib.moe_combine_bwd.argtypes = [P, P, P, P, P, c_int32, P, P, P]
     lib.moe_expert_ffn_bwd.argtypes = [P, P, P, P, P, P, P, P, P, P, c_int32, P, P, P, P, P]
     lib.moe_dispatch_bwd.argtypes = [P, P, P, c_int32, P, P]
+    lib.moe_profile_ffn_launches.argtypes = [P, c_int32]
     lib.moe_pipeline_create.argtypes = [POINTER(c_void_p), POINTER(MoEConfigC), c_int32, c_int32]
     lib.moe_pipeline_destroy.argtypes = [P]
     lib.moe_pipeline_set_placement.argtypes = [P, POINTER(c_int32)]
@@ -319,6 +320,11 @@ def moe_route_bwd(ctx, x, Wg, topk_idx, topk_w, dtopk_w, logits=None, dx=None, w
 
 def moe_profile_ffn(ctx, n_calls: int) -> None:
     _check(load_library().moe_profile_ffn(ctx.handle, n_calls), "moe_profile_ffn")
+
+
+def moe_profile_ffn_launches(ctx, mask: int) -> None:
+    """bit 0 schedule, 1 gate/up, 2 down: which launches of moe_expert_ffn are timed."""
+    _check(load_library().moe_profile_ffn_launches(ctx.handle, mask), "moe_profile_ffn_launches")
 
 
 def moe_profile_ffn_read(ctx):

@@ -197,6 +197,13 @@ int moe_profile_ffn(moe_ctx* c, int32_t n_calls) {
       return MOE_EHIP;
     }
   c->prof_calls = n_calls;
+  if (c->prof_mask == 0) c->prof_mask = (1 << MOE_PROF_SLOTS) - 1;
+  return MOE_OK;
+}
+
+int moe_profile_ffn_launches(moe_ctx* c, int32_t mask) {
+  if (c == nullptr || mask < 1 || mask >= (1 << MOE_PROF_SLOTS) || c->prof_n != 0) return MOE_EINVAL;
+  c->prof_mask = mask;
   return MOE_OK;
 }
 
@@ -205,10 +212,14 @@ int moe_profile_ffn_read(moe_ctx* c, float* ms, int32_t* n_recorded) {
   for (int i = 0; i < MOE_PROF_SLOTS; ++i) ms[i] = 0.f;
   *n_recorded = c->prof_n;
   if (c->prof_n == 0) return MOE_OK;
+  int last = 0;   // last event recorded in a call
+  for (int i = 0; i < MOE_PROF_SLOTS; ++i)
+    if ((c->prof_mask >> i) & 1) last = i + 1;
   for (int call = 0; call < c->prof_n; ++call) {
     hipEvent_t* ev = c->prof_ev + (size_t)call * (MOE_PROF_SLOTS + 1);
-    if (hipEventSynchronize(ev[MOE_PROF_SLOTS]) != hipSuccess) return MOE_EHIP;
+    if (hipEventSynchronize(ev[last]) != hipSuccess) return MOE_EHIP;
     for (int i = 0; i < MOE_PROF_SLOTS; ++i) {
+      if (!((c->prof_mask >> i) & 1)) continue;
       float t = 0.f;
       if (hipEventElapsedTime(&t, ev[i], ev[i + 1]) != hipSuccess) return MOE_EHIP;
       ms[i] += t;

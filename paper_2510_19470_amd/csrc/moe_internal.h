@@ -89,12 +89,14 @@ struct moe_ctx {
   // optional HIP-event timing of the internal launches of moe_expert_ffn
   int prof_calls;         // capacity in calls (0 = off)
   int prof_n;             // calls recorded so far
+  int prof_mask;          // bit i: launch i is timed (events i and i+1 are recorded)
   hipEvent_t* prof_ev;    // [prof_calls][MOE_PROF_SLOTS + 1]
 };
 
 // Records event `slot` of the current profiled call (no-op when profiling is off).
 inline void prof_mark(moe_ctx* c, int slot, hipStream_t s) {
-  if (c->prof_calls > 0 && c->prof_n < c->prof_calls)
+  const int need = c->prof_mask | (c->prof_mask << 1);   // event i brackets launches i-1 and i
+  if (c->prof_calls > 0 && c->prof_n < c->prof_calls && ((need >> slot) & 1))
     (void)hipEventRecord(c->prof_ev[(size_t)c->prof_n * (MOE_PROF_SLOTS + 1) + slot], s);
 }
 
