@@ -133,6 +133,9 @@ def main() -> int:
                     help="also time the chunked overlap schedule (moe_pipeline_forward) with this "
                          "many chunks on --chunk-streams streams, outside the timed steps")
     ap.add_argument("--chunk-streams", type=int, default=2)
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one step into a HIP graph and time its replays (outside the "
+                         "timed steps)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -336,6 +339,25 @@ def main() -> int:
                             "gbs": by / (t_rb * 1e-3) / 1e9,
                             "note": "dlogits, dWg and dx += dlogits Wg; x read once, dx read and "
                                     "written; not part of the timed step"}
+    if args.graph:
+        # the same step captured once into a HIP graph (the calls launch kernels only)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(max(args.warmup, 1)):
+            graph.replay()
+        e0, e1 = ev(), ev()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        t_graph = e0.elapsed_time(e1) / args.steps
+        rec["graph_replay"] = {"ms_per_step": t_graph, "tokens_per_s": T / (t_graph * 1e-3),
+                               "eager_ms_per_step": ms_per_step}
     if args.chunks > 0:
         # chunked overlap schedule: the same forward, cut into chunks on several streams
         pipe = moe.MoEPipeline(T_max=T, d=d, E=E, k=k, f=f, R=R, local_rank=cfg.local_rank,
