@@ -16,10 +16,13 @@
 //      and writes it to its k packed rows.  Block 0 also writes counts / offsets / rank
 //      chunks.
 // The permutation is deterministic: no atomic decides a row number.
-// The totals start at zero and are left at zero: every scatter block takes a ticket once it
-// has read them, and the block with the last ticket clears them (and the ticket counter) for
-// the next call.  No state on the host changes from call to call, so a captured graph of the
-// two launches can be replayed.
+// The totals are double-buffered: call n accumulates into buffer n&1 and clears the other
+// one for call n+1.  The call number lives on the device, in two words so that no block reads
+// a word that another block of the same launch writes: the count kernel reads ctr[0] and
+// writes ctr[1] = ctr[0] + 1, the scatter kernel reads ctr[1] and writes ctr[0] = ctr[1].
+// Nothing on the host changes from call to call, so a captured graph of the two launches can
+// be replayed.  (A ticket per scatter block with the last block clearing the totals doubled
+// the kernel's time: 4096 returning atomics on one address.)
 #include "moe_internal.h"
 
 namespace {
@@ -40,7 +43,7 @@ constexpr int COUNT_WAVES = COUNT_THREADS / 64;
 
 __global__ __launch_bounds__(COUNT_THREADS) void dispatch_count_kernel(
     const int32_t* __restrict__ topk_idx, int S, int E, int ebits,
-    int32_t* __restrict__ chunk_hist, int32_t* __restrict__ totals,
+    int32_t* __restrict__ chunk_hist, int32_t* __restrict__ totals2,
     int32_t* __restrict__ slot_rank) {
   __shared__ int32_t wcnt[COUNT_WAVES][MOE_MAX_EXPERTS];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -52,6 +55,13 @@ __global__ __launch_bounds__(COUNT_THREADS) void dispatch_count_kernel(
     if ((unsigned)e >= (unsigned)E) e = -1;
   }
   for (int i = tid; i < COUNT_WAVES * MOE_MAX_EXPERTS; i += COUNT_THREADS) (&wcnt[0][0])[i] = 0;
+  int32_t* ctr = totals2 + 2 * MOE_MAX_EXPERTS;
+  const int call = ctr[0];
+  int32_t* totals = totals2 + (call & 1) * MOE_MAX_EXPERTS;
+  if (b == 0) {
+    if (tid < MOE_MAX_EXPERTS) totals2[((call + 1) & 1) * MOE_MAX_EXPERTS + tid] = 0;
+    if (tid == 0) ctr[1] = call + 1;
+  }
   __syncthreads();
   const unsigned long long same = match_same(e, ebits);
   const int in_wave = __popcll(same & ((1ull << lane) - 1ull));
@@ -92,7 +102,7 @@ __global__ void dispatch_empty_kernel(int E, int R, int32_t* expert_counts, int3
 template <int K_MAX>
 __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     const uint4* __restrict__ x, const int32_t* __restrict__ topk_idx,
-    const int32_t* __restrict__ chunk_hist, int32_t* __restrict__ totals,
+    const int32_t* __restrict__ chunk_hist, int32_t* __restrict__ totals2,
     const int32_t* __restrict__ seg_order, const int32_t* __restrict__ dest_rank, int T, int k,
     int E, int R, int row_vec, int32_t* __restrict__ slot_to_row,
     int32_t* __restrict__ row_to_slot, uint4* __restrict__ x_packed,
@@ -101,8 +111,11 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
   __shared__ int32_t scan[MOE_MAX_EXPERTS + 1];
   __shared__ int32_t offs[MOE_MAX_EXPERTS];   // expert id -> first row of its segment
   __shared__ int32_t rcnt[MOE_MAX_RANKS + 1];
-  __shared__ int last_block;
   const int tid = threadIdx.x, lane = tid & 63;
+  int32_t* ctr = totals2 + 2 * MOE_MAX_EXPERTS;
+  const int call = ctr[1] - 1;   // the number the count kernel of this call saw
+  const int32_t* totals = totals2 + (call & 1) * MOE_MAX_EXPERTS;
+  if (blockIdx.x == 0 && tid == 0) ctr[0] = call + 1;
   // ---- expert offsets: inclusive scan of the totals taken in segment order
   int ex = 0, mine = 0;
   if (tid < E) {
@@ -122,12 +135,6 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     __syncthreads();
   }
   if (tid < E) offs[ex] = scan[tid];
-  // this block has read the totals (before the scan's first barrier): take a ticket; the
-  // last block of the grid resets totals and ticket counter (totals[MOE_MAX_EXPERTS])
-  if (tid == 0) {
-    __threadfence();
-    last_block = atomicAdd(&totals[MOE_MAX_EXPERTS], 1) == (int)gridDim.x - 1;
-  }
   if (blockIdx.x == 0) {  // the integer outputs of the call
     if (tid < E) {
       expert_offsets[ex] = scan[tid];
@@ -146,10 +153,6 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     }
   }
   __syncthreads();
-  if (last_block) {   // every block of the grid has read the totals
-    if (tid < MOE_MAX_EXPERTS) totals[tid] = 0;
-    if (tid == 0) totals[MOE_MAX_EXPERTS] = 0;
-  }
 
   const int t = (int)((blockIdx.x * (size_t)blockDim.x + tid) >> 6);
   if (t >= T) return;
@@ -212,7 +215,7 @@ int launch_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int T, v
   if (n_chunks > c->n_chunks_max) return MOE_EINVAL;
   int ebits = 0;
   while ((1 << ebits) < E) ++ebits;
-  int32_t* totals = c->d_totals;   // [MOE_MAX_EXPERTS] totals, then the ticket counter
+  int32_t* totals = c->d_totals;   // [2][MOE_MAX_EXPERTS] totals, then the two call counters
   hipLaunchKernelGGL(dispatch_count_kernel, dim3(n_chunks), dim3(COUNT_THREADS), 0, s, topk_idx, S,
                      E, ebits, c->d_chunk_hist, totals, slot_to_row);
   const int elem = c->cfg.dtype == MOE_BF16 ? 2 : 4;

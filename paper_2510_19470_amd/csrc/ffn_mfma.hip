@@ -85,15 +85,15 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
   if (blockIdx.x == 0 && tid == 0) {
     sched->n_mtiles = total_m;
     // Down GEMM: when the last round of tiles fills at most half of the compute units, its
-    // tiles are cut along the contraction into `split` parts (2, 4 or 8; every part a whole
+    // tiles are cut along the contraction into `split` parts (2 .. 8; every part a whole
     // number >= 4 of k-step pairs, the first parts one pair longer when the pairs do not
     // divide evenly; all parts together still one round), summed afterwards.
     const int total = total_m * nt_down;
     const int tail = total % n_cu;
     const int pairs = kt_down / 2;
     int split = 1;
-    while (tail > 0 && split < 8 && tail * (split * 2) <= n_cu && pairs / (split * 2) >= 4)
-      split *= 2;
+    while (tail > 0 && split < 8 && tail * (split + 1) <= n_cu && pairs / (split + 1) >= 4)
+      ++split;
     sched->down_split = split;
     sched->down_split_tiles = split > 1 ? tail : 0;
     sched->down_full = split > 1 ? total - tail : total;

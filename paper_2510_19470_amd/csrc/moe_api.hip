@@ -139,7 +139,7 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
   ok = ok && dev_alloc(&c->d_dest_rank, E) == hipSuccess;
   ok = ok && dev_alloc(&c->d_seg_order, E) == hipSuccess;
   ok = ok && dev_alloc(&c->d_chunk_hist, (size_t)c->n_chunks_max * E) == hipSuccess;
-  ok = ok && dev_alloc(&c->d_totals, 2 * MOE_MAX_EXPERTS) == hipSuccess;
+  ok = ok && dev_alloc(&c->d_totals, 2 * MOE_MAX_EXPERTS + 2) == hipSuccess;
   ok = ok && dev_alloc(&c->d_logits, (size_t)cfg->T_max * E) == hipSuccess;
   ok = ok && dev_alloc(&c->d_wtab, MOE_WTAB_ROWS * MOE_MAX_EXPERTS) == hipSuccess;
   for (int i = 0; i < 2 && ok; ++i) {
@@ -153,7 +153,7 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
     ok = ok && dev_alloc(&c->d_split_ws, (size_t)c->n_cu * MFMA_BM * 256) == hipSuccess;
   }
   ok = ok && hipMalloc(&c->d_H, std::max<size_t>((size_t)S * cfg->f * c->elem, 16)) == hipSuccess;
-  ok = ok && hipMemset(c->d_totals, 0, sizeof(int32_t) * 2 * MOE_MAX_EXPERTS) == hipSuccess;
+  ok = ok && hipMemset(c->d_totals, 0, sizeof(int32_t) * (2 * MOE_MAX_EXPERTS + 2)) == hipSuccess;
   ok = ok && hipMemset(c->d_wtab, 0, sizeof(void*) * MOE_WTAB_ROWS * MOE_MAX_EXPERTS) == hipSuccess;
   if (!ok) {
     (void)hipGetLastError();

@@ -50,7 +50,8 @@ struct moe_ctx {
   // dispatch workspace
   int32_t n_chunks_max;   // slot chunks of DISPATCH_CHUNK
   int32_t* d_chunk_hist;  // [n_chunks_max][E] per-chunk expert histograms
-  int32_t* d_totals;      // [MOE_MAX_EXPERTS] per-expert totals + [1] ticket counter (zero between calls)
+  int32_t* d_totals;      // [2][MOE_MAX_EXPERTS] per-expert totals, double-buffered per call, then
+                          // [2] the call number as the device keeps it
   float* d_logits;        // [T_max][E] when the caller does not want the logits
   // expert weight pointer tables: device copy [6][MOE_MAX_EXPERTS] (W1, W3, W2, dW1, dW3,
   // dW2), refreshed only when the host tables change
