@@ -264,6 +264,22 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
     call_ms = {n: float(np.mean([marks[s][i].elapsed_time(marks[s][i + 1])
                                  for s in range(args.steps)])) for i, n in enumerate(names)}
+    step_ms = [marks[s][0].elapsed_time(marks[s][len(names)]) for s in range(args.steps)]
+
+    # dispatch and combine once more, back to back on the same buffers ("warm": what fits the
+    # 256 MB Infinity Cache stays there; inside a step the expert GEMMs run in between and the
+    # two calls find their data in HBM, which is what the roofline fractions use)
+    def warm(fn, reps=10):
+        fn()
+        a, b_ = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b_.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b_) / reps
+    warm_dispatch_ms = warm(lambda: moe.moe_dispatch(lay.ctx, x, topk_idx, out=disp))
+    warm_combine_ms = warm(lambda: moe.moe_combine(lay.ctx, y_packed, disp.slot_to_row, topk_w, out=out))
     n_loc = int(disp.rank_counts[cfg.local_rank].item())
     n_res = len(wl.resident_experts(cfg))
 
@@ -315,8 +331,15 @@ def main() -> int:
             "combine_gbs": gbs(bytes_combine, call_ms["combine"]),
             "combine_frac": gbs(bytes_combine, call_ms["combine"]) / PEAK_HBM_GBS,
             "bytes_dispatch": bytes_dispatch, "bytes_combine": bytes_combine, "peak_gbs": PEAK_HBM_GBS,
+            "dispatch_warm_gbs": gbs(bytes_dispatch, warm_dispatch_ms),
+            "combine_warm_gbs": gbs(bytes_combine, warm_combine_ms),
+            "note": "dispatch_gbs / combine_gbs: inside a step (data in HBM); *_warm_gbs: the same "
+                    "call repeated back to back (whatever fits the 256 MB Infinity Cache stays there)",
         },
         "call_ms": call_ms,
+        "breakdown_step_ms": {"median": float(np.median(step_ms)), "min": float(np.min(step_ms)),
+                              "max": float(np.max(step_ms)),
+                              "note": "steps of the breakdown pass (an event after every call)"},
         "input_generation_s": t_gen,
     }
     if mfma and not args.no_sr:
