@@ -75,3 +75,12 @@ def test_pipeline_create_rejects_invalid_arguments_on_the_host():
         assert not h
     assert lib.moe_pipeline_create(None, ctypes.byref(cfg), 2, 2) == -1
     assert lib.moe_pipeline_destroy(None) == 0
+
+
+def test_create_rejects_more_slots_than_supported_on_the_host():
+    import ctypes
+    lib = moe.load_library()
+    cfg = moe.MoEConfigC((1 << 20) + 1, 64, 8, 4, 64, 2, 0, moe.MOE_BF16, 1)   # T_max*k > 2^22
+    h = ctypes.c_void_p()
+    assert lib.moe_create(ctypes.byref(h), ctypes.byref(cfg)) == -2          # MOE_EUNSUPPORTED
+    assert not h
