@@ -116,3 +116,50 @@ def test_full_size_expert_matrix_sampled_properties():
     assert np.array_equal(o[idx_h], want)
     assert np.array_equal(o[~kept], s_bits[~kept])
     moe.moe_destroy(ctx)
+
+
+def test_migrated_expert_arrives_compressed_and_is_computed():
+    """The paper's parameter-efficient migration end to end on one GPU: the weights of the
+    migrated expert reach this rank as shared expert + value-index list (SREncode at CR = 50
+    where they live, SRDecode here), the decoded matrices go into the pointer tables, and the
+    grouped FFN computes that expert's tokens with them.  Decoded weights bit-exact against the
+    oracle's decode, FFN output against the oracle's FFN on the oracle-decoded weights."""
+    from oracle import moe_oracle as orc
+    from gpu_common import DEV, TOL, nerr, vals, layer_from_inputs, to_host_f32, say
+    cfg = wl.scaled(wl.CONFIGS["small"], T=1024, d=512, f=512, E=8, R=4, migrated=(5,))
+    say(f"[sr+ffn] T={cfg.T} d={cfg.d} f={cfg.f} E={cfg.E} migrated={cfg.migrated}")
+    inp = wl.make_inputs(cfg, experts="resident")
+    e = 5
+    # the migrated expert's three matrices = a shared expert + a concentrated residual
+    dec_o, dec_g = {}, {}
+    lay = layer_from_inputs(inp)
+    for m, (name, shape) in enumerate((("W1", (cfg.f, cfg.d)), ("W3", (cfg.f, cfg.d)), ("W2", (cfg.d, cfg.f)))):
+        shared, experts = wl.make_sr_inputs(shape, 700 + m, "bf16", n_experts=1)
+        k = sr.keep_count(shape[0] * shape[1], 50)
+        dS, dW = to_device(shared, "bf16"), to_device(experts[0], "bf16")
+        v, i = moe.moe_sr_encode(lay.ctx, dW, dS, k)            # at the expert's home
+        dec_g[name] = moe.moe_sr_decode(lay.ctx, dS, v, i)      # on this rank
+        ov, oi = sr.sr_encode(experts[0], shared, k, "bf16")
+        dec_o[name] = sr.sr_decode(shared, ov, oi, "bf16")
+        assert np.array_equal(to_host_bits(dec_g[name]), dec_o[name].view(np.uint16))
+    lay.W1[e], lay.W3[e], lay.W2[e] = dec_g["W1"], dec_g["W3"], dec_g["W2"]
+    idx = wl.random_routing(cfg.T, cfg.E, cfg.k, seed=11)
+    cnt, off, _, _, s2r, r2s = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
+    xp_st = orc.pack_rows(inp.x, r2s, cfg.k)
+    y, _, _ = moe.moe_expert_ffn(lay.ctx, to_device(xp_st, "bf16"), torch.from_numpy(cnt).to(DEV),
+                                 torch.from_numpy(off).to(DEV), lay.W1, lay.W3, lay.W2)
+    torch.cuda.synchronize()
+    f64 = lambda ws: [None if w is None else vals(w, "bf16") for w in ws]
+    W1, W3, W2 = f64(inp.W1), f64(inp.W3), f64(inp.W2)
+    W1[e], W3[e], W2[e] = (vals(dec_o[n].view(np.uint16).reshape(s_), "bf16")
+                           for n, s_ in (("W1", (cfg.f, cfg.d)), ("W3", (cfg.f, cfg.d)), ("W2", (cfg.d, cfg.f))))
+    yo, _, _ = orc.expert_ffn(vals(xp_st, "bf16"), cnt, off, W1, W3, W2)
+    rows = slice(int(off[e]), int(off[e] + cnt[e]))
+    assert cnt[e] > 0
+    assert nerr(to_host_f32(y)[rows], yo[rows]) <= TOL["bf16"]
+    res = [q for q in range(cfg.E) if inp.W1[q] is not None]
+    done = np.zeros(cfg.S, bool)
+    for q in res:
+        done[off[q]:off[q] + cnt[q]] = True
+    assert nerr(to_host_f32(y)[done], yo[done]) <= TOL["bf16"]
+    lay.close()
