@@ -55,8 +55,7 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
     const void* const* __restrict__ present, int E, int S, int max_mtiles, int nt_up, int nt_down,
     int n_cu, int kt_down, TileSched* __restrict__ sched, const void* const* __restrict__ up_b0,
     const void* const* __restrict__ up_b1, const void* const* __restrict__ down_b0,
-    TileDesc* __restrict__ order_up, TileDesc* __restrict__ order_down,
-    int32_t* __restrict__ koff) {
+    TileDesc* __restrict__ order_up, TileDesc* __restrict__ order_down) {
   __shared__ int32_t start[MOE_MAX_EXPERTS + 1];
   __shared__ int bad;
   const int tid = threadIdx.x;
@@ -97,25 +96,6 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
     sched->down_split = split;
     sched->down_split_tiles = split > 1 ? tail : 0;
     sched->down_full = split > 1 ? total - tail : total;
-  }
-  // Backward only: column offset of every expert in the transposed activation buffers,
-  // each expert's rows padded to a multiple of 128 (koff[e+1]-koff[e] = padded count).
-  if (koff != nullptr && blockIdx.x == 0) {
-    __shared__ int32_t kp[MOE_MAX_EXPERTS + 1];
-    int pad = 0;
-    if (!bad && tid < E && present[tid] != nullptr) pad = (counts[tid] + 127) & ~127;
-    kp[tid + 1] = pad;
-    if (tid == 0) kp[0] = 0;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-      int v = 0;
-      if (tid >= off) v = kp[tid + 1 - off];
-      __syncthreads();
-      if (tid >= off) kp[tid + 1] += v;
-      __syncthreads();
-    }
-    if (tid <= E) koff[tid] = kp[tid];
-    if (tid == 0 && E == 256) koff[256] = kp[256];
   }
   const int gsz = gridDim.x * blockDim.x;
   const int gid = blockIdx.x * blockDim.x + tid;
@@ -179,32 +159,21 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
   return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
 }
 
-enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_WGRAD = 3, MODE_UP1 = 4, MODE_DH1 = 5 };
+enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_UP1 = 4, MODE_DH1 = 5 };
 
 struct GemmArgs {
   const uint16_t* A;    // token-role operand: [rows, lda]
-  int lda;              // elements per row of A (and of BT in MODE_WGRAD)
+  int lda;              // elements per row of A
   const TileSched* sched;
   const TileDesc* order;
   int n_tiles_n;
-  int K;                   // contraction length (not MODE_WGRAD)
+  int K;                   // contraction length
   int N;                   // elements per output row
   uint16_t* C;             // UP: H; DOWN: Y / dX; DH: [dG|dU] with row pitch 2N
   uint16_t* C2;            // DH: H
   float* split_ws;         // DOWN: fp32 partial tiles of the K-split tail
   uint16_t* Gs;            // UP: optional save (out); DH: saved G (in)
   uint16_t* Us;
-  // MODE_WGRAD: n_jobs (<= 3) products dW[e][Mo,No] = AT_e * BT_e^T over the expert's padded
-  // row range in one launch (blocks [j * tiles, (j+1) * tiles) belong to job j)
-  int n_jobs;
-  struct WJob {
-    const uint16_t* AT;      // [rows >= a_row0 + Mo][lda]
-    const uint16_t* BT;      // [No][lda]
-    const void* const* dWt;  // table of fp32 outputs
-    int Mo, No, a_row0;
-  } wj[3];
-  const int32_t* koff;
-  const void* const* present;
 };
 
 // One unit of work of a block: a whole tile, or one K-split part of a tile (all fields are
@@ -318,7 +287,6 @@ __device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][
 // MODE_DOWN : C = A B^T                               (down projection; also dX = [dG|dU][W1^T|W3^T]^T)
 // MODE_DH   : dH = A B^T, then dG = dH*u*silu'(g), dU = dH*silu(g), H = silu(g)*u
 // MODE_DH1  : dH = A B^T, then dG = dH where g > 0 (else 0), H = max(g, 0)   (two-matrix expert)
-// MODE_WGRAD: fp32 dW = AT BT^T, both operands transposed activations (contraction = rows)
 //
 // Tiled modes run persistent blocks (one per compute unit) over a static share of the tile
 // order, and the copy stream does not stop at a tile boundary: during the last two k-steps
@@ -332,8 +300,6 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = __builtin_amdgcn_readfirstlane(wave >> 2), wn = wave & 3;
-  float* dW = nullptr;
-  int mblk = 0, w_No = 0;
   Unit cur;
   // global -> LDS assignment: one copy instruction fills 8 rows (lane>>3) x 8 chunk slots
   // (lane&7); slot c of row r must hold global chunk c ^ swz(r).  Token rows: copy i of a
@@ -342,7 +308,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   // otherwise bbase1 is bbase0 + 128 rows).  Per-lane byte offsets from the unit's bases:
   uint32_t a_off[4], b_off[4];
   const int a_pitch = p.lda * 2;                                   // bytes per token-role row
-  const int b_pitch = (MODE == MODE_WGRAD ? p.lda : p.K) * 2;      // ... per weight-role row
+  const int b_pitch = p.K * 2;                                     // ... per weight-role row
   auto token_off = [&](int rows, int i) -> uint32_t {
     const int ra = (16 * wm + 4 * i + wn) * 8 + (lane >> 3);
     return (uint32_t)min(ra, rows - 1) * a_pitch + (((lane & 7) ^ swz(ra)) << 4);
@@ -352,34 +318,8 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
     const int rb = (8 * i + wave) * 8 + (lane >> 3);
     b_off[i] = (uint32_t)(rb & 127) * b_pitch + (((lane & 7) ^ swz(rb)) << 4);
   }
-  if (MODE == MODE_WGRAD) {
-    // all jobs have the same number of tiles per expert: (d/256) * (f/256)
-    const int tiles = (p.wj[0].Mo >> 8) * (p.wj[0].No >> 8);
-    const int per_job = (int)gridDim.x / p.n_jobs;
-    const int job = blockIdx.x / per_job;
-    const int jb = blockIdx.x % per_job;
-    const GemmArgs::WJob& J = p.wj[job];
-    const int NoT = J.No >> 8;
-    const int e = jb / tiles;
-    const int rem = jb % tiles;
-    mblk = rem / NoT;
-    w_No = J.No;
-    dW = (float*)J.dWt[e];
-    if (dW == nullptr || p.present[e] == nullptr) return;
-    const int k0 = p.koff[e];
-    cur.valid = 1;
-    cur.KT = (p.koff[e + 1] - k0) / BK;
-    cur.row0 = 0;
-    cur.rows = BM;
-    cur.nblk = rem % NoT;
-    cur.ws_unit = -1;
-    cur.abase = (const char*)(J.AT + (size_t)(J.a_row0 + mblk * 256) * p.lda + k0);
-    cur.bbase0 = (const char*)(J.BT + (size_t)(cur.nblk * 256) * p.lda + k0);
-    cur.bbase1 = cur.bbase0 + (size_t)128 * b_pitch;
-  } else {
-    cur = fetch_unit<MODE>(p, 0);
-    if (!cur.valid) return;
-  }
+  cur = fetch_unit<MODE>(p, 0);
+  if (!cur.valid) return;
 #pragma unroll
   for (int i = 0; i < 4; ++i) a_off[i] = token_off(cur.rows, i);
 
@@ -408,23 +348,6 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
           for (int q = 0; q < 4; ++q)
             ws[((j * 4 + i) * 4 + q) * NT] = make_float4(acc[j][i][q * 4], acc[j][i][q * 4 + 1],
                                                          acc[j][i][q * 4 + 2], acc[j][i][q * 4 + 3]);
-      return;
-    }
-    if (MODE == MODE_WGRAD) {   // fp32 weight gradient: 16 bytes per lane as the accumulator has them
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int m_local = wm * 128 + i * 32 + fr_row;
-        float* orow = dW + (size_t)(mblk * 256 + m_local) * w_No;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int col0 = u.nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
-#pragma unroll
-          for (int g = 0; g < 4; ++g)
-            *reinterpret_cast<float4*>(orow + col0 + 8 * g) =
-                make_float4(acc[j][i][g * 4], acc[j][i][g * 4 + 1], acc[j][i][g * 4 + 2],
-                            acc[j][i][g * 4 + 3]);
-        }
-      }
       return;
     }
     // bf16 outputs: every lane takes part in the half-wavefront swaps, only the stores are
@@ -573,9 +496,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
 
   bf16x8 wb[2][4];
   for (int idx = 0;; ++idx) {
-    Unit nxt;
-    nxt.valid = 0;
-    if (MODE != MODE_WGRAD) nxt = fetch_unit<MODE>(p, idx + 1);
+    const Unit nxt = fetch_unit<MODE>(p, idx + 1);
     zero_acc();
     const int KT = cur.KT;
     // steady part: steps 0 .. KT-3; what was read one cluster ago is refilled with the data
@@ -667,12 +588,12 @@ __global__ __launch_bounds__(NT) void ffn_split_reduce_kernel(const GemmArgs p) 
   }
 }
 
-// ---- transposes feeding the backward GEMMs ------------------------------------------
-// All GEMMs here want both operands contiguous along the contraction dimension.  The
-// backward contracts over the other index of the weights (dH = dY W2, dX = dG W1 + dU W3)
-// and over the token rows (dW = P^T Q), so the weights and the activations are transposed
-// once per call, 64 x 64 elements per block through LDS, 16 bytes per lane on both the
-// global reads and the global writes.  LDS row pitch 66 elements: the eight 2-byte reads
+// ---- transposes feeding the backward's data-gradient GEMMs ---------------------------
+// The GEMMs of this file want both operands contiguous along the contraction dimension.  The
+// data gradients contract over the other index of the weights (dH = dY W2, dX = dG W1 +
+// dU W3), so the weights are transposed once per call, 64 x 64 elements per block through
+// LDS, 16 bytes per lane on both the global reads and the global writes.  (The weight
+// gradients, which contract over the token rows, need no transposed copies: wgrad_tr.hip.)  LDS row pitch 66 elements: the eight 2-byte reads
 // that gather one output chunk fall on distinct banks across the wavefront.
 constexpr int TP = 66;
 
@@ -720,31 +641,6 @@ __global__ __launch_bounds__(256) void transpose_weights_kernel(const void* cons
   tile_out_t(tile, dst + (size_t)c0 * dst_pitch + col_off + r0, dst_pitch);
 }
 
-// dst[c][koff[e] + r] = src[offsets[e] + r][c] for r < counts[e], 0 for the padding rows.
-__global__ __launch_bounds__(256) void transpose_acts_kernel(
-    const uint16_t* __restrict__ src, int src_pitch, int C, const int32_t* __restrict__ counts,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ koff, int E,
-    uint16_t* __restrict__ dst, int dst_pitch) {
-  __shared__ uint16_t tile[64][TP];
-  __shared__ int32_t s_koff[MOE_MAX_EXPERTS + 1];
-  for (int i = threadIdx.x; i <= E; i += 256) s_koff[i] = koff[i];
-  __syncthreads();
-  const int k0 = blockIdx.x * 64;  // 64 padded rows; never straddles experts (pads are x128)
-  if (k0 >= s_koff[E]) return;
-  int lo = 0, hi = E;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (s_koff[mid] <= k0) lo = mid; else hi = mid;
-  }
-  const int e = lo;
-  const int rel = k0 - s_koff[e];
-  const int n = counts[e], row0 = offsets[e];
-  const int c0 = blockIdx.y * 64;
-  tile_in(tile, src + (size_t)(row0 + rel) * src_pitch + c0, src_pitch, n - rel);
-  __syncthreads();
-  tile_out_t(tile, dst + (size_t)c0 * dst_pitch + k0, dst_pitch);
-}
-
 }  // namespace
 
 // two-matrix expert: the first GEMM has 256-column blocks of one matrix
@@ -766,11 +662,11 @@ size_t ffn_mfma_order_entries(const moe_ctx* c) {
 
 static int run_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets, int nt_a, int nt_b,
                      int kt_b, const void* const* up_b0, const void* const* up_b1,
-                     const void* const* down_b0, int32_t* koff, hipStream_t s) {
+                     const void* const* down_b0, hipStream_t s) {
   hipLaunchKernelGGL(mfma_sched_kernel, dim3(32), dim3(256), 0, s, counts, offsets,
                      c->d_wtab + 0 * MOE_MAX_EXPERTS, c->cfg.E, c->S_max, c->max_mtiles[1], nt_a,
                      nt_b, c->n_cu, kt_b, c->d_sched[1], up_b0, up_b1, down_b0, c->d_order_up,
-                     c->d_order_down, koff);
+                     c->d_order_down);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 
@@ -808,8 +704,7 @@ int launch_ffn_mfma(moe_ctx* c, bool gated, const int32_t* counts, const int32_t
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
   const int max_mt = c->max_mtiles[1];
   prof_mark(c, 0, s);
-  int st = run_sched(c, counts, offsets, nt_up, nt_down, f / BK, W1, gated ? W3 : nullptr, W2,
-                     nullptr, s);
+  int st = run_sched(c, counts, offsets, nt_up, nt_down, f / BK, W1, gated ? W3 : nullptr, W2, s);
   if (st != MOE_OK) return st;
   prof_mark(c, 1, s);
   GemmArgs up = tiled_args(c, x_packed, d, c->d_order_up, nt_up, d, f, c->d_H);
@@ -830,42 +725,28 @@ bool ffn_bwd_mfma_supported(const moe_ctx* c) {
   return ffn_mfma_supported(c) && c->cfg.f % 256 == 0;
 }
 
-// Elements per row of the transposed activation buffers: every expert padded to x128.
-int ffn_bwd_ktot(const moe_ctx* c) { return ((c->S_max + 127 * c->cfg.E + 127) / 128) * 128; }
-
 // dy, xp: [S,d]; G, U: [S,f] (forward saves); dxp out.  Workspace (context): d_H [S,f],
-// d_dGU [S,2f], d_actT: dY^T [d,Kt] | X^T [d,Kt] | H^T [f,Kt] | [dG|dU]^T [2f,Kt];
-// table rows 6 (W2^T) and 7 ([W1^T|W3^T]) point into d_wT.  Two-matrix expert (!gated):
+// d_dGU [S,2f]; table rows 6 (W2^T) and 7 ([W1^T|W3^T]) point into d_wT.  Two-matrix expert (!gated):
 // no U, no W3: d_dGU holds dG [S,f], row 7 points to W1^T [d,f], two weight gradients.
 int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, const void* G,
                         const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
                         hipStream_t s) {
   const int d = c->cfg.d, f = c->cfg.f, E = c->cfg.E;
-  const int Kt = ffn_bwd_ktot(c);
   const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
   const void* const* W3 = c->d_wtab + 1 * MOE_MAX_EXPERTS;
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
-  const void* const* dW1 = c->d_wtab + 3 * MOE_MAX_EXPERTS;
-  const void* const* dW3 = c->d_wtab + 4 * MOE_MAX_EXPERTS;
-  const void* const* dW2 = c->d_wtab + 5 * MOE_MAX_EXPERTS;
   const void* const* W2T = c->d_wtab + 6 * MOE_MAX_EXPERTS;
   const void* const* W13T = c->d_wtab + 7 * MOE_MAX_EXPERTS;
   const int nt_f = f / 256, nt_d = d / 256;
   const int gw = gated ? 2 * f : f;   // elements per row of [dG|dU] and of [W1^T|W3^T]
-  int st = run_sched(c, counts, offsets, nt_f, nt_d, gw / BK, W2T, nullptr, W13T, c->d_koff, s);
+  int st = run_sched(c, counts, offsets, nt_f, nt_d, gw / BK, W2T, nullptr, W13T, s);
   if (st != MOE_OK) return st;
-  // The transposes are HBM-bound and the two data-gradient GEMMs leave compute units idle
-  // (few tiles), so everything the first GEMM does not wait for runs beside the GEMMs on the
-  // context's second stream x:
-  //   s: W2^T, dH GEMM ............., dX GEMM ........., weight gradients
-  //   x: [W1^T|W3^T], dY^T, X^T ....| H^T, [dG|dU]^T ..|
+  // The transposes are HBM-bound; the one the first GEMM does not wait for runs beside it on
+  // the context's second stream x:
+  //   s: W2^T, dH GEMM ....., dX GEMM, weight gradients
+  //   x: [W1^T|W3^T] .......|
   hipStream_t x = c->aux_stream;
-  hipEvent_t ev_fork = c->aux_ev[0], ev_w13 = c->aux_ev[1], ev_dh = c->aux_ev[2], ev_tr = c->aux_ev[3];
-  uint16_t* dYT = (uint16_t*)c->d_actT;
-  uint16_t* XT = dYT + (size_t)d * Kt;
-  uint16_t* HT = XT + (size_t)d * Kt;
-  uint16_t* dGUT = HT + (size_t)f * Kt;
-  const int kblocks = Kt / 64;
+  hipEvent_t ev_fork = c->aux_ev[0], ev_w13 = c->aux_ev[1];
   bool ok = hipEventRecord(ev_fork, s) == hipSuccess && hipStreamWaitEvent(x, ev_fork, 0) == hipSuccess;
   if (!ok) return MOE_EHIP;
   // weights: W1, W3 [f,d] -> [W1^T | W3^T] [d,2f] (second stream); W2 [d,f] -> W2^T [f,d]
@@ -875,11 +756,6 @@ int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, 
     hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, x, W3, W13T,
                        f, d, gw, f);
   ok = ok && hipEventRecord(ev_w13, x) == hipSuccess;
-  // activations transposed per expert segment (zero padded to x128 rows)
-  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, d / 64), dim3(256), 0, x,
-                     (const uint16_t*)dy, d, d, counts, offsets, c->d_koff, E, dYT, Kt);
-  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, d / 64), dim3(256), 0, x,
-                     (const uint16_t*)xp, d, d, counts, offsets, c->d_koff, E, XT, Kt);
   hipLaunchKernelGGL(transpose_weights_kernel, dim3(f / 64, d / 64, E), dim3(256), 0, s, W2, W2T, d,
                      f, d, 0);
   // dH = dY W2 with the activation's derivative in the epilogue -> [dG|dU], H
@@ -891,29 +767,13 @@ int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, 
     hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
   else
     hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH1>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
-  ok = ok && hipEventRecord(ev_dh, s) == hipSuccess && hipStreamWaitEvent(x, ev_dh, 0) == hipSuccess;
-  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, f / 64), dim3(256), 0, x,
-                     (const uint16_t*)c->d_H, f, f, counts, offsets, c->d_koff, E, HT, Kt);
-  hipLaunchKernelGGL(transpose_acts_kernel, dim3(kblocks, gw / 64), dim3(256), 0, x,
-                     (const uint16_t*)c->d_dGU, gw, gw, counts, offsets, c->d_koff, E, dGUT, Kt);
-  ok = ok && hipEventRecord(ev_tr, x) == hipSuccess;
   // dX = [dG|dU] [W1^T|W3^T]^T  (one GEMM with contraction length 2f; f without U)
   ok = ok && hipStreamWaitEvent(s, ev_w13, 0) == hipSuccess;
   GemmArgs dx = tiled_args(c, c->d_dGU, gw, c->d_order_down, nt_d, gw, d, dxp);
   launch_down(c, dx, nt_d, s);
-  // join: the weight gradients read all four transposed activation arrays
-  ok = ok && hipStreamWaitEvent(s, ev_tr, 0) == hipSuccess;
   if (!ok) return MOE_EHIP;
-  // weight gradients, fp32
-  GemmArgs w{};
-  w.lda = Kt;
-  w.koff = c->d_koff;
-  w.present = W1;
-  w.n_jobs = gated ? 3 : 2;
-  w.wj[0] = {dYT, HT, dW2, d, f, 0};     // dW2 [d,f] = dY^T H
-  w.wj[1] = {dGUT, XT, dW1, f, d, 0};    // dW1 [f,d] = dG^T X
-  w.wj[2] = {dGUT, XT, dW3, f, d, f};    // dW3 [f,d] = dU^T X
-  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_WGRAD>), dim3(w.n_jobs * E * nt_d * nt_f), dim3(NT), 0, s,
-                     w);
+  // weight gradients straight from dY, X, H and [dG|dU] (transpose reads from LDS)
+  st = launch_wgrad_tr(c, gated, dy, xp, c->d_H, c->d_dGU, counts, offsets, s);
+  if (st != MOE_OK) return st;
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }

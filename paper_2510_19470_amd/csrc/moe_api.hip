@@ -36,9 +36,8 @@ void free_all(moe_ctx* c) {
   (void)hipFree(c->d_dG);
   (void)hipFree(c->d_dU);
   (void)hipFree(c->d_dGU);
-  (void)hipFree(c->d_actT);
-  (void)hipFree(c->d_koff);
   (void)hipFree(c->d_wT);
+  (void)hipFree(c->d_zero);
   if (c->aux_stream != nullptr) (void)hipStreamDestroy(c->aux_stream);
   for (hipEvent_t e : c->aux_ev)
     if (e != nullptr) (void)hipEventDestroy(e);
@@ -438,24 +437,22 @@ int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, 
     size_t n_present = 0;
     for (int e = 0; e < E; ++e) n_present += W1[e] != nullptr;
     if (c->d_dGU == nullptr) {
-      const size_t kt = (size_t)ffn_bwd_ktot(c);
       bool ok = hipMalloc(&c->d_dGU, 2 * sf_bytes) == hipSuccess;
-      ok = ok && hipMalloc(&c->d_actT, (2 * (size_t)d + 3 * (size_t)f) * kt * 2) == hipSuccess;
-      ok = ok && hipMalloc(reinterpret_cast<void**>(&c->d_koff), sizeof(int32_t) * (E + 1)) ==
-                     hipSuccess;
+      // the fill runs on the null stream: wait for it, the caller's stream may not
+      ok = ok && hipMalloc(&c->d_zero, 512) == hipSuccess &&
+           hipMemset(c->d_zero, 0, 512) == hipSuccess && hipStreamSynchronize(nullptr) == hipSuccess;
       if (!ok) {
         (void)hipGetLastError();
         (void)hipFree(c->d_dGU);
-        (void)hipFree(c->d_actT);
-        (void)hipFree(c->d_koff);
-        c->d_dGU = c->d_actT = nullptr;
-        c->d_koff = nullptr;
+        (void)hipFree(c->d_zero);
+        c->d_zero = nullptr;
+        c->d_dGU = nullptr;
         return MOE_ENOMEM;
       }
     }
     if (c->aux_stream == nullptr) {
       bool ok = hipStreamCreateWithFlags(&c->aux_stream, hipStreamNonBlocking) == hipSuccess;
-      for (int i = 0; i < 4 && ok; ++i)
+      for (int i = 0; i < 2 && ok; ++i)
         ok = hipEventCreateWithFlags(&c->aux_ev[i], hipEventDisableTiming) == hipSuccess;
       if (!ok) {
         (void)hipGetLastError();

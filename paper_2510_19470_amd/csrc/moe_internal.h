@@ -73,14 +73,13 @@ struct moe_ctx {
   void* d_dG;             // [T_max*k][f]   (vector-ALU backward)
   void* d_dU;             // [T_max*k][f]
   void* d_dGU;            // [T_max*k][2f]  (MFMA backward: dG | dU)
-  void* d_actT;           // transposed activations of the MFMA backward
-  int32_t* d_koff;        // [E+1] padded row offsets of the experts in d_actT
+  void* d_zero;           // 512 bytes of zeros (rows past a segment's end in the weight gradients)
   void* d_wT;             // transposed weights of the MFMA backward
   size_t wT_experts;      // experts d_wT has room for
   // MFMA backward: the transposes run on a second stream (default priority) beside the
   // GEMMs; events fork it from / join it into the caller's stream
   hipStream_t aux_stream;
-  hipEvent_t aux_ev[4];   // fork, [W1^T|W3^T] ready, dH done, transposes done
+  hipEvent_t aux_ev[2];   // fork, [W1^T|W3^T] ready
   // gate backward: per-chunk partial sums of dWg, [T_max/128][E][d] (first call allocates)
   float* d_rbwd_ws;
   // shared/residual compression: selection state, histogram, per-chunk counts
@@ -133,10 +132,12 @@ bool ffn_mfma_supported_2mat(const moe_ctx* c);
 int launch_ffn_mfma(moe_ctx* c, bool gated, const int32_t* counts, const int32_t* offsets,
                     const void* x_packed, void* y_packed, void* G, void* U, hipStream_t s);
 bool ffn_bwd_mfma_supported(const moe_ctx* c);
-int ffn_bwd_ktot(const moe_ctx* c);
 int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, const void* G,
                         const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
                         hipStream_t s);
+int launch_wgrad_tr(moe_ctx* c, bool gated, const void* dy, const void* xp, const void* H,
+                    const void* dGU, const int32_t* counts, const int32_t* offsets,
+                    hipStream_t s);
 size_t route_bwd_workspace_floats(const moe_ctx* c);
 int launch_route_bwd(moe_ctx* c, const void* x, const void* Wg, const float* logits,
                      const int32_t* topk_idx, const float* topk_w, const float* dtopk_w, int T,
