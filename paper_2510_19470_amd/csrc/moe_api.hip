@@ -18,7 +18,7 @@ hipError_t dev_alloc(T** p, size_t n) {
 
 void free_all(moe_ctx* c) {
   (void)hipFree(c->d_dest_rank);
-  (void)hipFree(c->d_seg_order);
+  (void)hipFree(c->d_seg_pos);
   (void)hipFree(c->d_chunk_hist);
   (void)hipFree(c->d_totals);
   (void)hipFree(c->d_logits);
@@ -136,7 +136,7 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
   c->max_mtiles[1] = (int)(S / MFMA_BM) + E;
   bool ok = true;
   ok = ok && dev_alloc(&c->d_dest_rank, E) == hipSuccess;
-  ok = ok && dev_alloc(&c->d_seg_order, E) == hipSuccess;
+  ok = ok && dev_alloc(&c->d_seg_pos, E) == hipSuccess;
   ok = ok && dev_alloc(&c->d_chunk_hist, (size_t)c->n_chunks_max * E) == hipSuccess;
   ok = ok && dev_alloc(&c->d_totals, 2 * MOE_MAX_EXPERTS + 2) == hipSuccess;
   ok = ok && dev_alloc(&c->d_logits, (size_t)cfg->T_max * E) == hipSuccess;
@@ -287,9 +287,11 @@ int moe_set_placement(moe_ctx* c, const int32_t* expert_dest_rank) {
   std::stable_sort(order, order + E, [&](int a, int b) {
     return expert_dest_rank[a] < expert_dest_rank[b];
   });
+  int32_t pos[MOE_MAX_EXPERTS];   // expert id -> position in (dest_rank, id) order
+  for (int i = 0; i < E; ++i) pos[order[i]] = i;
   if (hipMemcpy(c->d_dest_rank, expert_dest_rank, sizeof(int32_t) * E, hipMemcpyHostToDevice) !=
           hipSuccess ||
-      hipMemcpy(c->d_seg_order, order, sizeof(int32_t) * E, hipMemcpyHostToDevice) != hipSuccess)
+      hipMemcpy(c->d_seg_pos, pos, sizeof(int32_t) * E, hipMemcpyHostToDevice) != hipSuccess)
     return MOE_EHIP;
   return MOE_OK;
 }

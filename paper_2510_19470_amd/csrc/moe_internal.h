@@ -46,7 +46,7 @@ struct moe_ctx {
   int ffn_path;           // MOE_FFN_AUTO / MOE_FFN_VALU
   // placement
   int32_t* d_dest_rank;   // [E]
-  int32_t* d_seg_order;   // [E] experts in (dest_rank, id) order
+  int32_t* d_seg_pos;     // [E] position of every expert in (dest_rank, id) order
   // dispatch workspace
   int32_t n_chunks_max;   // slot chunks of DISPATCH_CHUNK
   int32_t* d_chunk_hist;  // [n_chunks_max][E] per-chunk expert histograms
