@@ -4,14 +4,18 @@
 // a single rounding to the storage type at the end.
 #include "moe_internal.h"
 #include "numeric.h"
+#include <type_traits>
 
 namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename T, int K_MAX>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_packed,
                                                       const int32_t* __restrict__ slot_to_row,
                                                       const float* __restrict__ topk_w, int Tn,
-                                                      int k, int S, int d, T* __restrict__ out) {
+                                                      int k, int S, int d, T* __restrict__ out,
+                                                      int stream) {
   constexpr int N = Vec16<T>::N;
   const int lane = threadIdx.x & 63;
   const int t = (int)((blockIdx.x * (size_t)blockDim.x + threadIdx.x) >> 6);
@@ -28,23 +32,35 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pa
     rowp[j] = y_packed + (size_t)(ok[j] ? r : 0) * d;
     w[j] = j < k ? topk_w[(size_t)t * k + j] : 0.f;
   }
+  // stream != 0 (packed rows larger than the last-level cache): the rows are read once, with
+  // non-temporal loads (measured 94 -> 81 us on 403 MB of packed rows; no gain when they fit)
+  auto body = [&](auto NT) {
 #pragma unroll(K_MAX <= 4 ? 2 : 1)
-  for (int c = lane * N; c < d; c += 64 * N) {
-    uint4 raw[K_MAX];
+    for (int c = lane * N; c < d; c += 64 * N) {
+      uint4 raw[K_MAX];
 #pragma unroll
-    for (int j = 0; j < K_MAX; ++j) raw[j] = Vec16<T>::load_raw(rowp[j] + c);
-    float acc[N];
+      for (int j = 0; j < K_MAX; ++j) {
+        if constexpr (decltype(NT)::value) {
+          const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rowp[j] + c));
+          raw[j] = make_uint4(r.x, r.y, r.z, r.w);
+        } else {
+          raw[j] = Vec16<T>::load_raw(rowp[j] + c);
+        }
+      }
+      float acc[N];
 #pragma unroll
-    for (int i = 0; i < N; ++i) acc[i] = 0.f;
+      for (int i = 0; i < N; ++i) acc[i] = 0.f;
 #pragma unroll
-    for (int j = 0; j < K_MAX; ++j) {
-      float v[N];
-      Vec16<T>::unpack(raw[j], v);
+      for (int j = 0; j < K_MAX; ++j) {
+        float v[N];
+        Vec16<T>::unpack(raw[j], v);
 #pragma unroll
-      for (int i = 0; i < N; ++i) acc[i] = ok[j] ? fmaf(w[j], v[i], acc[i]) : acc[i];
+        for (int i = 0; i < N; ++i) acc[i] = ok[j] ? fmaf(w[j], v[i], acc[i]) : acc[i];
+      }
+      Vec16<T>::store(out + (size_t)t * d + c, acc);
     }
-    Vec16<T>::store(out + (size_t)t * d + c, acc);
-  }
+  };
+  if (stream) body(std::true_type{}); else body(std::false_type{});
 }
 
 template <typename T, int K_MAX>
@@ -151,12 +167,13 @@ int launch_combine(const moe_ctx* c, const void* y_packed, const int32_t* slot_t
   if (T == 0) return MOE_OK;
   const int k = c->cfg.k, d = c->cfg.d, S = T * k;
   const int grid = (T + 3) / 4;
+  const int stream = (size_t)S * d * c->elem > ((size_t)192 << 20);   // 256 MB last-level cache
   if (c->cfg.dtype == MOE_BF16)
     DISPATCH_K(combine_kernel, uint16_t, (const uint16_t*)y_packed, slot_to_row, w, T, k, S, d,
-               (uint16_t*)out);
+               (uint16_t*)out, stream);
   else
     DISPATCH_K(combine_kernel, float, (const float*)y_packed, slot_to_row, w, T, k, S, d,
-               (float*)out);
+               (float*)out, stream);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 

@@ -147,3 +147,30 @@ def test_combine_and_rowwise_backward(name, T):
     torch.cuda.synchronize()
     assert nerr(to_host_f32(dx), orc.dispatch_bwd(vals(y_st, cfg.dtype), s2r, cfg.T, cfg.k)) <= tol
     ctx.close()
+
+
+def test_combine_full_size_streaming():
+    """Combine at the full 'finegrained' size: the packed rows (403 MB) exceed the last-level
+    cache, which selects the kernel's streaming loads.  The oracle computes a sample of tokens."""
+    from gpu_common import DEV, TOL, moe, say, nerr, vals, to_device, to_host_f32
+    cfg = wl.CONFIGS["finegrained"]
+    say(f"[combine] full size config=finegrained T={cfg.T} d={cfg.d} k={cfg.k} S={cfg.S}")
+    rng = np.random.default_rng(cfg.seed + 1)
+    inp = wl.make_inputs(cfg, experts="none")
+    idx_np = wl.random_routing(cfg.T, cfg.E, cfg.k, cfg.seed, skew=0.3)
+    w_np = rng.random((cfg.T, cfg.k)).astype(np.float32)
+    w_np /= w_np.sum(1, keepdims=True)
+    _, _, _, _, s2r, _ = orc.dispatch_maps(idx_np, inp.dest_rank, cfg.R)
+    y_st = wl.store(rng.standard_normal((cfg.S, cfg.d), dtype=np.float32), cfg.dtype)
+    ctx = moe.moe_create(T_max=cfg.T, d=cfg.d, E=cfg.E, k=cfg.k, f=cfg.f, R=cfg.R)
+    out = moe.moe_combine(ctx, to_device(y_st, cfg.dtype), torch.from_numpy(s2r).to(DEV),
+                          torch.from_numpy(w_np).to(DEV))
+    torch.cuda.synchronize()
+    got = to_host_f32(out)
+    ts = np.unique(np.concatenate([np.arange(8), np.arange(cfg.T - 8, cfg.T),
+                                   rng.integers(0, cfg.T, 1000)]))
+    rows = s2r.reshape(cfg.T, cfg.k)[ts]                      # rows of the sampled tokens
+    uniq, inv = np.unique(rows, return_inverse=True)
+    want = orc.combine(vals(y_st[uniq], cfg.dtype), inv.reshape(-1).astype(np.int32), w_np[ts])
+    assert nerr(got[ts], want) <= TOL[cfg.dtype]
+    ctx.close()
