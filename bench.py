@@ -139,6 +139,10 @@ def main() -> int:
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--table3-sweep", action="store_true",
+                    help="instead of one workload: the paper's layer shapes (Table 3: K, B*L, H, M "
+                         "varied one at a time around K=2, B*L=8192, H=1024, M=4096; E=32, "
+                         "two-matrix expert, forward + backward), one JSON line with a row per shape")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -153,7 +157,52 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 3
-    cfg = wl.CONFIGS[args.config]
+    if args.table3_sweep:
+        return table3_sweep(args)
+    print(json.dumps(run(wl.CONFIGS[args.config], args)))
+    return 0
+
+
+def table3_sweep(args) -> int:
+    """The paper's own layer shapes (Sec. 5.1, Table 3) on one GPU's share of an 8-rank layout:
+    4 home experts + 4 fetched ones resident, two-matrix expert, forward + backward.  Every
+    parameter is varied alone around the base shape; B*L is the number of tokens."""
+    from dataclasses import replace
+    import moe_workloads as wl
+    base = wl.CONFIGS["paper_train"]
+    shapes = [dict()]
+    shapes += [dict(k=K) for K in (1, 4)]
+    shapes += [dict(T=T) for T in (1024, 4096, 16384)]
+    shapes += [dict(d=H) for H in (512, 768)]
+    shapes += [dict(f=M) for M in (768, 1024, 1536, 2048, 3072)]
+    args.no_sr = args.no_cpu_baseline = True
+    args.graph, args.chunks, args.copy_calibration = False, 0, False
+    rows = []
+    for i, sh in enumerate(shapes):
+        cfg = replace(base, name="table3", seed=base.seed + i, **sh)
+        r = run(cfg, args)
+        g, c = r["grouped_gemm"], r["call_ms"]
+        rows.append({"K": cfg.k, "tokens": cfg.T, "H": cfg.d, "M": cfg.f,
+                     "n_loc_rows": r["config"]["n_loc_rows"], "ms_per_step": r["ms_per_step"],
+                     "tokens_per_s": r["value"], "first_gemm_tflops": g["gate_up_tflops"],
+                     "second_gemm_tflops": g["down_tflops"], "call_ms": c})
+        print(f"table3 K={cfg.k} tokens={cfg.T} H={cfg.d} M={cfg.f}: "
+              f"{r['ms_per_step']:.3f} ms per step", file=sys.stderr, flush=True)
+    print(json.dumps({"metric": "MoE-layer step time over the paper's Table 3 shapes (1 GPU, forward "
+                                "+ backward, E=32, two-matrix expert)", "unit": "ms", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "dtype": "bf16",
+                      "data": "synthetic", "rows": rows}))
+    return 0
+
+
+def run(cfg, args) -> dict:
+    """One workload: warm-up, the timed steps, the breakdown pass and the extras; returns the
+    record that main() prints."""
+    import torch
+    import moe_workloads as wl
+    import paper_2510_19470_amd as moe
+    from paper_2510_19470_amd.layer import layer_from_inputs, to_device
+
     t_gen = time.perf_counter()
     inp = wl.make_inputs(cfg, experts="resident")
     t_gen = time.perf_counter() - t_gen
@@ -408,9 +457,8 @@ def main() -> int:
         flops_tok = 2.0 * (n_up + 1) * d * f * k * (3 if cfg.backward else 1) + 2.0 * d * E
         sample = args.cpu_sample_tokens or int(max(16, min(cfg.T, 8e12 / flops_tok)))
         rec["cpu_baseline"] = cpu_baseline(cfg, inp, sample)
-    print(json.dumps(rec))
     lay.close()
-    return 0
+    return rec
 
 
 if __name__ == "__main__":
