@@ -39,6 +39,9 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
 constexpr int BM = MFMA_BM;       // token rows per block tile
 constexpr int BNW = 256;          // weight rows per block tile
@@ -55,7 +58,8 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
     const void* const* __restrict__ present, int E, int S, int max_mtiles, int nt_up, int nt_down,
     int n_cu, int kt_down, TileSched* __restrict__ sched, const void* const* __restrict__ up_b0,
     const void* const* __restrict__ up_b1, const void* const* __restrict__ down_b0,
-    TileDesc* __restrict__ order_up, TileDesc* __restrict__ order_down) {
+    const void* const* __restrict__ down_b1, TileDesc* __restrict__ order_up,
+    TileDesc* __restrict__ order_down) {
   __shared__ int32_t start[MOE_MAX_EXPERTS + 1];
   __shared__ int bad;
   const int tid = threadIdx.x;
@@ -125,7 +129,8 @@ __global__ __launch_bounds__(256) void mfma_sched_kernel(
       t.nblk = n;
       t.expert = lo;
       t.b0 = pass == 0 ? up_b0[lo] : down_b0[lo];
-      t.b1 = pass == 0 && up_b1 != nullptr ? up_b1[lo] : nullptr;
+      const void* const* tab1 = pass == 0 ? up_b1 : down_b1;
+      t.b1 = tab1 != nullptr ? tab1[lo] : nullptr;
       order[L] = t;
     }
   }
@@ -174,6 +179,9 @@ struct GemmArgs {
   float* split_ws;         // DOWN: fp32 partial tiles of the K-split tail
   uint16_t* Gs;            // UP: optional save (out); DH: saved G (in)
   uint16_t* Us;
+  // k-major weight-role operand (BKM kernels): B[k][n] with ldb elements per k-row; the first
+  // kseg k-steps come from the tile's first matrix, the rest from its second one
+  int ldb, kseg;
 };
 
 // One unit of work of a block: a whole tile, or one K-split part of a tile (all fields are
@@ -185,6 +193,7 @@ struct Unit {
   const char* bbase0;       // weight-role operand: first row of the column block (gate/up: W1)
   const char* bbase1;       // gate/up: the same rows of W3; else bbase0 + 128 rows
   int KT;                   // k-steps of 64 (even)
+  int kstart;               // first k-step of the unit (K-split parts; 0 otherwise)
   int ws_unit;              // >= 0: K-split part, index of its partial tile in the workspace
 };
 
@@ -192,7 +201,7 @@ struct Unit {
 // blocks round-robin to the XCDs) owns a contiguous range of the tile order and, after it,
 // a contiguous range of the K-split units of the tail; its gridDim/8 blocks take them in
 // turn.  The sequence of a block is dense: once a unit is invalid, all later ones are.
-template <int MODE>
+template <int MODE, bool BKM>
 __device__ __forceinline__ Unit fetch_unit(const GemmArgs& p, int idx) {
   Unit u;
   u.valid = 0;
@@ -226,9 +235,13 @@ __device__ __forceinline__ Unit fetch_unit(const GemmArgs& p, int idx) {
   u.row0 = td.row0;
   u.rows = td.rows;
   u.nblk = td.nblk;
+  u.kstart = kstart;
   const size_t kbeg = (size_t)kstart * (BK * 2);  // bytes into a row
   u.abase = (const char*)p.A + (size_t)td.row0 * p.lda * 2 + kbeg;
-  if (MODE == MODE_UP) {
+  if (BKM) {   // column block of the k-major matrices; the k-step is applied per copy
+    u.bbase0 = (const char*)td.b0 + (size_t)td.nblk * 512;
+    u.bbase1 = (const char*)td.b1 + (size_t)td.nblk * 512;
+  } else if (MODE == MODE_UP) {
     u.bbase0 = (const char*)td.b0 + (size_t)td.nblk * 128 * p.K * 2 + kbeg;
     u.bbase1 = (const char*)td.b1 + (size_t)td.nblk * 128 * p.K * 2 + kbeg;
   } else {
@@ -241,7 +254,7 @@ __device__ __forceinline__ Unit fetch_unit(const GemmArgs& p, int idx) {
 // One cluster pair of the main loop: memory cluster of token block I in stage S (fragment
 // reads; two copies, base + offset each, into the rows read one cluster ago), then the
 // compute cluster.
-template <int S, int I>
+template <int S, int I, bool BKM>
 __device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][4],
                                            const uint4* lds, const int (&fr_a)[4],
                                            const int (&fr_b)[2], int fr_half, int fr_swz,
@@ -254,8 +267,20 @@ __device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-        wb[j][kk] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ((kk * 2 + fr_half) ^ fr_swz)]);
+      for (int j = 0; j < 2; ++j) {
+        if (BKM) {
+          // k-major stage (64 k-rows x 512 bytes): fr_b[j] is the lane's LDS byte address for
+          // k-rows 0..3 of its 16-row group; two transpose reads make the 8 k of the fragment
+          const uint32_t a0 = (uint32_t)fr_b[j] + (2 * S + 1) * 32768 + kk * 8192;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)a0);
+          const s16x4 hi =
+              __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(a0 + 4 * 512));
+          const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          wb[j][kk] = __builtin_bit_cast(bf16x8, v);
+        } else {
+          wb[j][kk] = __builtin_bit_cast(bf16x8, Bs[fr_b[j] + ((kk * 2 + fr_half) ^ fr_swz)]);
+        }
+      }
   }
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
@@ -292,7 +317,13 @@ __device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][
 // order, and the copy stream does not stop at a tile boundary: during the last two k-steps
 // of a tile the rows that become free are refilled with the first two k-steps of the
 // block's next tile, so that only the very first tile of a block pays a load latency.
-template <int MODE>
+//
+// BKM: the weight-role operand is stored k-major, B[k][n] (the data gradients contract over
+// the other index of the weights).  A stage then holds 64 k-rows x 256 columns (512 bytes
+// per row, 16-byte chunks XOR-swizzled by (row & 3) << 1), copied as it is -- one copy
+// instruction fills two k-rows -- and the fragments come out of LDS through the transpose
+// read ds_read_b64_tr_b16 (the layout and the lane arithmetic of wgrad_tr.hip).
+template <int MODE, bool BKM = false>
 __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   // stage s: token rows at (2s) * STAGE_VEC, weight rows at (2s+1) * STAGE_VEC
   __shared__ uint4 lds[4 * STAGE_VEC];
@@ -315,10 +346,25 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   };
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int rb = (8 * i + wave) * 8 + (lane >> 3);
-    b_off[i] = (uint32_t)(rb & 127) * b_pitch + (((lane & 7) ^ swz(rb)) << 4);
+    if (BKM) {   // copy i of the wavefront: k-rows 2c and 2c+1 of the step, c = 8i + wave
+      const int r = 2 * (8 * i + wave) + (lane >> 5);
+      b_off[i] = (uint32_t)r * (uint32_t)(p.ldb * 2) + (((lane & 31) ^ ((r & 3) << 1)) << 4);
+    } else {
+      const int rb = (8 * i + wave) * 8 + (lane >> 3);
+      b_off[i] = (uint32_t)(rb & 127) * b_pitch + (((lane & 7) ^ swz(rb)) << 4);
+    }
   }
-  cur = fetch_unit<MODE>(p, 0);
+  // weight-role source of k-step `step` of unit u (half: 0 = first, 1 = second 128 rows of the
+  // column block when the operand is row-major)
+  const size_t bstep = (size_t)BK * p.ldb * 2;
+  auto bsrc = [&](const Unit& u, int step, int half) -> const char* {
+    if (BKM) {
+      const int kg = u.kstart + step;
+      return kg < p.kseg ? u.bbase0 + (size_t)kg * bstep : u.bbase1 + (size_t)(kg - p.kseg) * bstep;
+    }
+    return (half ? u.bbase1 : u.bbase0) + step * 128;
+  };
+  cur = fetch_unit<MODE, BKM>(p, 0);
   if (!cur.valid) return;
 #pragma unroll
   for (int i = 0; i < 4; ++i) a_off[i] = token_off(cur.rows, i);
@@ -331,6 +377,18 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   for (int i = 0; i < 4; ++i) fr_a[i] = (wm * 128 + i * 32 + fr_row) * 8;
 #pragma unroll
   for (int j = 0; j < 2; ++j) fr_b[j] = (j * 128 + wn * 32 + fr_row) * 8;
+  if (BKM) {
+    // transpose reads: groups of 16 lanes; lane (j4 = (lane & 15) >> 2, q4 = lane & 3) of group
+    // g16 = lane >> 4 points at k-row 8 * (g16 >> 1) + j4 and the 4 columns 16 * (g16 & 1) +
+    // 4 * q4 .. + 3 of the fragment's 32 columns
+    const int g16 = lane >> 4, j4 = (lane & 15) >> 2, q4 = lane & 3;
+    const uint32_t lb = (uint32_t)(uintptr_t)(lptr_t)lds;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int chunk = (j * 128 + wn * 32 + (g16 & 1) * 16) / 8 + (q4 >> 1);
+      fr_b[j] = (int)(lb + (8 * (g16 >> 1) + j4) * 512 + ((chunk ^ (j4 << 1)) << 4) + (q4 & 1) * 8);
+    }
+  }
 
   f32x16 acc[2][4];
 
@@ -488,7 +546,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       dma16(a_off[i], cur.abase + st * 128, a_dst + st * 65536 + i * 4096);
-      dma16(b_off[i], (i < 2 ? cur.bbase0 : cur.bbase1) + st * 128, b_dst + st * 65536 + i * 8192);
+      dma16(b_off[i], bsrc(cur, st, i >= 2), b_dst + st * 65536 + i * 8192);
     }
   // stage 0 has landed (stage 1 is first read four clusters on, after the vmcnt(6) waits)
   asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
@@ -496,7 +554,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
 
   bf16x8 wb[2][4];
   for (int idx = 0;; ++idx) {
-    const Unit nxt = fetch_unit<MODE>(p, idx + 1);
+    const Unit nxt = fetch_unit<MODE, BKM>(p, idx + 1);
     zero_acc();
     const int KT = cur.KT;
     // steady part: steps 0 .. KT-3; what was read one cluster ago is refilled with the data
@@ -504,18 +562,16 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
     // step k+2; at i == 0 block 3 of the other stage with step k+1)
     for (int kt = 0; kt < KT - 2; kt += 2) {
       const char* a1 = cur.abase + (kt + 1) * 128;  // step kt+1 (+128: kt+2, +256: kt+3)
-      const char* b01 = cur.bbase0 + (kt + 1) * 128;
-      const char* b11 = cur.bbase1 + (kt + 1) * 128;
 #define PP(S, I, OA, BA, OB, BB) \
-  pp_cluster<S, I>(acc, wb, lds, fr_a, fr_b, fr_half, fr_swz, OA, BA, OB, BB, a_dst, b_dst)
-      PP(0, 0, a_off[3], a1, b_off[3], b11);
-      PP(0, 1, a_off[0], a1 + 128, b_off[0], b01 + 128);
-      PP(0, 2, a_off[1], a1 + 128, b_off[1], b01 + 128);
-      PP(0, 3, a_off[2], a1 + 128, b_off[2], b11 + 128);
-      PP(1, 0, a_off[3], a1 + 128, b_off[3], b11 + 128);
-      PP(1, 1, a_off[0], a1 + 256, b_off[0], b01 + 256);
-      PP(1, 2, a_off[1], a1 + 256, b_off[1], b01 + 256);
-      PP(1, 3, a_off[2], a1 + 256, b_off[2], b11 + 256);
+  pp_cluster<S, I, BKM>(acc, wb, lds, fr_a, fr_b, fr_half, fr_swz, OA, BA, OB, BB, a_dst, b_dst)
+      PP(0, 0, a_off[3], a1, b_off[3], bsrc(cur, kt + 1, 1));
+      PP(0, 1, a_off[0], a1 + 128, b_off[0], bsrc(cur, kt + 2, 0));
+      PP(0, 2, a_off[1], a1 + 128, b_off[1], bsrc(cur, kt + 2, 0));
+      PP(0, 3, a_off[2], a1 + 128, b_off[2], bsrc(cur, kt + 2, 1));
+      PP(1, 0, a_off[3], a1 + 128, b_off[3], bsrc(cur, kt + 2, 1));
+      PP(1, 1, a_off[0], a1 + 256, b_off[0], bsrc(cur, kt + 3, 0));
+      PP(1, 2, a_off[1], a1 + 256, b_off[1], bsrc(cur, kt + 3, 0));
+      PP(1, 3, a_off[2], a1 + 256, b_off[2], bsrc(cur, kt + 3, 1));
     }
     // last two steps: the refills fetch steps 0 and 1 of the next unit (the token offsets
     // are switched block by block, each right after its last use for this unit).  Without a
@@ -524,10 +580,12 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
     {
       const int last = (KT - 1) * 128;
       const char* na = nxt.valid ? nxt.abase : cur.abase + last;      // next unit's step 0
-      const char* nb0 = nxt.valid ? nxt.bbase0 : cur.bbase0 + last;
-      const char* nb1 = nxt.valid ? nxt.bbase1 : cur.bbase1 + last;
+      const char* nb0 = nxt.valid ? bsrc(nxt, 0, 0) : bsrc(cur, KT - 1, 0);
+      const char* nb1 = nxt.valid ? bsrc(nxt, 0, 1) : bsrc(cur, KT - 1, 1);
       const int o1 = nxt.valid ? 128 : 0;                             // ... its step 1
-      PP(0, 0, a_off[3], cur.abase + last, b_off[3], cur.bbase1 + last);
+      const char* nc0 = nxt.valid ? bsrc(nxt, 1, 0) : nb0;
+      const char* nc1 = nxt.valid ? bsrc(nxt, 1, 1) : nb1;
+      PP(0, 0, a_off[3], cur.abase + last, b_off[3], bsrc(cur, KT - 1, 1));
       if (nxt.valid) {
 #pragma unroll
         for (int i = 0; i < 3; ++i) a_off[i] = token_off(nxt.rows, i);
@@ -537,9 +595,9 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
       PP(0, 3, a_off[2], na, b_off[2], nb1);
       if (nxt.valid) a_off[3] = token_off(nxt.rows, 3);
       PP(1, 0, a_off[3], na, b_off[3], nb1);
-      PP(1, 1, a_off[0], na + o1, b_off[0], nb0 + o1);
-      PP(1, 2, a_off[1], na + o1, b_off[1], nb0 + o1);
-      PP(1, 3, a_off[2], na + o1, b_off[2], nb1 + o1);
+      PP(1, 1, a_off[0], na + o1, b_off[0], nc0);
+      PP(1, 2, a_off[1], na + o1, b_off[1], nc0);
+      PP(1, 3, a_off[2], na + o1, b_off[2], nc1);
 #undef PP
     }
     epilogue(cur);
@@ -588,59 +646,6 @@ __global__ __launch_bounds__(NT) void ffn_split_reduce_kernel(const GemmArgs p) 
   }
 }
 
-// ---- transposes feeding the backward's data-gradient GEMMs ---------------------------
-// The GEMMs of this file want both operands contiguous along the contraction dimension.  The
-// data gradients contract over the other index of the weights (dH = dY W2, dX = dG W1 +
-// dU W3), so the weights are transposed once per call, 64 x 64 elements per block through
-// LDS, 16 bytes per lane on both the global reads and the global writes.  (The weight
-// gradients, which contract over the token rows, need no transposed copies: wgrad_tr.hip.)  LDS row pitch 66 elements: the eight 2-byte reads
-// that gather one output chunk fall on distinct banks across the wavefront.
-constexpr int TP = 66;
-
-// in: 64 x 64 tile, row r at src + r * pitch (rows >= valid_rows read as zero)
-__device__ __forceinline__ void tile_in(uint16_t (*tile)[TP], const uint16_t* src, size_t pitch,
-                                        int valid_rows) {
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int chunk = threadIdx.x + h * 256;
-    const int r = chunk >> 3, ch = chunk & 7;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < valid_rows) v = *reinterpret_cast<const uint4*>(src + (size_t)r * pitch + ch * 8);
-    uint32_t* d = reinterpret_cast<uint32_t*>(&tile[r][ch * 8]);   // 4-byte aligned (pitch 132 B)
-    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-  }
-}
-
-// out: row c of the transposed tile (= column c of the input) at dst + c * pitch, 64 elements
-__device__ __forceinline__ void tile_out_t(const uint16_t (*tile)[TP], uint16_t* dst, size_t pitch) {
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int chunk = threadIdx.x + h * 256;
-    const int c = chunk >> 3, q = chunk & 7;
-    uint32_t w[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      w[j] = (uint32_t)tile[8 * q + 2 * j][c] | ((uint32_t)tile[8 * q + 2 * j + 1][c] << 16);
-    store16(dst + (size_t)c * pitch + q * 8, w[0], w[1], w[2], w[3]);
-  }
-}
-
-// out[c][col_off + r] = in[r][c] for every expert with a source; in: [R,C], out pitch given.
-__global__ __launch_bounds__(256) void transpose_weights_kernel(const void* const* __restrict__ src_t,
-                                                                const void* const* __restrict__ dst_t,
-                                                                int R, int C, int dst_pitch,
-                                                                int col_off) {
-  __shared__ uint16_t tile[64][TP];
-  const int e = blockIdx.z;
-  const uint16_t* src = (const uint16_t*)src_t[e];
-  uint16_t* dst = (uint16_t*)dst_t[e];
-  if (src == nullptr || dst == nullptr) return;
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  tile_in(tile, src + (size_t)r0 * C + c0, C, 64);
-  __syncthreads();
-  tile_out_t(tile, dst + (size_t)c0 * dst_pitch + col_off + r0, dst_pitch);
-}
-
 }  // namespace
 
 // two-matrix expert: the first GEMM has 256-column blocks of one matrix
@@ -662,11 +667,11 @@ size_t ffn_mfma_order_entries(const moe_ctx* c) {
 
 static int run_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets, int nt_a, int nt_b,
                      int kt_b, const void* const* up_b0, const void* const* up_b1,
-                     const void* const* down_b0, hipStream_t s) {
+                     const void* const* down_b0, const void* const* down_b1, hipStream_t s) {
   hipLaunchKernelGGL(mfma_sched_kernel, dim3(32), dim3(256), 0, s, counts, offsets,
                      c->d_wtab + 0 * MOE_MAX_EXPERTS, c->cfg.E, c->S_max, c->max_mtiles[1], nt_a,
-                     nt_b, c->n_cu, kt_b, c->d_sched[1], up_b0, up_b1, down_b0, c->d_order_up,
-                     c->d_order_down);
+                     nt_b, c->n_cu, kt_b, c->d_sched[1], up_b0, up_b1, down_b0, down_b1,
+                     c->d_order_up, c->d_order_down);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 
@@ -704,7 +709,8 @@ int launch_ffn_mfma(moe_ctx* c, bool gated, const int32_t* counts, const int32_t
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
   const int max_mt = c->max_mtiles[1];
   prof_mark(c, 0, s);
-  int st = run_sched(c, counts, offsets, nt_up, nt_down, f / BK, W1, gated ? W3 : nullptr, W2, s);
+  int st = run_sched(c, counts, offsets, nt_up, nt_down, f / BK, W1, gated ? W3 : nullptr, W2,
+                     nullptr, s);
   if (st != MOE_OK) return st;
   prof_mark(c, 1, s);
   GemmArgs up = tiled_args(c, x_packed, d, c->d_order_up, nt_up, d, f, c->d_H);
@@ -726,52 +732,39 @@ bool ffn_bwd_mfma_supported(const moe_ctx* c) {
 }
 
 // dy, xp: [S,d]; G, U: [S,f] (forward saves); dxp out.  Workspace (context): d_H [S,f],
-// d_dGU [S,2f]; table rows 6 (W2^T) and 7 ([W1^T|W3^T]) point into d_wT.  Two-matrix expert (!gated):
-// no U, no W3: d_dGU holds dG [S,f], row 7 points to W1^T [d,f], two weight gradients.
+// d_dGU [S,2f].  Two-matrix expert (!gated): no U, no W3: d_dGU holds dG [S,f], two weight
+// gradients.  The weights are read as they are stored: W2 [d,f] is k-major for dH = dY W2,
+// W1 and W3 [f,d] are k-major for dX = dG W1 + dU W3 (one GEMM over the concatenated k).
 int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, const void* G,
                         const void* U, const int32_t* counts, const int32_t* offsets, void* dxp,
                         hipStream_t s) {
-  const int d = c->cfg.d, f = c->cfg.f, E = c->cfg.E;
+  const int d = c->cfg.d, f = c->cfg.f;
   const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
   const void* const* W3 = c->d_wtab + 1 * MOE_MAX_EXPERTS;
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
-  const void* const* W2T = c->d_wtab + 6 * MOE_MAX_EXPERTS;
-  const void* const* W13T = c->d_wtab + 7 * MOE_MAX_EXPERTS;
   const int nt_f = f / 256, nt_d = d / 256;
-  const int gw = gated ? 2 * f : f;   // elements per row of [dG|dU] and of [W1^T|W3^T]
-  int st = run_sched(c, counts, offsets, nt_f, nt_d, gw / BK, W2T, nullptr, W13T, s);
+  const int gw = gated ? 2 * f : f;   // elements per row of [dG|dU]
+  int st = run_sched(c, counts, offsets, nt_f, nt_d, gw / BK, W2, nullptr, W1,
+                     gated ? W3 : nullptr, s);
   if (st != MOE_OK) return st;
-  // The transposes are HBM-bound; the one the first GEMM does not wait for runs beside it on
-  // the context's second stream x:
-  //   s: W2^T, dH GEMM ....., dX GEMM, weight gradients
-  //   x: [W1^T|W3^T] .......|
-  hipStream_t x = c->aux_stream;
-  hipEvent_t ev_fork = c->aux_ev[0], ev_w13 = c->aux_ev[1];
-  bool ok = hipEventRecord(ev_fork, s) == hipSuccess && hipStreamWaitEvent(x, ev_fork, 0) == hipSuccess;
-  if (!ok) return MOE_EHIP;
-  // weights: W1, W3 [f,d] -> [W1^T | W3^T] [d,2f] (second stream); W2 [d,f] -> W2^T [f,d]
-  hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, x, W1, W13T, f,
-                     d, gw, 0);
-  if (gated)
-    hipLaunchKernelGGL(transpose_weights_kernel, dim3(d / 64, f / 64, E), dim3(256), 0, x, W3, W13T,
-                       f, d, gw, f);
-  ok = ok && hipEventRecord(ev_w13, x) == hipSuccess;
-  hipLaunchKernelGGL(transpose_weights_kernel, dim3(f / 64, d / 64, E), dim3(256), 0, s, W2, W2T, d,
-                     f, d, 0);
   // dH = dY W2 with the activation's derivative in the epilogue -> [dG|dU], H
   GemmArgs dh = tiled_args(c, dy, d, c->d_order_up, nt_f, d, f, c->d_dGU);
   dh.C2 = (uint16_t*)c->d_H;
   dh.Gs = (uint16_t*)const_cast<void*>(G);
   dh.Us = (uint16_t*)const_cast<void*>(U);
+  dh.ldb = f;
+  dh.kseg = d / BK;
   if (gated)
-    hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
+    hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH, true>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
   else
-    hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH1>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
-  // dX = [dG|dU] [W1^T|W3^T]^T  (one GEMM with contraction length 2f; f without U)
-  ok = ok && hipStreamWaitEvent(s, ev_w13, 0) == hipSuccess;
+    hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH1, true>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
+  // dX = [dG|dU] [W1; W3]  (one GEMM with contraction length 2f; f without U)
   GemmArgs dx = tiled_args(c, c->d_dGU, gw, c->d_order_down, nt_d, gw, d, dxp);
-  launch_down(c, dx, nt_d, s);
-  if (!ok) return MOE_EHIP;
+  dx.ldb = d;
+  dx.kseg = f / BK;
+  dx.split_ws = c->d_split_ws;
+  hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN, true>), dim3(persistent_grid(c)), dim3(NT), 0, s, dx);
+  hipLaunchKernelGGL(ffn_split_reduce_kernel, dim3((c->n_cu / 2) * 8), dim3(NT), 0, s, dx);
   // weight gradients straight from dY, X, H and [dG|dU] (transpose reads from LDS)
   st = launch_wgrad_tr(c, gated, dy, xp, c->d_H, c->d_dGU, counts, offsets, s);
   if (st != MOE_OK) return st;

@@ -36,11 +36,7 @@ void free_all(moe_ctx* c) {
   (void)hipFree(c->d_dG);
   (void)hipFree(c->d_dU);
   (void)hipFree(c->d_dGU);
-  (void)hipFree(c->d_wT);
   (void)hipFree(c->d_zero);
-  if (c->aux_stream != nullptr) (void)hipStreamDestroy(c->aux_stream);
-  for (hipEvent_t e : c->aux_ev)
-    if (e != nullptr) (void)hipEventDestroy(e);
 }
 
 int check_ctx_T(const moe_ctx* c, int32_t T) {
@@ -367,7 +363,7 @@ int moe_expert_ffn(moe_ctx* c, const void* x_packed, const int32_t* expert_count
   if (!aligned16(x_packed) || !aligned16(y_packed) || !aligned16(G_save) || !aligned16(U_save))
     return MOE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
-  const void* const* tabs[MOE_WTAB_ROWS] = {W1, W3, W2, nullptr, nullptr, nullptr, nullptr, nullptr};
+  const void* const* tabs[MOE_WTAB_ROWS] = {W1, W3, W2, nullptr, nullptr, nullptr};
   st = sync_tables(c, tabs, s);
   if (st != MOE_OK) return st;
   if (c->ffn_path == MOE_FFN_AUTO && (gated ? ffn_mfma_supported(c) : ffn_mfma_supported_2mat(c))) {
@@ -434,10 +430,7 @@ int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, 
   hipStream_t s = (hipStream_t)stream;
   const size_t sf_bytes = std::max<size_t>((size_t)c->S_max * c->cfg.f * c->elem, 16);
   if (c->ffn_path == MOE_FFN_AUTO && ffn_bwd_mfma_supported(c)) {
-    // first call (or more resident experts than before): allocate the backward workspace
-    const int d = c->cfg.d, f = c->cfg.f, E = c->cfg.E;
-    size_t n_present = 0;
-    for (int e = 0; e < E; ++e) n_present += W1[e] != nullptr;
+    // first call: allocate the backward workspace
     if (c->d_dGU == nullptr) {
       bool ok = hipMalloc(&c->d_dGU, 2 * sf_bytes) == hipSuccess;
       // the fill runs on the null stream: wait for it, the caller's stream may not
@@ -452,55 +445,12 @@ int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, 
         return MOE_ENOMEM;
       }
     }
-    if (c->aux_stream == nullptr) {
-      bool ok = hipStreamCreateWithFlags(&c->aux_stream, hipStreamNonBlocking) == hipSuccess;
-      for (int i = 0; i < 2 && ok; ++i)
-        ok = hipEventCreateWithFlags(&c->aux_ev[i], hipEventDisableTiming) == hipSuccess;
-      if (!ok) {
-        (void)hipGetLastError();
-        if (c->aux_stream != nullptr) (void)hipStreamDestroy(c->aux_stream);
-        c->aux_stream = nullptr;
-        for (hipEvent_t& e : c->aux_ev) {
-          if (e != nullptr) (void)hipEventDestroy(e);
-          e = nullptr;
-        }
-        return MOE_EHIP;
-      }
-    }
-    if (n_present > c->wT_experts) {
-      if (c->d_wT != nullptr) {
-        (void)hipStreamSynchronize(s);
-        (void)hipFree(c->d_wT);
-        c->d_wT = nullptr;
-        c->wT_experts = 0;
-      }
-      if (hipMalloc(&c->d_wT, n_present * 3 * (size_t)d * f * 2) != hipSuccess) {
-        (void)hipGetLastError();
-        return MOE_ENOMEM;
-      }
-      c->wT_experts = n_present;
-    }
-    const void* w2t[MOE_MAX_EXPERTS];
-    const void* w13t[MOE_MAX_EXPERTS];
-    size_t slot = 0;
-    for (int e = 0; e < E; ++e) {
-      if (W1[e] == nullptr) {
-        w2t[e] = w13t[e] = nullptr;
-        continue;
-      }
-      uint16_t* base = (uint16_t*)c->d_wT + slot * 3 * (size_t)d * f;
-      w2t[e] = base;
-      w13t[e] = base + (size_t)d * f;
-      ++slot;
-    }
     const void* const* tabs[MOE_WTAB_ROWS] = {W1,
                                               W3,
                                               W2,
                                               reinterpret_cast<const void* const*>(dW1),
                                               reinterpret_cast<const void* const*>(dW3),
-                                              reinterpret_cast<const void* const*>(dW2),
-                                              w2t,
-                                              w13t};
+                                              reinterpret_cast<const void* const*>(dW2)};
     st = sync_tables(c, tabs, s);
     if (st != MOE_OK) return st;
     return launch_ffn_bwd_mfma(c, gated, dy_packed, x_packed, G_save, U_save, expert_counts,
@@ -519,9 +469,7 @@ int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, 
                                             W2,
                                             reinterpret_cast<const void* const*>(dW1),
                                             reinterpret_cast<const void* const*>(dW3),
-                                            reinterpret_cast<const void* const*>(dW2),
-                                            nullptr,
-                                            nullptr};
+                                            reinterpret_cast<const void* const*>(dW2)};
   st = sync_tables(c, tabs, s);
   if (st != MOE_OK) return st;
   st = launch_build_sched(c, expert_counts, expert_offsets, 0, s);

@@ -36,8 +36,8 @@ struct TileSched {
   int32_t down_split;
 };
 
-// pointer-table rows: W1, W3, W2, dW1, dW3, dW2, W2^T, [W1^T|W3^T]
-#define MOE_WTAB_ROWS 8
+// pointer-table rows: W1, W3, W2, dW1, dW3, dW2
+#define MOE_WTAB_ROWS 6
 
 struct moe_ctx {
   moe_config cfg;
@@ -74,12 +74,6 @@ struct moe_ctx {
   void* d_dU;             // [T_max*k][f]
   void* d_dGU;            // [T_max*k][2f]  (MFMA backward: dG | dU)
   void* d_zero;           // 512 bytes of zeros (rows past a segment's end in the weight gradients)
-  void* d_wT;             // transposed weights of the MFMA backward
-  size_t wT_experts;      // experts d_wT has room for
-  // MFMA backward: the transposes run on a second stream (default priority) beside the
-  // GEMMs; events fork it from / join it into the caller's stream
-  hipStream_t aux_stream;
-  hipEvent_t aux_ev[2];   // fork, [W1^T|W3^T] ready
   // gate backward: per-chunk partial sums of dWg, [T_max/128][E][d] (first call allocates)
   float* d_rbwd_ws;
   // shared/residual compression: selection state, histogram, per-chunk counts
