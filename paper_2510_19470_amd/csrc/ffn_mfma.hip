@@ -163,6 +163,15 @@ __device__ __forceinline__ uint4 pair16(uint2 a /* piece g */, uint2 b /* piece 
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
   return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
 }
+// The inverse, for epilogue loads: every lane loads the 16 bytes pair16 would store (lanes
+// 0-31 columns 8g .. 8g+7, lanes 32-63 columns 8(g+1) .. 8(g+1)+7 of their row); the swaps
+// give each lane its own 8-byte pieces of g (a) and g+1 (b).
+__device__ __forceinline__ void unpair16(const uint4& v, uint2& a, uint2& b) {
+  const auto x = __builtin_amdgcn_permlane32_swap(v.x, v.z, false, false);
+  const auto y = __builtin_amdgcn_permlane32_swap(v.y, v.w, false, false);
+  a = make_uint2(x[0], y[0]);
+  b = make_uint2(x[1], y[1]);
+}
 
 enum { MODE_UP = 0, MODE_DOWN = 1, MODE_DH = 2, MODE_UP1 = 4, MODE_DH1 = 5 };
 
@@ -415,6 +424,22 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
       const int m_local = wm * 128 + i * 32 + fr_row;
       const bool live = m_local < u.rows;
       const size_t row = (size_t)(u.row0 + m_local);
+      // MODE_DH, MODE_DH1: the saved G (and U) of the whole row block, 16 bytes per lane at the
+      // addresses the outputs are stored to, all requested before the first is used
+      uint4 gsv[2][2], usv[2][2];
+      if (MODE == MODE_DH || MODE == MODE_DH1) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int gp = 0; gp < 2; ++gp) {
+            const size_t col = (size_t)u.nblk * 256 + j * 128 + wn * 32 + 8 * fr_half + 16 * gp;
+            gsv[j][gp] = usv[j][gp] = make_uint4(0, 0, 0, 0);
+            if (live) {
+              gsv[j][gp] = *reinterpret_cast<const uint4*>(p.Gs + row * p.N + col);
+              if (MODE == MODE_DH) usv[j][gp] = *reinterpret_cast<const uint4*>(p.Us + row * p.N + col);
+            }
+          }
+      }
       if (MODE == MODE_UP) {
         const int colb = u.nblk * 128 + wn * 32 + 8 * fr_half;
 #pragma unroll
@@ -466,17 +491,15 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
                                         pack4(acc[j][i][g0 * 4 + 4], acc[j][i][g0 * 4 + 5], acc[j][i][g0 * 4 + 6], acc[j][i][g0 * 4 + 7]));
                 if (live) *reinterpret_cast<uint4*>(p.Gs + row * p.N + col) = gv;
               }
-            } else {  // MODE_DH, MODE_DH1: saved G (and U) are read in the accumulator's own layout
+            } else {  // MODE_DH, MODE_DH1
               uint2 dgp[2], dup[2], hhp[2];
+              uint2 gqs[2], uqs[2];
+              unpair16(gsv[j][gp], gqs[0], gqs[1]);
+              unpair16(usv[j][gp], uqs[0], uqs[1]);
 #pragma unroll
               for (int t = 0; t < 2; ++t) {
                 const int g = g0 + t;
-                const size_t cg = (size_t)u.nblk * 256 + j * 128 + wn * 32 + 4 * fr_half + 8 * g;
-                uint2 gq = make_uint2(0, 0), uq = make_uint2(0, 0);
-                if (live) {
-                  gq = *reinterpret_cast<const uint2*>(p.Gs + row * p.N + cg);
-                  if (MODE == MODE_DH) uq = *reinterpret_cast<const uint2*>(p.Us + row * p.N + cg);
-                }
+                const uint2 gq = gqs[t], uq = uqs[t];
                 const uint32_t gw[2] = {gq.x, gq.y}, uw[2] = {uq.x, uq.y};
                 float dg[4], du[4], hh[4];
 #pragma unroll
