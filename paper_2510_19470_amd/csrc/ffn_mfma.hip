@@ -51,6 +51,10 @@ constexpr int STAGE_VEC = 2048;   // uint4 per operand per stage (256 rows x 8 c
 constexpr int ORDER_GROUP_M = 8;  // row blocks per group of the tile order
 
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
+// ... of a k-major stage (512-byte rows, transpose reads): the groups of 16 lanes that can
+// share an LDS cycle read 4 rows (row & 3) x 32 bytes each, from the two halves of bit 3 of
+// the row or the two 32-byte column halves; their 16 chunks must differ modulo 16
+__device__ __forceinline__ int tr_swz(int row) { return ((row & 3) << 2) ^ (((row >> 3) & 1) << 1); }
 
 // tile list entry: (mtile index << 12) | column block
 __global__ __launch_bounds__(256) void mfma_sched_kernel(
@@ -329,7 +333,7 @@ __device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][
 //
 // BKM: the weight-role operand is stored k-major, B[k][n] (the data gradients contract over
 // the other index of the weights).  A stage then holds 64 k-rows x 256 columns (512 bytes
-// per row, 16-byte chunks XOR-swizzled by (row & 3) << 1), copied as it is -- one copy
+// per row, 16-byte chunks XOR-swizzled by tr_swz(row)), copied as it is -- one copy
 // instruction fills two k-rows -- and the fragments come out of LDS through the transpose
 // read ds_read_b64_tr_b16 (the layout and the lane arithmetic of wgrad_tr.hip).
 template <int MODE, bool BKM = false>
@@ -357,7 +361,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   for (int i = 0; i < 4; ++i) {
     if (BKM) {   // copy i of the wavefront: k-rows 2c and 2c+1 of the step, c = 8i + wave
       const int r = 2 * (8 * i + wave) + (lane >> 5);
-      b_off[i] = (uint32_t)r * (uint32_t)(p.ldb * 2) + (((lane & 31) ^ ((r & 3) << 1)) << 4);
+      b_off[i] = (uint32_t)r * (uint32_t)(p.ldb * 2) + (((lane & 31) ^ tr_swz(r)) << 4);
     } else {
       const int rb = (8 * i + wave) * 8 + (lane >> 3);
       b_off[i] = (uint32_t)(rb & 127) * b_pitch + (((lane & 7) ^ swz(rb)) << 4);
@@ -395,7 +399,8 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int chunk = (j * 128 + wn * 32 + (g16 & 1) * 16) / 8 + (q4 >> 1);
-      fr_b[j] = (int)(lb + (8 * (g16 >> 1) + j4) * 512 + ((chunk ^ (j4 << 1)) << 4) + (q4 & 1) * 8);
+      const int row = 8 * (g16 >> 1) + j4;
+      fr_b[j] = (int)(lb + row * 512 + ((chunk ^ tr_swz(row)) << 4) + (q4 & 1) * 8);
     }
   }
 

@@ -17,8 +17,8 @@
 // = 4 x 2 accumulators of v_mfma_f32_32x32x16_bf16, as in the forward kernels.  The k-loop
 // runs in half-steps of 32 token rows through 4 LDS stages of 32 KB (P tile 16 KB + Q tile
 // 16 KB); the copies of half-step h+3 are issued when half-step h starts.  16-byte chunks of
-// a row are XOR-swizzled by (row & 3) << 1, which puts the 4 rows x 32 bytes that a group of
-// 16 lanes reads on distinct banks.  Rows past the end of the expert's segment are fetched
+// a row are XOR-swizzled (tr_swz below), which puts the rows x 32 bytes that the groups of 16
+// lanes sharing an LDS cycle read on distinct banks.  Rows past the end of the expert's segment are fetched
 // from a row of zeros, so a ragged segment needs no padded copy.
 #include "moe_internal.h"
 
@@ -44,11 +44,20 @@ struct WgradArgs {
     int p_pitch, p_col0, q_pitch, Mo, No;
   } job[3];
   int n_jobs, E;
+  int n_list;                         // experts that get weight gradients
+  uint8_t list[MOE_MAX_EXPERTS];      // ... their ids, ascending
   const int32_t* counts;
   const int32_t* offsets;
-  const void* const* present;
   const uint16_t* zero_row;   // 512 bytes of zeros
 };
+
+// Swizzle of the 16-byte chunks of a 512-byte tile row.  A transpose read takes, per group of
+// 16 lanes, 4 rows (j4 = row & 3) x 32 bytes; the four groups of a wavefront are (hh = bit 3
+// of the row, cb = the 32-byte column half).  LDS has 64 banks of 4 bytes and serves 32 lanes
+// per cycle, and the row pitch is a multiple of 256 bytes, so the 16 chunks of any two
+// groups that can share a cycle -- (hh, cb = 0 | 1) or (hh = 0 | 1, cb) -- must differ
+// modulo 16: bits 2-3 of the chunk take j4, bit 1 takes hh (cb sits in bit 1 already).
+__device__ __forceinline__ int tr_swz(int row) { return ((row & 3) << 2) ^ (((row >> 3) & 1) << 1); }
 
 // 16 bytes per lane global -> LDS, per-lane 64-bit address; the wavefront's 1 KB lands at
 // lds_addr (wave-uniform, via M0) + lane * 16.
@@ -63,17 +72,26 @@ __global__ __launch_bounds__(NT) void wgrad_tr_kernel(const WgradArgs p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
 
-  // block -> (job, expert, row block of dW, column block of dW); every job has the same
-  // number of tiles per expert
+  // block -> tile.  The tiles are ordered (expert, job, groups of 4 row blocks of dW, column
+  // block, row block inside the group): 32 consecutive tiles are a 4 x 8 patch of one matrix,
+  // 12 operand panels for 32 tiles.  The hardware deals blocks round-robin to the 8 XCDs, each
+  // with an L2 of its own, so XCD x (= blockIdx & 7) takes the chunks of 32 consecutive tiles
+  // x, x + 8, ...: the 32 blocks resident on an XCD share their panels in its L2.  (Every job
+  // has the same number of tiles per expert.)
   const int tiles = (p.job[0].Mo >> 8) * (p.job[0].No >> 8);
-  const int per_job = (int)gridDim.x / p.n_jobs;
-  const int jidx = blockIdx.x / per_job, jb = blockIdx.x % per_job;
-  const WgradArgs::Job& J = p.job[jidx];
-  const int e = jb / tiles, rem = jb % tiles;
-  const int NoT = J.No >> 8;
-  const int mblk = rem / NoT, nblk = rem % NoT;
+  const int total = p.n_list * p.n_jobs * tiles;
+  const int slot = (int)(blockIdx.x >> 3), xcd = (int)(blockIdx.x & 7);
+  const int L = ((slot >> 5) * 8 + xcd) * 32 + (slot & 31);
+  if (L >= total) return;
+  const int ej = L / tiles, rel = L % tiles;
+  const int e = p.list[ej / p.n_jobs];
+  const WgradArgs::Job& J = p.job[ej % p.n_jobs];
+  const int NoT = J.No >> 8, MoT = J.Mo >> 8;
+  const int mg = rel / (4 * NoT), r2 = rel % (4 * NoT);
+  const int gm = min(4, MoT - 4 * mg);
+  const int nblk = r2 / gm, mblk = 4 * mg + r2 % gm;
   float* dW = (float*)J.dWt[e];
-  if (dW == nullptr || p.present[e] == nullptr) return;
+  if (dW == nullptr) return;   // this gradient is not wanted
   const int n_e = p.counts[e];
   const int row0 = p.offsets[e];
   const int NH = (n_e + HK - 1) / HK;
@@ -89,7 +107,7 @@ __global__ __launch_bounds__(NT) void wgrad_tr_kernel(const WgradArgs p) {
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
 
   // ---- copies: instruction c (0..15) of a tile fills rows 2c (lanes 0-31) and 2c+1 (lanes
-  // 32-63), 32 chunk slots each; slot s of row r holds global chunk s ^ ((r & 3) << 1).
+  // 32-63), 32 chunk slots each; slot s of row r holds global chunk s ^ tr_swz(r).
   // Wavefront w issues instructions w and w + 8 of the P tile and of the Q tile.
   const int c_row = lane >> 5, c_slot = lane & 31;
   const char* p_col = (const char*)(J.P + J.p_col0 + mblk * 256);
@@ -101,7 +119,7 @@ __global__ __launch_bounds__(NT) void wgrad_tr_kernel(const WgradArgs p) {
       const int c = wave + 8 * u;
       const int r = 2 * c + c_row;                     // row inside the stage
       const int rg = h * HK + r;                       // row inside the expert's segment
-      const int gch = c_slot ^ ((r & 3) << 1);         // global chunk this lane fetches
+      const int gch = c_slot ^ tr_swz(r);              // global chunk this lane fetches
       const bool ok = rg < n_e;
       const size_t rr = (size_t)(row0 + min(rg, n_e - 1));   // in bounds also when not used
       const char* zp = (const char*)p.zero_row + gch * 16;
@@ -116,7 +134,7 @@ __global__ __launch_bounds__(NT) void wgrad_tr_kernel(const WgradArgs p) {
   const int g16 = lane >> 4, hh = g16 >> 1, cb = g16 & 1;
   const int s16 = lane & 15, j4 = s16 >> 2, q4 = s16 & 3;
   const int rd_row = 8 * hh + j4;                 // + 16 * kk + 4 * t
-  const int rd_swz = j4 << 1;                     // (row & 3) << 1: the terms above keep row & 3
+  const int rd_swz = tr_swz(rd_row);              // + 16 * kk + 4 * t leaves the swizzle unchanged
   const int rd_half = (q4 & 1) * 8;
   int x_chunk[4], w_chunk[2];                     // chunk of the lane's 4 columns, before the swizzle
 #pragma unroll
@@ -145,7 +163,9 @@ __global__ __launch_bounds__(NT) void wgrad_tr_kernel(const WgradArgs p) {
       const uint32_t sb = (uint32_t)(h & (STAGES - 1)) * STAGE_BYTES;   // LDS offsets from 0: generic
       const uint32_t pt = lds_base + sb, qt = lds_base + sb + TILE_BYTES;
       // all 12 fragments of the half-step first (24 transpose reads in flight), then the 16
-      // MFMAs: the other wavefront of the SIMD computes meanwhile
+      // MFMAs: the other wavefront of the SIMD computes meanwhile (one barrier per half-step
+      // lets the wavefronts drift apart; a strict two-group ping-pong with two barriers per
+      // half-step measured 13 % slower)
       bf16x8 xa[2][4], wb[2][2];
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
@@ -198,7 +218,11 @@ int launch_wgrad_tr(moe_ctx* c, bool gated, const void* dy, const void* xp, cons
   a.E = E;
   a.counts = counts;
   a.offsets = offsets;
-  a.present = c->d_wtab + 0 * MOE_MAX_EXPERTS;
+  for (int e = 0; e < E; ++e)   // host copy of the pointer tables: resident, some dW wanted
+    if (c->h_wtab[0][e] != nullptr &&
+        (c->h_wtab[3][e] != nullptr || c->h_wtab[4][e] != nullptr || c->h_wtab[5][e] != nullptr))
+      a.list[a.n_list++] = (uint8_t)e;
+  if (a.n_list == 0) return MOE_OK;
   a.zero_row = (const uint16_t*)c->d_zero;
   const void* const* dW1 = c->d_wtab + 3 * MOE_MAX_EXPERTS;
   const void* const* dW3 = c->d_wtab + 4 * MOE_MAX_EXPERTS;
@@ -208,6 +232,7 @@ int launch_wgrad_tr(moe_ctx* c, bool gated, const void* dy, const void* xp, cons
   a.job[1] = {(const uint16_t*)dGU, (const uint16_t*)xp, dW1, gw, 0, d, f, d};
   a.job[2] = {(const uint16_t*)dGU, (const uint16_t*)xp, dW3, gw, f, d, f, d};
   const int tiles = (d / 256) * (f / 256);
-  hipLaunchKernelGGL(wgrad_tr_kernel, dim3(a.n_jobs * E * tiles), dim3(NT), 0, s, a);
+  const int total = a.n_jobs * a.n_list * tiles;
+  hipLaunchKernelGGL(wgrad_tr_kernel, dim3((total + 255) / 256 * 256), dim3(NT), 0, s, a);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
