@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per launch of the dominant kernel (read + written), from the two rocprofv3
 # --pmc passes (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0, factors from the plain 512 MiB copy of
 # --copy-calibration) summarised in profiles/hotpath_mixtral_kernel_trace_and_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"mixtral": 6448.9e6 + 469.7e6}
+MEASURED_TRAFFIC_BYTES = {"mixtral": 6528.4e6 + 469.8e6}
 
 
 def cpu_baseline(cfg, inp, sample_tokens: int):
@@ -359,8 +359,8 @@ def run(cfg, args) -> dict:
                    "resident_experts": n_res, "n_loc_rows": n_loc,
                    "steps_in_path": names},
         "roofline": {
-            "kernel": ("ffn_mfma_kernel<0> (MODE_UP: gate/up grouped GEMM + SwiGLU)" if cfg.gated
-                       else "ffn_mfma_kernel<4> (MODE_UP1: first GEMM of the two-matrix expert + ReLU)") if mfma
+            "kernel": ("ffn_mfma_kernel<0, false> (MODE_UP: gate/up grouped GEMM + SwiGLU)" if cfg.gated
+                       else "ffn_mfma_kernel<4, false> (MODE_UP1: first GEMM of the two-matrix expert + ReLU)") if mfma
                       else "ffn_gate_up_kernel<float>",
             "bound": "mfma" if mfma else "alu",
             "achieved": ach_up, "peak": peak, "unit": "TFLOP/s", "frac": ach_up / peak,
