@@ -786,6 +786,11 @@ int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, 
     hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH, true>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
   else
     hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DH1, true>), dim3(persistent_grid(c)), dim3(NT), 0, s, dh);
+  // weight gradients straight from dY, X, H and [dG|dU] (transpose reads from LDS), right
+  // after the kernel that wrote H and [dG|dU]; dX last, so that the caller's next kernel
+  // (the backward of dispatch) finds it in the last-level cache
+  st = launch_wgrad_tr(c, gated, dy, xp, c->d_H, c->d_dGU, counts, offsets, s);
+  if (st != MOE_OK) return st;
   // dX = [dG|dU] [W1; W3]  (one GEMM with contraction length 2f; f without U)
   GemmArgs dx = tiled_args(c, c->d_dGU, gw, c->d_order_down, nt_d, gw, d, dxp);
   dx.ldb = d;
@@ -793,8 +798,5 @@ int launch_ffn_bwd_mfma(moe_ctx* c, bool gated, const void* dy, const void* xp, 
   dx.split_ws = c->d_split_ws;
   hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN, true>), dim3(persistent_grid(c)), dim3(NT), 0, s, dx);
   hipLaunchKernelGGL(ffn_split_reduce_kernel, dim3((c->n_cu / 2) * 8), dim3(NT), 0, s, dx);
-  // weight gradients straight from dY, X, H and [dG|dU] (transpose reads from LDS)
-  st = launch_wgrad_tr(c, gated, dy, xp, c->d_H, c->d_dGU, counts, offsets, s);
-  if (st != MOE_OK) return st;
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
