@@ -4,29 +4,77 @@
 // Selection: one token is handled by a group of W lanes of a 64-wide wavefront (W = power
 // of two, >= min(E,64)), so that small expert counts pack several tokens into one
 // wavefront.  Each lane keeps ceil(E/W) logits in registers.  The k winners are found by k
-// rounds of "local best, then butterfly arg-max across the group"; the order relation is
-// total on finite floats: larger logit first, equal logits by lower expert id.  The same
+// rounds of "local best, then butterfly arg-max across the group" on 64-bit keys (logit,
+// id); the order relation is total on finite floats: larger logit first, equal logits by
+// lower expert id.  The same
 // device function serves moe_route_logits (logits in global memory) and the fused
 // moe_route kernel (logits in LDS), so both select identically from identical logits.
 #include "moe_internal.h"
 
 namespace {
 
-struct Cand {
-  float v;
-  int id;  // INT_MAX = no candidate
-};
+// A logit and its expert id as one 64-bit key whose unsigned order is the selection order:
+// high word = the float's bits mapped monotonically to unsigned (-0 is folded into +0 first,
+// the two compare equal), low word = INT_MAX - id, so that of two equal logits the lower id
+// has the larger key.  0 = no candidate (smaller than every key of a finite logit).
+typedef unsigned long long key_t;
 
-__device__ __forceinline__ bool better(const Cand& b, const Cand& a) {
-  // true when b should replace a
-  if (b.id == 0x7fffffff) return false;
-  if (a.id == 0x7fffffff) return true;
-  return (b.v > a.v) || (b.v == a.v && b.id < a.id);
+__device__ __forceinline__ key_t make_key(float v, int id) {
+  const uint32_t u = __float_as_uint(v + 0.f);
+  const uint32_t ord = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ((key_t)ord << 32) | (uint32_t)(0x7fffffff - id);
+}
+__device__ __forceinline__ float key_value(key_t k) {
+  const uint32_t ord = (uint32_t)(k >> 32);
+  return __uint_as_float((ord & 0x80000000u) ? (ord ^ 0x80000000u) : ~ord);
+}
+__device__ __forceinline__ int key_id(key_t k) { return 0x7fffffff - (int)(uint32_t)k; }
+
+// Exchange inside a group of W lanes for a reduction whose operator is commutative and
+// associative on the values at hand (max of keys; the sum's rounding is the same on every
+// lane of a pair, since both add the same two numbers).  Levels 1, 2 swap inside quads, level
+// 4 mirrors 8 lanes and level 8 mirrors 16 (after the lower levels every lane of a half holds
+// the half's result, so any lane of the other half will do): data-parallel-primitive moves
+// instead of LDS permutes; above that, LDS permutes.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
+template <int OFF>
+__device__ __forceinline__ uint32_t partner32(uint32_t x) {
+  if (OFF == 1) return dpp_mov<0xB1>(x);    // quad_perm [1,0,3,2]
+  if (OFF == 2) return dpp_mov<0x4E>(x);    // quad_perm [2,3,0,1]
+  if (OFF == 4) return dpp_mov<0x141>(x);   // row_half_mirror
+  if (OFF == 8) return dpp_mov<0x140>(x);   // row_mirror
+  return (uint32_t)__shfl_xor((int)x, OFF, 64);
+}
+template <int OFF>
+__device__ __forceinline__ key_t partner(key_t k) {
+  return ((key_t)partner32<OFF>((uint32_t)(k >> 32)) << 32) | partner32<OFF>((uint32_t)k);
+}
+template <int W, int OFF = 1>
+__device__ __forceinline__ key_t group_max(key_t best) {
+  if constexpr (OFF < W) {
+    const key_t o = partner<OFF>(best);
+    return group_max<W, OFF * 2>(o > best ? o : best);
+  } else {
+    return best;
+  }
+}
+template <int W, int OFF = 1>
+__device__ __forceinline__ float group_sum(float x) {
+  if constexpr (OFF < W) {
+    return group_sum<W, OFF * 2>(x + __uint_as_float(partner32<OFF>(__float_as_uint(x))));
+  } else {
+    return x;
+  }
 }
 
 // Selection and weights of token t, done by the W lanes [sub*W, sub*W+W) of the wavefront.
 // `row` points at the token's E logits (global memory or LDS); every lane of the wavefront
-// must call this together (dead groups pass live = false).
+// must call this together (dead groups pass live = false).  Round j finds the largest key
+// left (local scan, then a butterfly over the group); the winner is kept by lane j mod W of
+// the group (slot j / W), which later computes and writes that slot's weight.
 template <int W, int VPL>
 __device__ __forceinline__ void select_token(const float* row, bool live, int t, int E, int k,
                                              int renormalize, int32_t* __restrict__ topk_idx,
@@ -34,80 +82,62 @@ __device__ __forceinline__ void select_token(const float* row, bool live, int t,
   const int lane = threadIdx.x & 63;
   const int sub = lane / W;  // token slot inside the wavefront
   const int gl = lane % W;   // lane inside the group
+  constexpr int SLOTS = (MOE_MAX_TOPK + W - 1) / W;
 
   float v[VPL];
-  bool taken[VPL];
+  key_t key[VPL];
 #pragma unroll
   for (int i = 0; i < VPL; ++i) {
     const int e = gl + i * W;
     const bool ok = live && e < E;
     v[i] = ok ? row[e] : 0.f;
-    taken[i] = !ok;
+    key[i] = ok ? make_key(v[i], e) : 0;
   }
 
-  float sel_v[MOE_MAX_TOPK];
-  int sel_id[MOE_MAX_TOPK];
+  key_t mine[SLOTS];
 #pragma unroll
-  for (int j = 0; j < MOE_MAX_TOPK; ++j) {
-    sel_v[j] = 0.f;
-    sel_id[j] = 0;
-  }
+  for (int q = 0; q < SLOTS; ++q) mine[q] = 0;
+  key_t first = 0;   // the winner of round 0: the largest logit
 
 #pragma unroll 1
   for (int j = 0; j < k; ++j) {
-    Cand best{0.f, 0x7fffffff};
+    key_t best = 0;
 #pragma unroll
-    for (int i = 0; i < VPL; ++i) {
-      Cand c{v[i], taken[i] ? 0x7fffffff : gl + i * W};
-      if (better(c, best)) best = c;
-    }
+    for (int i = 0; i < VPL; ++i) best = key[i] > best ? key[i] : best;
+    best = group_max<W>(best);
 #pragma unroll
-    for (int off = W / 2; off >= 1; off >>= 1) {
-      Cand o;
-      o.v = __shfl_xor(best.v, off, 64);
-      o.id = __shfl_xor(best.id, off, 64);
-      if (better(o, best)) best = o;
-    }
-    // all lanes of the group take lane 0's answer (identical for finite inputs)
-    best.v = __shfl(best.v, sub * W, 64);
-    best.id = __shfl(best.id, sub * W, 64);
+    for (int i = 0; i < VPL; ++i) key[i] = key[i] == best ? 0 : key[i];
+    if (j == 0) first = best;
 #pragma unroll
-    for (int i = 0; i < VPL; ++i)
-      if (best.id == gl + i * W) taken[i] = true;
-#pragma unroll
-    for (int jj = 0; jj < MOE_MAX_TOPK; ++jj)
-      if (jj == j) {
-        sel_v[jj] = best.v;
-        sel_id[jj] = best.id;
-      }
+    for (int q = 0; q < SLOTS; ++q)
+      if (j == q * W + gl) mine[q] = best;
   }
 
   // weights: exp(l - max) over the selection, normalised over the selection or over all E
-  const float m = sel_v[0];
-  float den = 0.f;
+  const float m = key_value(first);
+  float part = 0.f;
   if (renormalize) {
 #pragma unroll
-    for (int j = 0; j < MOE_MAX_TOPK; ++j)
-      if (j < k) den += expf(sel_v[j] - m);
+    for (int q = 0; q < SLOTS; ++q)
+      if (q * W + gl < k) part += expf(key_value(mine[q]) - m);
   } else {
-    float part = 0.f;
 #pragma unroll
     for (int i = 0; i < VPL; ++i) {
       const int e = gl + i * W;
       if (live && e < E) part += expf(v[i] - m);
     }
-#pragma unroll
-    for (int off = W / 2; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
-    den = __shfl(part, sub * W, 64);
   }
-  if (live && gl == 0) {
-    const float inv = 1.f / den;
+  part = group_sum<W>(part);
+  const float inv = 1.f / part;
+  if (live) {
 #pragma unroll
-    for (int j = 0; j < MOE_MAX_TOPK; ++j)
+    for (int q = 0; q < SLOTS; ++q) {
+      const int j = q * W + gl;
       if (j < k) {
-        topk_idx[(size_t)t * k + j] = sel_id[j] == 0x7fffffff ? 0 : sel_id[j];
-        topk_w[(size_t)t * k + j] = expf(sel_v[j] - m) * inv;
+        topk_idx[(size_t)t * k + j] = mine[q] == 0 ? 0 : key_id(mine[q]);
+        topk_w[(size_t)t * k + j] = expf(key_value(mine[q]) - m) * inv;
       }
+    }
   }
 }
 
