@@ -215,6 +215,9 @@ def test_full_size_configs_sampled_rows(name):
     ("tiny", None, "auto", None), ("train", 512, "auto", None), ("train", 512, "valu", None),
     ("train", 700, "auto", dict(d=256, f=512, E=8, k=2, R=4, migrated=(5,))),      # ragged, small
     ("train", 300, "auto", dict(d=512, f=256, E=16, k=1, R=4, migrated=())),       # empty experts
+    # dX with a K-split tail whose middle part straddles the switch from W1 to W3
+    # (K = 2f = 24 k-steps in 3 parts of 8, the k-major operand changes at step 12)
+    ("train", 700, "auto", dict(d=512, f=768, E=4, k=2, R=2, migrated=(3,))),
 ])
 def test_backward_matches_oracle(name, T, path, shape):
     from gpu_common import DEV, TOL, moe, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
