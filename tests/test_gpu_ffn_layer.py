@@ -267,6 +267,46 @@ def test_backward_matches_oracle(name, T, path, shape):
     lay.close()
 
 
+@pytest.mark.parametrize("path", ["mfma", "valu"])
+def test_backward_unwanted_weight_gradients(path):
+    """NULL entries in the gradient tables: that gradient is not computed, every other output
+    is bit-identical to the call that asks for all of them (the kernels are deterministic)."""
+    from gpu_common import DEV, moe, say, to_device, layer_from_inputs
+    cfg = wl.scaled(wl.CONFIGS["train"], T=600, d=256, f=512, E=8, k=2, R=2, migrated=(5,),
+                    backward=True)
+    say(f"[bwd] unwanted gradients path={path} T={cfg.T} d={cfg.d} E={cfg.E} f={cfg.f}")
+    inp = wl.make_inputs(cfg)
+    lay = layer_from_inputs(inp)
+    if path == "valu":
+        moe.moe_set_ffn_path(lay.ctx, moe.MOE_FFN_VALU)
+    x = to_device(inp.x, cfg.dtype)
+    dout = to_device(inp.dOut, cfg.dtype)
+    fwd = lay.forward(x, save=True)
+    disp = fwd["disp"]
+    dy, _ = moe.moe_combine_bwd(lay.ctx, dout, fwd["y_packed"], disp.slot_to_row, fwd["topk_w"])
+    full = moe.moe_expert_ffn_bwd(lay.ctx, dy, disp.x_packed, fwd["G"], fwd["U"], disp.expert_counts,
+                                  disp.expert_offsets, lay.W1, lay.W3, lay.W2)
+    torch.cuda.synchronize()
+    res = [e for e in range(cfg.E) if lay.W1[e] is not None]
+    assert len(res) >= 3
+    mk = lambda ws: [None if w is None else torch.full(w.shape, 7.0, dtype=torch.float32, device=DEV)
+                     for w in ws]
+    dW1, dW3, dW2 = mk(lay.W1), mk(lay.W3), mk(lay.W2)
+    dW1[res[0]] = None                                   # one gradient of an expert
+    dW3[res[1]] = dW2[res[1]] = None                     # two of another
+    dW1[res[2]] = dW3[res[2]] = dW2[res[2]] = None       # none of a third
+    part = moe.moe_expert_ffn_bwd(lay.ctx, dy, disp.x_packed, fwd["G"], fwd["U"], disp.expert_counts,
+                                  disp.expert_offsets, lay.W1, lay.W3, lay.W2,
+                                  dW1=dW1, dW3=dW3, dW2=dW2)
+    torch.cuda.synchronize()
+    assert torch.equal(part[0].view(torch.int16), full[0].view(torch.int16))     # dx_packed
+    for got, want in zip(part[1:], full[1:]):
+        for e in res:
+            if got[e] is not None:
+                assert torch.equal(got[e], want[e]), e
+    lay.close()
+
+
 def test_train_config_full_size_backward_sampled():
     """The training configuration at full size with resident experts only (the launch shape
     bench.py times): sampled rows of dx_packed / dx and sampled rows of the weight gradients
