@@ -61,6 +61,9 @@ def test_dispatch_full_size_configs(name):
     (2049, 256, 16, 8, 64, "maxE"), (3000, 7, 1, 7, 136, "k1"), (1500, 8, 2, 2, 64, "allone"),
     (700, 12, 2, 3, 64, "hole"), (5000, 64, 6, 256, 64, "manyranks"),
     (1 << 20, 32, 4, 8, 8, "maxS"),          # T*k = 2^22 slots: the largest a context accepts
+    # 16 KB rows and 194 MiB of packed rows: the streaming variant of the scatter kernel, with
+    # rows longer than what a wavefront fetches ahead (8 KB)
+    (6200, 8, 2, 2, 4096, "stream_long_rows"),
 ])
 def test_dispatch_edge_cases(T, E, k, R, d, case):
     from gpu_common import say
