@@ -4,7 +4,7 @@ Follows the paper's Sec. 4.1 "Domain-Based Partition" (multilevel description, l
 renumbering, Algorithm 1 "Communication Topology Construction") and Sec. 3.3/3.4 (latency
 model and its closed-form solution).  Plain Python, no imports from the GPU package.
 
-Readings taken where the text is ambiguous (listed in the design doc):
+Readings taken where the text is ambiguous:
   * the renumbering is the mixed-radix expansion of the global rank with radices
     SF[0..L-1], most significant digit first, integer (floor) division;
   * Algorithm 1's D/E subscripts are the m/n of its inputs (m holds the data, n the expert);
