@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per launch of the dominant kernel (read + written), from the two rocprofv3
 # --pmc passes (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0, factors from the plain 512 MiB copy of
 # --copy-calibration) summarised in profiles/hotpath_mixtral_kernel_trace_and_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"mixtral": 6528.4e6 + 469.8e6}
+MEASURED_TRAFFIC_BYTES = {"mixtral": 6476.2e6 + 469.8e6}
 
 
 def cpu_baseline(cfg, inp, sample_tokens: int):
