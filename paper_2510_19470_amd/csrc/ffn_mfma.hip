@@ -44,7 +44,6 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
 constexpr int BM = MFMA_BM;       // token rows per block tile
-constexpr int BNW = 256;          // weight rows per block tile
 constexpr int BK = 64;            // k per stage
 constexpr int NT = 512;           // threads
 constexpr int STAGE_VEC = 2048;   // uint4 per operand per stage (256 rows x 8 chunks)
@@ -340,7 +339,6 @@ template <int MODE, bool BKM = false>
 __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
   // stage s: token rows at (2s) * STAGE_VEC, weight rows at (2s+1) * STAGE_VEC
   __shared__ uint4 lds[4 * STAGE_VEC];
-  constexpr bool GATED = MODE == MODE_UP;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = __builtin_amdgcn_readfirstlane(wave >> 2), wn = wave & 3;
@@ -708,7 +706,7 @@ static int run_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets, 
 static int persistent_grid(const moe_ctx* c) { return std::max(8, (c->n_cu / 8) * 8); }
 
 // Down-type GEMM (plain epilogue) with the K-split tail: the GEMM, then the sum of the parts.
-static void launch_down(moe_ctx* c, GemmArgs& a, int nt, hipStream_t s) {
+static void launch_down(moe_ctx* c, GemmArgs& a, hipStream_t s) {
   a.split_ws = c->d_split_ws;
   hipLaunchKernelGGL((ffn_mfma_kernel<MODE_DOWN>), dim3(persistent_grid(c)), dim3(NT), 0, s, a);
   hipLaunchKernelGGL(ffn_split_reduce_kernel, dim3((c->n_cu / 2) * 8), dim3(NT), 0, s, a);
@@ -735,7 +733,6 @@ int launch_ffn_mfma(moe_ctx* c, bool gated, const int32_t* counts, const int32_t
   const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
   const void* const* W3 = c->d_wtab + 1 * MOE_MAX_EXPERTS;
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
-  const int max_mt = c->max_mtiles[1];
   prof_mark(c, 0, s);
   int st = run_sched(c, counts, offsets, nt_up, nt_down, f / BK, W1, gated ? W3 : nullptr, W2,
                      nullptr, s);
@@ -750,7 +747,7 @@ int launch_ffn_mfma(moe_ctx* c, bool gated, const int32_t* counts, const int32_t
     hipLaunchKernelGGL((ffn_mfma_kernel<MODE_UP1>), dim3(persistent_grid(c)), dim3(NT), 0, s, up);
   prof_mark(c, 2, s);
   GemmArgs dn = tiled_args(c, c->d_H, f, c->d_order_down, nt_down, f, d, y_packed);
-  launch_down(c, dn, nt_down, s);
+  launch_down(c, dn, s);
   prof_mark(c, 3, s);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }

@@ -80,7 +80,6 @@ __device__ __forceinline__ void select_token(const float* row, bool live, int t,
                                              int renormalize, int32_t* __restrict__ topk_idx,
                                              float* __restrict__ topk_w) {
   const int lane = threadIdx.x & 63;
-  const int sub = lane / W;  // token slot inside the wavefront
   const int gl = lane % W;   // lane inside the group
   constexpr int SLOTS = (MOE_MAX_TOPK + W - 1) / W;
 
