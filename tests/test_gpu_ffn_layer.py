@@ -65,6 +65,7 @@ def test_ffn_tiny_fp32():
     (1031, 512, 8, 2, 384, 1.5, None),          # skewed: one expert > 256 rows, some < 32
     (300, 256, 16, 1, 256, 2.5, None),          # experts with zero tokens
     (515, 768, 6, 3, 640, 0.5, (0, 2, 5)),      # only some experts resident
+    (2000, 256, 256, 8, 256, 1.0, None),        # the largest expert count: many tiny segments
 ])
 def test_ffn_bf16_reduced_shapes(path, T, d, E, k, f, skew, present):
     from gpu_common import moe, say
@@ -218,6 +219,8 @@ def test_full_size_configs_sampled_rows(name):
     # dX with a K-split tail whose middle part straddles the switch from W1 to W3
     # (K = 2f = 24 k-steps in 3 parts of 8, the k-major operand changes at step 12)
     ("train", 700, "auto", dict(d=512, f=768, E=4, k=2, R=2, migrated=(3,))),
+    # many experts with a handful of rows each (and empty ones): 64 resident experts
+    ("train", 900, "auto", dict(d=256, f=256, E=128, k=8, R=2, migrated=())),
 ])
 def test_backward_matches_oracle(name, T, path, shape):
     from gpu_common import DEV, TOL, moe, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
