@@ -127,6 +127,29 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int32_t T
                  int32_t* expert_counts, int32_t* expert_offsets, int32_t* rank_counts,
                  int32_t* rank_offsets, void* stream);
 
+/* moe_dispatch for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  It needs no moe_ctx (creating
+ * one allocates) and calls no allocator: the per-chunk expert histograms, the per-expert
+ * totals and the segment positions live in a static device array inside the library, of
+ * MOE_NOALLOC_MAX_HIST + 1088 int32 (just over 1 MiB) per GPU, which every GPU the library
+ * runs on holds until the process ends.  The first call on a device (or moe_create on that
+ * device) looks its address up; make that call outside a capture.
+ *   cfg [host]: d, E, k, R, dtype are used as in moe_create; the other fields are ignored.
+ *   expert_dest_rank [dev][E]: the placement map on the DEVICE (read by a kernel: nothing is
+ *   copied from the host); an entry outside [0,R) is taken as the nearest valid rank.
+ *   All other arguments as in moe_dispatch; same outputs, bit for bit.
+ * Limits: T*k <= 2^22 and ceil(T*k / 1024) * E <= MOE_NOALLOC_MAX_HIST, else
+ * MOE_EUNSUPPORTED and nothing is launched; MOE_EUNSUPPORTED also for a device ordinal >= 64.
+ * Every call on a GPU uses that GPU's one array (each call clears what it needs at its start):
+ * calls that overlap in time on one GPU, on different streams or from different threads,
+ * race.  Calls on one stream are ordered and safe. */
+#define MOE_NOALLOC_MAX_HIST (256 * 1024)
+int moe_dispatch_noalloc(const moe_config* cfg, const int32_t* expert_dest_rank, const void* x,
+                         const int32_t* topk_idx, int32_t T, void* x_packed,
+                         int32_t* slot_to_row, int32_t* row_to_slot, int32_t* expert_counts,
+                         int32_t* expert_offsets, int32_t* rank_counts, int32_t* rank_offsets,
+                         void* stream);
+
 /* Grouped SwiGLU expert FFN (Sec. 2.1: experts are replicated FFNs; Sec. 3.1: the
  * experts of one GPU are computed one after another on their own tokens).  For
  * every expert e whose three table entries are non-NULL and every row r of its

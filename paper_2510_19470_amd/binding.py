@@ -14,6 +14,7 @@ import torch
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_FFN_AUTO, MOE_FFN_VALU = 0, 1
+MOE_NOALLOC_MAX_HIST = 256 * 1024   # include/moe.h
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libmoe_hip.so"
@@ -58,6 +59,8 @@ def load_library(build_if_missing: bool = True):
     lib.moe_route.argtypes = [P, P, P, P, c_int32, P, P, P, P]
     lib.moe_route_logits.argtypes = [P, P, c_int32, P, P, P]
     lib.moe_dispatch.argtypes = [P, P, P, c_int32, P, P, P, P, P, P, P, P]
+    lib.moe_dispatch_noalloc.argtypes = [POINTER(MoEConfigC), P, P, P, c_int32, P, P, P, P, P, P, P, P]
+    lib.moe_dispatch_noalloc.restype = c_int
     lib.moe_expert_ffn.argtypes = [P, P, P, P, P, P, P, c_int32, P, P, P, P]
     lib.moe_combine.argtypes = [P, P, P, P, c_int32, P, P]
     lib.moe_combine_bwd.argtypes = [P, P, P, P, P, c_int32, P, P, P]
@@ -222,6 +225,18 @@ def moe_dispatch(ctx, x, topk_idx, out: Optional[DispatchOut] = None, T: Optiona
         ctx.handle, _ptr(x), _ptr(topk_idx), T, _ptr(out.x_packed), _ptr(out.slot_to_row),
         _ptr(out.row_to_slot), _ptr(out.expert_counts), _ptr(out.expert_offsets),
         _ptr(out.rank_counts), _ptr(out.rank_offsets), _stream()), "moe_dispatch")
+    return out
+
+
+def moe_dispatch_noalloc(cfg: MoEConfigC, dest_rank_dev, x, topk_idx, out: DispatchOut, T=None):
+    """moe_dispatch without a context and without any allocation: every output is passed in
+    (`out`), the placement map is a device tensor [E] int32."""
+    T = topk_idx.shape[0] if T is None else T
+    _check(load_library().moe_dispatch_noalloc(
+        ctypes.byref(cfg), _ptr(dest_rank_dev), _ptr(x), _ptr(topk_idx), T, _ptr(out.x_packed),
+        _ptr(out.slot_to_row), _ptr(out.row_to_slot), _ptr(out.expert_counts),
+        _ptr(out.expert_offsets), _ptr(out.rank_counts), _ptr(out.rank_offsets), _stream()),
+        "moe_dispatch_noalloc")
     return out
 
 

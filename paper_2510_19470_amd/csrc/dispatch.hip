@@ -23,6 +23,8 @@
 // Nothing on the host changes from call to call, so a captured graph of the two launches can
 // be replayed.  (A ticket per scatter block with the last block clearing the totals doubled
 // the kernel's time: 4096 returning atomics on one address.)
+#include <mutex>
+
 #include "moe_internal.h"
 
 namespace {
@@ -239,6 +241,46 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
   }
 }
 
+// The two launches, on explicit workspace pointers (a context's, or the static scratch of
+// moe_dispatch_noalloc).  chunk_hist holds at least ceil(S / DISPATCH_CHUNK) * E integers.
+int launch_dispatch_on(const int32_t* seg_pos, const int32_t* dest_rank, int32_t* chunk_hist,
+                       int32_t* totals, int E, int R, int k, int d, int elem, const void* x,
+                       const int32_t* topk_idx, int T, void* x_packed, int32_t* slot_to_row,
+                       int32_t* row_to_slot, int32_t* expert_counts, int32_t* expert_offsets,
+                       int32_t* rank_counts, int32_t* rank_offsets, hipStream_t s) {
+  const int S = T * k;
+  const int n_chunks = (S + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK;
+  int ebits = 0;
+  while ((1 << ebits) < E) ++ebits;
+  hipLaunchKernelGGL(dispatch_count_kernel, dim3(n_chunks), dim3(COUNT_THREADS), 0, s, topk_idx, S,
+                     E, ebits, chunk_hist, totals, slot_to_row);
+  const int row_vec = x != nullptr ? d * elem / 16 : 0;
+  const int grid = (T + 3) / 4;
+  // stream past the cache when the packed rows do not fit it (256 MB on this part)
+  const bool stream = (size_t)S * row_vec * 16 > ((size_t)192 << 20);
+#define LAUNCH_SCATTER(KM)                                                                       \
+  if (stream) LAUNCH_SCATTER2(KM, true); else LAUNCH_SCATTER2(KM, false)
+#define LAUNCH_SCATTER2(KM, ST)                                                                  \
+  hipLaunchKernelGGL((dispatch_scatter_kernel<KM, ST>), dim3(grid), dim3(256), 0, s, (const u32x4*)x, \
+                     topk_idx, chunk_hist, totals, seg_pos, dest_rank, T, k, E, R, row_vec,        \
+                     slot_to_row, row_to_slot, (u32x4*)x_packed, expert_counts, expert_offsets,  \
+                     rank_counts, rank_offsets)
+  if (k <= 2) LAUNCH_SCATTER(2);
+  else if (k <= 4) LAUNCH_SCATTER(4);
+  else if (k <= 8) LAUNCH_SCATTER(8);
+  else LAUNCH_SCATTER(MOE_MAX_TOPK);
+#undef LAUNCH_SCATTER
+#undef LAUNCH_SCATTER2
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+}
+
+int launch_dispatch_empty(int E, int R, int32_t* expert_counts, int32_t* expert_offsets,
+                          int32_t* rank_counts, int32_t* rank_offsets, hipStream_t s) {
+  hipLaunchKernelGGL(dispatch_empty_kernel, dim3(1), dim3(256), 0, s, E, R, expert_counts,
+                     expert_offsets, rank_counts, rank_offsets);
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+}
+
 }  // namespace
 
 int launch_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int T, void* x_packed,
@@ -247,35 +289,119 @@ int launch_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int T, v
                     hipStream_t s) {
   const int E = c->cfg.E, R = c->cfg.R, k = c->cfg.k;
   const int S = T * k;
-  if (S == 0) {
-    hipLaunchKernelGGL(dispatch_empty_kernel, dim3(1), dim3(256), 0, s, E, R, expert_counts,
-                       expert_offsets, rank_counts, rank_offsets);
-    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
-  }
+  if (S == 0) return launch_dispatch_empty(E, R, expert_counts, expert_offsets, rank_counts, rank_offsets, s);
   const int n_chunks = (S + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK;
   if (n_chunks > c->n_chunks_max) return MOE_EINVAL;
-  int ebits = 0;
-  while ((1 << ebits) < E) ++ebits;
-  int32_t* totals = c->d_totals;   // [2][MOE_MAX_EXPERTS] totals, then the two call counters
-  hipLaunchKernelGGL(dispatch_count_kernel, dim3(n_chunks), dim3(COUNT_THREADS), 0, s, topk_idx, S,
-                     E, ebits, c->d_chunk_hist, totals, slot_to_row);
-  const int elem = c->cfg.dtype == MOE_BF16 ? 2 : 4;
-  const int row_vec = x != nullptr ? c->cfg.d * elem / 16 : 0;
-  const int grid = (T + 3) / 4;
-  // stream past the cache when the packed rows do not fit it (256 MB on this part)
-  const bool stream = (size_t)S * row_vec * 16 > ((size_t)192 << 20);
-#define LAUNCH_SCATTER(KM)                                                                       \
-  if (stream) LAUNCH_SCATTER2(KM, true); else LAUNCH_SCATTER2(KM, false)
-#define LAUNCH_SCATTER2(KM, ST)                                                                  \
-  hipLaunchKernelGGL((dispatch_scatter_kernel<KM, ST>), dim3(grid), dim3(256), 0, s, (const u32x4*)x, \
-                     topk_idx, c->d_chunk_hist, totals, c->d_seg_pos, c->d_dest_rank, T, k, E, \
-                     R, row_vec, slot_to_row, row_to_slot, (u32x4*)x_packed, expert_counts,      \
-                     expert_offsets, rank_counts, rank_offsets)
-  if (k <= 2) LAUNCH_SCATTER(2);
-  else if (k <= 4) LAUNCH_SCATTER(4);
-  else if (k <= 8) LAUNCH_SCATTER(8);
-  else LAUNCH_SCATTER(MOE_MAX_TOPK);
-#undef LAUNCH_SCATTER
-#undef LAUNCH_SCATTER2
-  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+  // d_totals: [2][MOE_MAX_EXPERTS] totals, then the two call counters
+  return launch_dispatch_on(c->d_seg_pos, c->d_dest_rank, c->d_chunk_hist, c->d_totals, E, R, k,
+                            c->cfg.d, c->elem, x, topk_idx, T, x_packed, slot_to_row, row_to_slot,
+                            expert_counts, expert_offsets, rank_counts, rank_offsets, s);
+}
+
+// ---- moe_dispatch_noalloc: the same two kernels on a workspace that is part of the loaded
+// code object instead of a context's allocations.
+namespace {
+
+constexpr int NA_TOTALS = 0;                                    // [2][256] totals + 2 counters
+constexpr int NA_SEG_POS = 576;                                 // [256]
+constexpr int NA_DEST = NA_SEG_POS + MOE_MAX_EXPERTS;           // [256] sanitised placement
+constexpr int NA_HIST = NA_DEST + MOE_MAX_EXPERTS;              // [chunks][E]
+constexpr int NA_INTS = NA_HIST + MOE_NOALLOC_MAX_HIST;
+
+// Every GPU the library runs on holds its own copy of this array until the process ends.
+static __device__ __align__(256) int32_t scratch[NA_INTS];
+
+// Device addresses of `scratch`, one per device, resolved on first use.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: host code uses these pointers.
+constexpr int NA_MAX_DEVICES = 64;
+int32_t* g_scratch_ptr[NA_MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+int scratch_for_current_device(int32_t** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return MOE_EHIP;
+  if (dev < 0 || dev >= NA_MAX_DEVICES) return MOE_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return MOE_EHIP;
+    }
+    g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return MOE_OK;
+}
+
+// One block: clears the totals and the call counters (the array keeps what the last call left),
+// copies the placement with every entry forced into [0, R), and ranks the experts by
+// (destination rank, id): seg_pos[e] = number of experts ordered before e.
+__global__ __launch_bounds__(MOE_MAX_EXPERTS) void dispatch_noalloc_prep_kernel(
+    const int32_t* __restrict__ dest_in, int E, int R, int32_t* __restrict__ ws) {
+  __shared__ int32_t dest[MOE_MAX_EXPERTS];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 2 * MOE_MAX_EXPERTS + 2; i += MOE_MAX_EXPERTS) ws[NA_TOTALS + i] = 0;
+  int mine = 0;
+  if (tid < E) {
+    mine = min(max(dest_in[tid], 0), R - 1);
+    dest[tid] = mine;
+    ws[NA_DEST + tid] = mine;
+  }
+  __syncthreads();
+  if (tid < E) {
+    int pos = 0;
+    for (int e = 0; e < E; ++e) pos += (dest[e] < mine || (dest[e] == mine && e < tid)) ? 1 : 0;
+    ws[NA_SEG_POS + tid] = pos;
+  }
+}
+
+}  // namespace
+
+// Resolves the static workspace of the current device (moe_create calls it so that the
+// address is known before a caller starts capturing).
+int dispatch_noalloc_init() {
+  int32_t* ws = nullptr;
+  return scratch_for_current_device(&ws);
+}
+
+extern "C" int moe_dispatch_noalloc(const moe_config* cfg, const int32_t* expert_dest_rank,
+                                    const void* x, const int32_t* topk_idx, int32_t T,
+                                    void* x_packed, int32_t* slot_to_row, int32_t* row_to_slot,
+                                    int32_t* expert_counts, int32_t* expert_offsets,
+                                    int32_t* rank_counts, int32_t* rank_offsets, void* stream) {
+  if (cfg == nullptr || expert_dest_rank == nullptr) return MOE_EINVAL;
+  if (cfg->dtype != MOE_F32 && cfg->dtype != MOE_BF16) return MOE_EINVAL;
+  if (cfg->E < 1 || cfg->E > MOE_MAX_EXPERTS) return MOE_EINVAL;
+  if (cfg->k < 1 || cfg->k > cfg->E || cfg->k > MOE_MAX_TOPK) return MOE_EINVAL;
+  if (cfg->R < 1 || cfg->R > MOE_MAX_RANKS) return MOE_EINVAL;
+  if (cfg->d < 8 || cfg->d % 8 != 0 || T < 0) return MOE_EINVAL;
+  if (expert_counts == nullptr || expert_offsets == nullptr || rank_counts == nullptr ||
+      rank_offsets == nullptr)
+    return MOE_EINVAL;
+  if ((x == nullptr) != (x_packed == nullptr)) return MOE_EINVAL;
+  if (T > 0 && (topk_idx == nullptr || slot_to_row == nullptr || row_to_slot == nullptr))
+    return MOE_EINVAL;
+  auto aligned16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+  if (!aligned16(x) || !aligned16(x_packed) || !aligned16(topk_idx) || !aligned16(slot_to_row) ||
+      !aligned16(row_to_slot))
+    return MOE_EINVAL;
+  const long long S = (long long)T * cfg->k;
+  if (S > (1ll << 22)) return MOE_EUNSUPPORTED;
+  const long long n_chunks = (S + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK;
+  if (n_chunks * cfg->E > MOE_NOALLOC_MAX_HIST) return MOE_EUNSUPPORTED;   // beyond the static workspace
+  hipStream_t s = (hipStream_t)stream;
+  if (S == 0)
+    return launch_dispatch_empty(cfg->E, cfg->R, expert_counts, expert_offsets, rank_counts,
+                                 rank_offsets, s);
+  int32_t* ws = nullptr;
+  const int st = scratch_for_current_device(&ws);
+  if (st != MOE_OK) return st;
+  hipLaunchKernelGGL(dispatch_noalloc_prep_kernel, dim3(1), dim3(MOE_MAX_EXPERTS), 0, s,
+                     expert_dest_rank, cfg->E, cfg->R, ws);
+  if (hipGetLastError() != hipSuccess) return MOE_EHIP;
+  return launch_dispatch_on(ws + NA_SEG_POS, ws + NA_DEST, ws + NA_HIST, ws + NA_TOTALS, cfg->E,
+                            cfg->R, cfg->k, cfg->d, cfg->dtype == MOE_BF16 ? 2 : 4, x, topk_idx,
+                            (int)T, x_packed, slot_to_row, row_to_slot, expert_counts,
+                            expert_offsets, rank_counts, rank_offsets, s);
 }

@@ -126,6 +126,7 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
     delete c;
     return MOE_EHIP;
   }
+  (void)dispatch_noalloc_init();   // so that moe_dispatch_noalloc need not do it under a capture
   const int E = cfg->E;
   c->n_chunks_max = std::max<int>(1, (int)((S + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK));
   c->max_mtiles[0] = (int)(S / GENERIC_BM) + E;

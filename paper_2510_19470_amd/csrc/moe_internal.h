@@ -109,6 +109,7 @@ int launch_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int T, v
                     int32_t* slot_to_row, int32_t* row_to_slot, int32_t* expert_counts,
                     int32_t* expert_offsets, int32_t* rank_counts, int32_t* rank_offsets,
                     hipStream_t s);
+int dispatch_noalloc_init();   // resolves the static dispatch workspace of the current device
 int launch_combine(const moe_ctx* c, const void* y_packed, const int32_t* slot_to_row,
                    const float* w, int T, void* out, hipStream_t s);
 int launch_combine_bwd(const moe_ctx* c, const void* dout, const void* y_packed,
