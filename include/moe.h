@@ -73,8 +73,14 @@ typedef struct {
 const char* moe_strerror(int status);
 
 /* Create / destroy a context.  moe_create validates cfg, allocates the device
- * workspace on the current device (O(T_max*k + E) integers) and installs the
- * default placement dest_rank[e] = e / ceil(E/R).  *out is NULL on error. */
+ * workspace on the current device and installs the default placement
+ * dest_rank[e] = e / ceil(E/R).  *out is NULL on error.  The workspace, with S = T_max*k:
+ * H [S, f] in dtype between the two GEMMs of the FFN (the largest part: 470 MB at T_max =
+ * 8192, k = 2, f = 14336, bf16); 64 MB of fp32 partial tiles for contraction-split GEMM
+ * tiles; the tile lists (32 bytes per 256-row block and column block); [T_max, E] fp32 logits;
+ * S/1024 * E + O(E) integers for the dispatch.  The first moe_expert_ffn_bwd adds [S, 2f] in
+ * dtype, the first moe_route_bwd that wants dWg ceil(T_max/128) * E * d floats.
+ * MOE_EUNSUPPORTED: S > 2^22, or S/64 + E > 65535 (grid limit of the vector-ALU kernels). */
 int moe_create(moe_ctx** out, const moe_config* cfg);
 int moe_destroy(moe_ctx* ctx);
 
@@ -92,7 +98,7 @@ int moe_set_placement(moe_ctx* ctx, const int32_t* expert_dest_rank);
 #define MOE_FFN_VALU 1
 int moe_set_ffn_path(moe_ctx* ctx, int path);
 
-/* Gating (Sec. 2.1: "a gate network as the router").
+/* Gating (Sec. 2.1 "Expert Parallelism": the gate network routes every token to K experts).
  *   logits[t,e] = sum_c x[t,c]*Wg[e,c] (+ bias[e]);  the k largest per token in
  *   descending order, equal logits ordered by ascending expert id;  weights =
  *   softmax over the selected k (renormalize) or over all E, computed in fp32.
@@ -179,14 +185,19 @@ int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* expert_cou
 int moe_combine(moe_ctx* ctx, const void* y_packed, const int32_t* slot_to_row,
                 const float* topk_w, int32_t T, void* out, void* stream);
 
-/* Backward of combine:  dy_packed[row(t,j)] = topk_w[t,j]*dout[t];
+/* Backward of combine (the chain rule of the second rearrangement of Sec. 2.1; the paper
+ * models the backward pass only as the forward plus a constant all-reduce term, Sec. 6):
+ *                       dy_packed[row(t,j)] = topk_w[t,j]*dout[t];
  *                       dtopk_w[t,j] = <dout[t], y_packed[row(t,j)]>.
  * dout [dev][T,d]; dy_packed [dev][S,d] out; dtopk_w [dev][T,k] fp32 out. */
 int moe_combine_bwd(moe_ctx* ctx, const void* dout, const void* y_packed,
                     const int32_t* slot_to_row, const float* topk_w, int32_t T,
                     void* dy_packed, float* dtopk_w, void* stream);
 
-/* Backward of the expert FFN for every expert with non-NULL table entries:
+/* Backward of the expert FFN (chain rule of the replicated FFN of Sec. 2.1; Sec. 3.1's GeMM
+ * cost model applies to these products as to the forward ones; the cross-rank reduction of
+ * the gradients of migrated experts, the all-reduce of Sec. 6, is not part of this call),
+ * for every expert with non-NULL table entries:
  *   dH = dY W2; dG = dH*u*silu'(g); dU = dH*silu(g); dX = dG W1 + dU W3;
  *   dW2 = dY^T H; dW1 = dG^T X; dW3 = dU^T X        (H = silu(G)*U recomputed)
  * dy_packed,x_packed [dev][S,d]; G_save,U_save [dev][S,f] from the forward;
@@ -205,7 +216,10 @@ int moe_expert_ffn_bwd(moe_ctx* ctx, const void* dy_packed, const void* x_packed
                        const void* const* W3, const void* const* W2, int32_t T, void* dx_packed,
                        float* const* dW1, float* const* dW3, float* const* dW2, void* stream);
 
-/* Backward of dispatch (transpose of the pack): dx[t] = sum_j dx_packed[slot_to_row[t*k+j]]. */
+/* Backward of dispatch (chain rule of the first rearrangement of Sec. 2.1, the transpose of
+ * the pack): dx[t] = sum_j dx_packed[slot_to_row[t*k+j]], j ascending, fp32.
+ * dx_packed [dev][S,d] must hold every row (rows of other ranks' experts are what came back
+ * from them); dx [dev][T,d] dtype out. */
 int moe_dispatch_bwd(moe_ctx* ctx, const void* dx_packed, const int32_t* slot_to_row, int32_t T,
                      void* dx, void* stream);
 
@@ -224,21 +238,39 @@ int moe_dispatch_bwd(moe_ctx* ctx, const void* dx_packed, const int32_t* slot_to
 /* Location renumbering (Sec. 4.1): loc[i] = floor(rank / prod_{j>i} SF[j]) mod SF[i]. */
 int moe_plan_location(int32_t rank, int32_t L, const int32_t* SF, int32_t* loc /*[L]*/);
 
-/* Algorithm 1 "Communication Topology Construction" for the pair (m, n) at one level:
+/* Communication topology of Sec. 4.1 (Algorithm 1) for the pair (m, n) at one level:
  * MOE_COMM_AG inside a domain (different offsets), MOE_COMM_A2A across domains (same
- * offset), else MOE_COMM_NONE; only pairs whose other coordinates agree communicate. */
+ * offset), else MOE_COMM_NONE.  Which pairs may talk at level l is where this library departs
+ * from the algorithm as printed.  MOE_PLAN_RULE_ALL_OTHER (what moe_plan_comm_type,
+ * moe_plan_comm_frequency and moe_plan_expert_dest_rank use): every OTHER coordinate of the
+ * two locations must agree, so a pair differs in exactly one level's worker number.
+ * MOE_PLAN_RULE_PRINTED: only the deeper coordinates must agree, as the listing and the
+ * sentence before it say; at the innermost level that pairs GPUs of different DCs.  With one
+ * level the two rules coincide (all that Table 7 covers).  On the paper's example of 4 DCs x
+ * 4 GPUs, SF = [4,4], S_ED = [2,4]: 64 AG + 16 A2A ordered pairs under ALL_OTHER, 208 AG +
+ * 16 A2A under PRINTED.  MOE_EINVAL for an unknown rule. */
+#define MOE_PLAN_RULE_ALL_OTHER 0
+#define MOE_PLAN_RULE_PRINTED 1
 int moe_plan_comm_type(int32_t m, int32_t n, int32_t level, int32_t L, const int32_t* SF,
                        const int32_t* S_ED, int32_t* type_out);
+int moe_plan_comm_type_rule(int32_t m, int32_t n, int32_t level, int32_t L, const int32_t* SF,
+                            const int32_t* S_ED, int32_t rule, int32_t* type_out);
 
 /* Communication frequency (Sec. 5.6, Table 7): number of GPU-to-GPU communications of
- * each type over all ordered pairs and levels.  G <= 4096. */
+ * each type over all ordered pairs and levels.  G <= 4096.  Closed forms: ALL_OTHER
+ * n_ag = G sum_l (S_ED[l]-1), n_a2a = G sum_l (SF[l]/S_ED[l]-1); PRINTED: term l times
+ * prod_{j<l} SF[j]. */
 int moe_plan_comm_frequency(int32_t L, const int32_t* SF, const int32_t* S_ED, int64_t* n_ag,
                             int64_t* n_a2a);
+int moe_plan_comm_frequency_rule(int32_t L, const int32_t* SF, const int32_t* S_ED, int32_t rule,
+                                 int64_t* n_ag, int64_t* n_a2a);
 
 /* The map moe_set_placement takes, for E experts spread evenly over the G GPUs (expert e at
  * home rank e / (E/G)): dest[e] = local_rank when the home is reachable by all-gather at
  * every level (the expert is resident), else the rank of the home's domain with the local
- * offsets (domain rule).  dest [E] out; E must be a multiple of G. */
+ * offsets (domain rule), level by level: the destination is one all-to-all hop away per level
+ * whose domains differ, and the home reaches it by all-gather hops only.
+ * dest [E] out; E must be a multiple of G. */
 int moe_plan_expert_dest_rank(int32_t local_rank, int32_t E, int32_t L, const int32_t* SF,
                               const int32_t* S_ED, int32_t* dest);
 

@@ -8,13 +8,25 @@ Readings taken where the text is ambiguous:
   * the renumbering is the mixed-radix expansion of the global rank with radices
     SF[0..L-1], most significant digit first, integer (floor) division;
   * Algorithm 1's D/E subscripts are the m/n of its inputs (m holds the data, n the expert);
-  * two GPUs talk at level l only if all their OTHER coordinates agree (the listing only
-    compares the deeper ones; with a single level both readings coincide);
+  * two GPUs talk at level l only if all their OTHER coordinates agree (rule "all_other",
+    the default).  The listing and the sentence above it compare only the deeper coordinates
+    (rule "printed": Loc[l+1:] equal); with a single level both coincide.  With several levels
+    the printed rule pairs, at the innermost level, GPUs of different DCs (nothing deeper is
+    left to compare), which contradicts a level being a set of workers joined by one
+    bandwidth; both rules are implemented and each is pinned by its own closed-form count:
+      all_other: n_AG = G sum_l (S_ED[l]-1),             n_A2A = G sum_l (SF[l]/S_ED[l]-1)
+      printed  : n_AG = G sum_l (S_ED[l]-1) prod_{j<l} SF[j],  n_A2A likewise
+    (a GPU's partners at level l differ from it in coordinate l -- S_ED-1 of them in its
+    domain, SF/S_ED-1 with its offset in the other domains -- and, under the printed rule, in
+    any of the shallower coordinates), and by the hop structure of the placement map: a
+    non-resident expert's destination is reached from the local GPU by one A2A hop per level
+    whose domains differ, and is joined to the expert's home by AG hops only;
   * the exact proportion of a domain size S on G GPUs is p = (G-S)/(G-1) (Definition 1); the
     paper's 0.5 / 0.75 for G = 8 are the rounded (G-S)/G.
-Pins: Table 7 (communication frequency, exact integers), Table 4 (case of each verification
-configuration), closed form vs brute-force minimisation of the model.  The numeric p* of
-Table 4 cannot be reproduced from the printed units: that value is "parity unpinned".
+Pins: Table 7 (communication frequency, exact integers), the multi-level counts and hop
+structure above, Table 4 (case of each verification configuration), closed form vs
+brute-force minimisation of the model.  The numeric p* of Table 4 cannot be reproduced from
+the printed units: that value is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -35,11 +47,19 @@ def location(m: int, SF: Sequence[int]) -> List[int]:
     return loc
 
 
-def comm_type(m: int, n: int, level: int, SF: Sequence[int], S_ED: Sequence[int]) -> int:
-    """Algorithm 1 for the GPU pair (m, n) at one level."""
+def comm_type(m: int, n: int, level: int, SF: Sequence[int], S_ED: Sequence[int],
+              rule: str = "all_other") -> int:
+    """Algorithm 1 for the GPU pair (m, n) at one level.  rule "all_other": every other
+    coordinate of the two locations must agree; rule "printed": only the deeper ones
+    (Loc[l+1:]), as the listing has it."""
     lm, ln = location(m, SF), location(n, SF)
-    others_equal = all(lm[i] == ln[i] for i in range(len(SF)) if i != level)
-    if not others_equal:
+    if rule == "all_other":
+        compared = [i for i in range(len(SF)) if i != level]
+    elif rule == "printed":
+        compared = list(range(level + 1, len(SF)))
+    else:
+        raise ValueError(rule)
+    if not all(lm[i] == ln[i] for i in compared):
         return NONE
     wm, wn = lm[level], ln[level]
     dm, om = wm // S_ED[level], wm % S_ED[level]
@@ -51,7 +71,7 @@ def comm_type(m: int, n: int, level: int, SF: Sequence[int], S_ED: Sequence[int]
     return NONE
 
 
-def comm_frequency(SF: Sequence[int], S_ED: Sequence[int]) -> Tuple[int, int]:
+def comm_frequency(SF: Sequence[int], S_ED: Sequence[int], rule: str = "all_other") -> Tuple[int, int]:
     """Number of GPU-to-GPU communications of each type over all ordered pairs and levels
     (the "frequency" of Sec. 5.6).  Returns (n_AG, n_A2A)."""
     G = 1
@@ -63,7 +83,7 @@ def comm_frequency(SF: Sequence[int], S_ED: Sequence[int]) -> Tuple[int, int]:
             if m == n:
                 continue
             for l in range(len(SF)):
-                t = comm_type(m, n, l, SF, S_ED)
+                t = comm_type(m, n, l, SF, S_ED, rule)
                 n_ag += t == AG
                 n_a2a += t == A2A
     return n_ag, n_a2a

@@ -77,10 +77,15 @@ def load_library(build_if_missing: bool = True):
     lib.moe_plan_comm_type.argtypes = [c_int32, c_int32, c_int32, c_int32, I32P, I32P, I32P]
     lib.moe_plan_comm_frequency.argtypes = [c_int32, I32P, I32P, POINTER(ctypes.c_int64),
                                             POINTER(ctypes.c_int64)]
+    lib.moe_plan_comm_type_rule.argtypes = [c_int32, c_int32, c_int32, c_int32, I32P, I32P, c_int32,
+                                            I32P]
+    lib.moe_plan_comm_frequency_rule.argtypes = [c_int32, I32P, I32P, c_int32,
+                                                 POINTER(ctypes.c_int64), POINTER(ctypes.c_int64)]
     lib.moe_plan_expert_dest_rank.argtypes = [c_int32, c_int32, c_int32, I32P, I32P, I32P]
     lib.moe_plan_model.argtypes = [ctypes.c_double] * 4 + [c_int32, POINTER(ctypes.c_double), I32P,
                                                            I32P]
     for name in ("moe_plan_location", "moe_plan_comm_type", "moe_plan_comm_frequency",
+                 "moe_plan_comm_type_rule", "moe_plan_comm_frequency_rule",
                  "moe_plan_expert_dest_rank", "moe_plan_model"):
         getattr(lib, name).restype = c_int
     lib.moe_route_bwd.argtypes = [P, P, P, P, P, P, P, c_int32, P, P, P, P, P]
@@ -393,18 +398,33 @@ def moe_plan_location(rank: int, SF: Sequence[int]) -> List[int]:
     return list(out)
 
 
-def moe_plan_comm_type(m: int, n: int, level: int, SF: Sequence[int], S_ED: Sequence[int]) -> int:
+MOE_PLAN_RULE_ALL_OTHER, MOE_PLAN_RULE_PRINTED = 0, 1
+
+
+def moe_plan_comm_type(m: int, n: int, level: int, SF: Sequence[int], S_ED: Sequence[int],
+                       rule: Optional[int] = None) -> int:
     t = c_int32(0)
-    _check(load_library().moe_plan_comm_type(m, n, level, len(SF), _i32(SF), _i32(S_ED),
-                                             ctypes.byref(t)), "moe_plan_comm_type")
+    if rule is None:
+        _check(load_library().moe_plan_comm_type(m, n, level, len(SF), _i32(SF), _i32(S_ED),
+                                                 ctypes.byref(t)), "moe_plan_comm_type")
+    else:
+        _check(load_library().moe_plan_comm_type_rule(m, n, level, len(SF), _i32(SF), _i32(S_ED),
+                                                      rule, ctypes.byref(t)),
+               "moe_plan_comm_type_rule")
     return int(t.value)
 
 
-def moe_plan_comm_frequency(SF: Sequence[int], S_ED: Sequence[int]):
+def moe_plan_comm_frequency(SF: Sequence[int], S_ED: Sequence[int], rule: Optional[int] = None):
     """Returns (n_AG, n_A2A)."""
     ag, a2a = ctypes.c_int64(0), ctypes.c_int64(0)
-    _check(load_library().moe_plan_comm_frequency(len(SF), _i32(SF), _i32(S_ED), ctypes.byref(ag),
-                                                  ctypes.byref(a2a)), "moe_plan_comm_frequency")
+    if rule is None:
+        _check(load_library().moe_plan_comm_frequency(len(SF), _i32(SF), _i32(S_ED),
+                                                      ctypes.byref(ag), ctypes.byref(a2a)),
+               "moe_plan_comm_frequency")
+    else:
+        _check(load_library().moe_plan_comm_frequency_rule(len(SF), _i32(SF), _i32(S_ED), rule,
+                                                           ctypes.byref(ag), ctypes.byref(a2a)),
+               "moe_plan_comm_frequency_rule")
     return int(ag.value), int(a2a.value)
 
 

@@ -552,9 +552,9 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
         for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
   };
 
-  // Every unit has an even number of k-steps (K and the padded expert segments are
-  // multiples of 128; the K-split keeps parts even).  KT == 0 happens only for the weight
-  // gradient of an expert without rows: nothing is loaded, zeros are stored.
+  // Every unit has an even number of k-steps (K is a multiple of 128 and the K-split keeps
+  // its parts even).  KT == 0 cannot come out of the schedule (K >= 128); should it ever,
+  // nothing is loaded and zeros are stored.
   if (cur.KT == 0) {
     zero_acc();
     epilogue(cur);

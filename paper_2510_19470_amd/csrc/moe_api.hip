@@ -46,8 +46,7 @@ int check_ctx_T(const moe_ctx* c, int32_t T) {
 }
 
 // Refresh the device copy of the pointer tables when the host tables changed.
-// rows: 0 W1, 1 W3, 2 W2, 3 dW1, 4 dW3, 5 dW2, 6 W2^T, 7 [W1^T|W3^T]; a NULL table leaves
-// its row as it is.
+// rows: 0 W1, 1 W3, 2 W2, 3 dW1, 4 dW3, 5 dW2; a NULL table leaves its row as it is.
 int sync_tables(moe_ctx* c, const void* const* const tabs[MOE_WTAB_ROWS], hipStream_t s) {
   const int E = c->cfg.E;
   bool changed = !c->wtab_valid;
@@ -112,6 +111,9 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
   const long long S = (long long)cfg->T_max * cfg->k;
   if (S > (1ll << 22)) return MOE_EUNSUPPORTED;                           // grid / int32 headroom
   if (S * std::max(cfg->d, cfg->f) > (1ll << 40)) return MOE_EUNSUPPORTED;
+  // the vector-ALU kernels put the 64-row blocks of the segments (and of the tokens) on grid.y
+  if (S / GENERIC_BM + cfg->E > 65535 || cfg->T_max / GENERIC_BM + 1 > 65535)
+    return MOE_EUNSUPPORTED;
 
   moe_ctx* c = new (std::nothrow) moe_ctx();
   if (c == nullptr) return MOE_ENOMEM;

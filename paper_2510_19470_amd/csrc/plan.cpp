@@ -29,8 +29,11 @@ void locate(int64_t m, int32_t L, const int32_t* SF, int32_t* loc) {
   }
 }
 
-int comm_type(const int32_t* lm, const int32_t* ln, int32_t level, int32_t L, const int32_t* S_ED) {
-  for (int l = 0; l < L; ++l)
+// rule MOE_PLAN_RULE_ALL_OTHER: every other coordinate must agree; MOE_PLAN_RULE_PRINTED: only
+// the deeper ones, as Algorithm 1 is printed
+int comm_type(const int32_t* lm, const int32_t* ln, int32_t level, int32_t L, const int32_t* S_ED,
+              int32_t rule = MOE_PLAN_RULE_ALL_OTHER) {
+  for (int l = rule == MOE_PLAN_RULE_PRINTED ? level + 1 : 0; l < L; ++l)
     if (l != level && lm[l] != ln[l]) return MOE_COMM_NONE;
   const int32_t s = S_ED[level];
   const int32_t dm = lm[level] / s, om = lm[level] % s;
@@ -58,23 +61,35 @@ int moe_plan_location(int32_t rank, int32_t L, const int32_t* SF, int32_t* loc) 
   return MOE_OK;
 }
 
-int moe_plan_comm_type(int32_t m, int32_t n, int32_t level, int32_t L, const int32_t* SF,
-                       const int32_t* S_ED, int32_t* type_out) {
+int moe_plan_comm_type_rule(int32_t m, int32_t n, int32_t level, int32_t L, const int32_t* SF,
+                            const int32_t* S_ED, int32_t rule, int32_t* type_out) {
   int64_t G;
   if (S_ED == nullptr || !valid_levels(L, SF, S_ED, &G) || type_out == nullptr) return MOE_EINVAL;
   if (m < 0 || m >= G || n < 0 || n >= G || level < 0 || level >= L) return MOE_EINVAL;
+  if (rule != MOE_PLAN_RULE_ALL_OTHER && rule != MOE_PLAN_RULE_PRINTED) return MOE_EINVAL;
   int32_t lm[MOE_PLAN_MAX_LEVELS], ln[MOE_PLAN_MAX_LEVELS];
   locate(m, L, SF, lm);
   locate(n, L, SF, ln);
-  *type_out = comm_type(lm, ln, level, L, S_ED);
+  *type_out = comm_type(lm, ln, level, L, S_ED, rule);
   return MOE_OK;
+}
+
+int moe_plan_comm_type(int32_t m, int32_t n, int32_t level, int32_t L, const int32_t* SF,
+                       const int32_t* S_ED, int32_t* type_out) {
+  return moe_plan_comm_type_rule(m, n, level, L, SF, S_ED, MOE_PLAN_RULE_ALL_OTHER, type_out);
 }
 
 int moe_plan_comm_frequency(int32_t L, const int32_t* SF, const int32_t* S_ED, int64_t* n_ag,
                             int64_t* n_a2a) {
+  return moe_plan_comm_frequency_rule(L, SF, S_ED, MOE_PLAN_RULE_ALL_OTHER, n_ag, n_a2a);
+}
+
+int moe_plan_comm_frequency_rule(int32_t L, const int32_t* SF, const int32_t* S_ED, int32_t rule,
+                                 int64_t* n_ag, int64_t* n_a2a) {
   int64_t G;
   if (S_ED == nullptr || !valid_levels(L, SF, S_ED, &G) || n_ag == nullptr || n_a2a == nullptr)
     return MOE_EINVAL;
+  if (rule != MOE_PLAN_RULE_ALL_OTHER && rule != MOE_PLAN_RULE_PRINTED) return MOE_EINVAL;
   if (G > 4096) return MOE_EUNSUPPORTED;  // all ordered pairs are enumerated
   int64_t ag = 0, a2a = 0;
   int32_t lm[MOE_PLAN_MAX_LEVELS], ln[MOE_PLAN_MAX_LEVELS];
@@ -84,7 +99,7 @@ int moe_plan_comm_frequency(int32_t L, const int32_t* SF, const int32_t* S_ED, i
       if (n == m) continue;
       locate(n, L, SF, ln);
       for (int l = 0; l < L; ++l) {
-        const int t = comm_type(lm, ln, l, L, S_ED);
+        const int t = comm_type(lm, ln, l, L, S_ED, rule);
         ag += t == MOE_COMM_AG;
         a2a += t == MOE_COMM_A2A;
       }

@@ -1,5 +1,7 @@
 // Weight gradients of the expert FFN on the matrix cores without transposed copies of the
-// activations (backward of the grouped FFN; paper Sec. 6: the backward mirrors the forward).
+// activations: the chain rule of the expert FFN of Sec. 2.1 taken with respect to its
+// weights (the paper itself only notes, in Sec. 6, that the backward pass adds a constant
+// all-reduce term to its model).
 //
 //   dW[e][m, n] = sum over the rows r of expert e of  P[r, m] * Q[r, n]      (fp32 out)
 //
@@ -63,7 +65,7 @@ __device__ __forceinline__ int tr_swz(int row) { return ((row & 3) << 2) ^ (((ro
 // lds_addr (wave-uniform, via M0) + lane * 16.
 __device__ __forceinline__ void dma16v(const void* src, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr)
-               : "memory");
+               : "memory", "m0");
 }
 
 __global__ __launch_bounds__(NT) void wgrad_tr_kernel(const WgradArgs p) {

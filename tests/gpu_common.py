@@ -31,6 +31,18 @@ def nerr(got, want):
     return float(np.max(np.abs(got - want)) / scale)
 
 
+def r7_rate(got, want, rel=2e-2):
+    """Fraction of the elements with |got - want| <= rel * |want| + rel * rms(want): the
+    elementwise report that goes with the normalised maximum (which says nothing about the
+    small elements)."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    if want.size == 0:
+        return 1.0
+    rms = float(np.sqrt(np.mean(want * want)))
+    return float(np.mean(np.abs(got - want) <= rel * np.abs(want) + rel * rms))
+
+
 def vals(a, dtype):
     """Stored array -> float64 values."""
     return wl.stored_to_f32(a, dtype).astype(np.float64)

@@ -155,61 +155,101 @@ def test_small_config_full_size():
     lay.close()
 
 
-def _sampled_rows_check(cfg, n_per_expert=3):
-    """Full-size launch; the oracle recomputes a few packed rows per resident expert (first,
-    last and one inside -- the last row sits in a ragged tail tile)."""
-    from gpu_common import TOL, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
+def _full_size_check(cfg):
+    """The configuration at full size with resident experts only -- the launch shape bench.py
+    times (K-split tail, cross-tile prefetch over many units per block, XCD tile order at its
+    real tile count).  Every element of y_packed over the compute region and of out against
+    the oracle; with cfg.backward also every element of dy_packed, dtopk_w, dx_packed, dx and
+    of the three weight gradients of every resident expert.  The forward oracle runs expert
+    by expert (rows and experts are independent) so that only one expert's float64 weights
+    are alive at a time."""
+    from gpu_common import (TOL, say, nerr, r7_rate, vals, to_device, to_host_f32, i32,
+                            layer_from_inputs)
+    tol = TOL[cfg.dtype]
     inp = wl.make_inputs(cfg, experts="resident")
     lay = layer_from_inputs(inp)
     x = to_device(inp.x, cfg.dtype)
-    fwd = lay.forward(x)
+    fwd = lay.forward(x, save=cfg.backward)
+    bwd = lay.backward(fwd, to_device(inp.dOut, cfg.dtype)) if cfg.backward else None
     torch.cuda.synchronize()
     idx = i32(fwd["topk_idx"])
-    cnt, off, rcnt, roff, s2r, r2s = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
-    d = fwd["disp"]
-    assert np.array_equal(i32(d.slot_to_row), s2r) and np.array_equal(i32(d.expert_counts), cnt)
-    yg = to_host_f32(fwd["y_packed"])
-    xv = wl.stored_to_f32(inp.x, cfg.dtype)
-    worst = 0.0
-    for e in wl.resident_experts(cfg):
-        n = int(cnt[e])
+    w = fwd["topk_w"].cpu().numpy().astype(np.float64)
+    want = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
+    cnt, off, rcnt, roff, s2r, r2s = want
+    dsp = fwd["disp"]
+    for g, wv in zip((dsp.expert_counts, dsp.expert_offsets, dsp.rank_counts, dsp.rank_offsets,
+                      dsp.slot_to_row, dsp.row_to_slot), want):
+        assert np.array_equal(i32(g), wv)
+    lo, hi = int(roff[cfg.local_rank]), int(roff[cfg.local_rank + 1])
+    res = wl.resident_experts(cfg)
+    assert hi - lo == sum(int(cnt[e]) for e in res)
+    say(f"    compute region rows [{lo},{hi}) of {cfg.S}, {len(res)} resident experts")
+    xp = vals(orc.pack_rows(inp.x, r2s, cfg.k), cfg.dtype)
+    yo = np.zeros((cfg.S, cfg.d))
+    Go = Uo = None
+    if cfg.backward:
+        Go, Uo = np.zeros((cfg.S, cfg.f)), np.zeros((cfg.S, cfg.f))
+    one = np.ones(1, np.int64)
+    for e in res:
+        a, n = int(off[e]), int(cnt[e])
         if n == 0:
             continue
-        rows = sorted({int(off[e]), int(off[e]) + n // 2, int(off[e]) + n - 1})[:n_per_expert]
-        xe = xv[r2s[rows] // cfg.k].astype(np.float64)
-        w1 = vals(inp.W1[e], cfg.dtype)
-        w3 = vals(inp.W3[e], cfg.dtype)
-        h = orc.silu(xe @ w1.T) * (xe @ w3.T)
-        del w1, w3
-        yo = h @ vals(inp.W2[e], cfg.dtype).T
-        err = nerr(yg[rows], yo)
-        worst = max(worst, err)
-        assert err <= TOL["bf16"], (e, rows, err)
-    say(f"    worst normalised max error over sampled rows {worst:.3e}")
-    # the combined output of tokens whose experts are all resident, by the definition
-    res = set(wl.resident_experts(cfg))
-    tok = [t for t in range(cfg.T) if all(int(e) in res for e in idx[t])][:4]
-    if tok:
-        w = fwd["topk_w"].cpu().numpy()
-        W1 = [None if a is None else vals(a, cfg.dtype) if i in set(idx[tok].ravel()) else None
-              for i, a in enumerate(inp.W1)]
-        out_o = np.zeros((len(tok), cfg.d))
-        for n_, t in enumerate(tok):
-            for j in range(cfg.k):
-                e = int(idx[t, j])
-                xe = xv[t:t + 1].astype(np.float64)
-                h = orc.silu(xe @ vals(inp.W1[e], cfg.dtype).T) * (xe @ vals(inp.W3[e], cfg.dtype).T)
-                out_o[n_] += w[t, j] * (h @ vals(inp.W2[e], cfg.dtype).T)[0]
-        assert nerr(to_host_f32(fwd["out"])[tok], out_o) <= TOL["bf16"]
+        y_e, g_e, u_e = orc.expert_ffn(xp[a:a + n], n * one, 0 * one, [vals(inp.W1[e], cfg.dtype)],
+                                       [vals(inp.W3[e], cfg.dtype)], [vals(inp.W2[e], cfg.dtype)])
+        yo[a:a + n] = y_e
+        if cfg.backward:
+            Go[a:a + n], Uo[a:a + n] = g_e, u_e
+        del y_e, g_e, u_e
+    yg = to_host_f32(fwd["y_packed"]).astype(np.float64)
+    errs = dict(y_packed=nerr(yg[lo:hi], yo[lo:hi]))
+    for e in res:    # per expert as well: a bad tile of a small expert must not hide
+        a, n = int(off[e]), int(cnt[e])
+        if n:
+            errs[f"y[{e}]"] = nerr(yg[a:a + n], yo[a:a + n])
+    assert np.all(yg[:lo] == 0) and np.all(yg[hi:] == 0)     # send-buffer rows are not touched
+    say(f"    y_packed: normalised max error {errs['y_packed']:.3e}, "
+        f"elementwise pass rate {r7_rate(yg[lo:hi], yo[lo:hi]):.6f}")
+    out_o = orc.combine(yo, s2r, w)
+    out_g = to_host_f32(fwd["out"])
+    errs["out"] = nerr(out_g, out_o)
+    say(f"    out: normalised max error {errs['out']:.3e}, elementwise pass rate "
+        f"{r7_rate(out_g, out_o):.6f}")
+    if cfg.backward:
+        errs["G"] = nerr(to_host_f32(fwd["G"])[lo:hi], Go[lo:hi])
+        errs["U"] = nerr(to_host_f32(fwd["U"])[lo:hi], Uo[lo:hi])
+        W1, W3, W2 = ([None if a is None else vals(a, cfg.dtype) for a in ws]
+                      for ws in (inp.W1, inp.W3, inp.W2))
+        dy_o, dw_o = orc.combine_bwd(vals(inp.dOut, cfg.dtype), yo, s2r, w)
+        dxp_o, dW1_o, dW3_o, dW2_o = orc.expert_ffn_bwd(dy_o, xp, Go, Uo, cnt, off, W1, W3, W2)
+        dx_o = orc.dispatch_bwd(dxp_o, s2r, cfg.T, cfg.k)
+        dxp_g = to_host_f32(bwd["dx_packed"]).astype(np.float64)
+        assert np.all(dxp_g[:lo] == 0) and np.all(dxp_g[hi:] == 0)
+        errs.update(dy=nerr(to_host_f32(bwd["dy_packed"]), dy_o),
+                    dw=nerr(bwd["dtopk_w"].cpu().numpy(), dw_o),
+                    dxp=nerr(dxp_g[lo:hi], dxp_o[lo:hi]),
+                    dx=nerr(to_host_f32(bwd["dx"]), dx_o))
+        say(f"    dx_packed: normalised max error {errs['dxp']:.3e}, elementwise pass rate "
+            f"{r7_rate(dxp_g[lo:hi], dxp_o[lo:hi]):.6f}")
+        for e in res:
+            for nm, got, wv in (("dW1", bwd["dW1"][e], dW1_o[e]), ("dW3", bwd["dW3"][e], dW3_o[e]),
+                                ("dW2", bwd["dW2"][e], dW2_o[e])):
+                errs[f"{nm}[{e}]"] = nerr(got.cpu().numpy(), wv)
+        worst = max((v, k_) for k_, v in errs.items() if k_.startswith("dW"))
+        say(f"    weight gradients, every element of {3 * len(res)} matrices: worst {worst[1]} "
+            f"{worst[0]:.3e}")
+    say("    " + ", ".join(f"{k_}={v:.2e}" for k_, v in errs.items() if "[" not in k_))
+    bad = {k_: v for k_, v in errs.items() if not v <= tol}
+    assert not bad, bad
     lay.close()
 
 
 @pytest.mark.parametrize("name", ["mixtral", "finegrained", "train"])
-def test_full_size_configs_sampled_rows(name):
+def test_full_size_configs_every_element(name):
     from gpu_common import say
     cfg = wl.CONFIGS[name]
-    say(f"[ffn] full size, sampled rows: config={name} T={cfg.T} d={cfg.d} E={cfg.E} f={cfg.f}")
-    _sampled_rows_check(cfg)
+    say(f"[ffn] full size, every element: config={name} T={cfg.T} d={cfg.d} E={cfg.E} "
+        f"k={cfg.k} f={cfg.f} backward={cfg.backward}")
+    _full_size_check(cfg)
 
 
 @pytest.mark.parametrize("name,T,path,shape", [
@@ -307,75 +347,6 @@ def test_backward_unwanted_weight_gradients(path):
         for e in res:
             if got[e] is not None:
                 assert torch.equal(got[e], want[e]), e
-    lay.close()
-
-
-def test_train_config_full_size_backward_sampled():
-    """The training configuration at full size with resident experts only (the launch shape
-    bench.py times): sampled rows of dx_packed / dx and sampled rows of the weight gradients
-    of one expert against the oracle (every quantity is row-local or one expert's sum)."""
-    from gpu_common import TOL, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
-    cfg = wl.CONFIGS["train"]
-    say(f"[bwd] train full size T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} f={cfg.f}")
-    inp = wl.make_inputs(cfg, experts="resident")
-    lay = layer_from_inputs(inp)
-    x = to_device(inp.x, cfg.dtype)
-    fwd = lay.forward(x, save=True)
-    bwd = lay.backward(fwd, to_device(inp.dOut, cfg.dtype))
-    torch.cuda.synchronize()
-    tol = TOL["bf16"]
-    idx = i32(fwd["topk_idx"])
-    w = fwd["topk_w"].cpu().numpy().astype(np.float64)
-    cnt, off, _, roff, s2r, r2s = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
-    xv = wl.stored_to_f32(inp.x, cfg.dtype).astype(np.float64)
-    dov = wl.stored_to_f32(inp.dOut, cfg.dtype).astype(np.float64)
-    res = wl.resident_experts(cfg)
-    dxp_g = to_host_f32(bwd["dx_packed"])
-    worst = 0.0
-    for e in res:
-        n = int(cnt[e])
-        rows = np.array(sorted({int(off[e]), int(off[e]) + n // 3, int(off[e]) + n - 1}))
-        slots = r2s[rows]
-        W1, W3, W2 = (vals(a[e], cfg.dtype) for a in (inp.W1, inp.W3, inp.W2))
-        xe = xv[slots // cfg.k]
-        g, u = xe @ W1.T, xe @ W3.T
-        sg = 1.0 / (1.0 + np.exp(-g))
-        dy = w.reshape(-1)[slots][:, None] * dov[slots // cfg.k]
-        dh = dy @ W2
-        dxp = (dh * u * sg * (1 + g * (1 - sg))) @ W1 + (dh * g * sg) @ W3
-        err = nerr(dxp_g[rows], dxp)
-        worst = max(worst, err)
-        assert err <= tol, (e, err)
-    say(f"    dx_packed sampled rows: worst normalised error {worst:.3e}")
-    # weight gradients of one resident expert: a few rows of each matrix, summed over all
-    # of the expert's tokens
-    e = res[-1]
-    n, lo = int(cnt[e]), int(off[e])
-    slots = r2s[lo:lo + n]
-    W1, W3, W2 = (vals(a[e], cfg.dtype) for a in (inp.W1, inp.W3, inp.W2))
-    xe = xv[slots // cfg.k]
-    g, u = xe @ W1.T, xe @ W3.T
-    sg = 1.0 / (1.0 + np.exp(-g))
-    h = g * sg * u
-    dy = w.reshape(-1)[slots][:, None] * dov[slots // cfg.k]
-    dh = dy @ W2
-    dg, du = dh * u * sg * (1 + g * (1 - sg)), dh * g * sg
-    pick = [0, 777, cfg.d - 1]
-    dW2 = bwd["dW2"][e].cpu().numpy().astype(np.float64)
-    dW1 = bwd["dW1"][e].cpu().numpy().astype(np.float64)
-    dW3 = bwd["dW3"][e].cpu().numpy().astype(np.float64)
-    scale = np.max(np.abs(dy.T[pick] @ h))
-    errs = dict(dW2=np.max(np.abs(dW2[pick] - dy.T[pick] @ h)) / scale,
-                dW1=np.max(np.abs(dW1[pick] - dg.T[pick] @ xe)) / np.max(np.abs(dg.T[pick] @ xe)),
-                dW3=np.max(np.abs(dW3[pick] - du.T[pick] @ xe)) / np.max(np.abs(du.T[pick] @ xe)))
-    say("    " + ", ".join(f"{k_}={v:.2e}" for k_, v in errs.items()))
-    assert all(v <= tol for v in errs.values()), errs
-    # dx of tokens whose experts are all resident: the sum of their k dx_packed rows
-    tok = [t for t in range(cfg.T) if all(int(a) in set(res) for a in idx[t])][:3]
-    if tok:
-        want = np.stack([sum(dxp_g[s2r[t * cfg.k + j]].astype(np.float64) for j in range(cfg.k))
-                         for t in tok])
-        assert nerr(to_host_f32(bwd["dx"])[tok], want) <= 2.0 ** -7
     lay.close()
 
 

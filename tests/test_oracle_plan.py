@@ -117,3 +117,95 @@ def test_best_domain_size_is_the_brute_force_argmin():
         assert all(lat_of(S) <= lat_of(s) + 1e-18 for s in range(1, G + 1) if G % s == 0)
     # AG-only configurations of Table 4 pick the full domain (p = 0)
     assert po.best_domain_size(3e6, 0.094e6, 16e9, 99e-6, 8) == 8
+
+
+# ------------------------------------------------------------------ several levels
+MULTI = [([4, 4], [2, 4]),          # Fig. "group-split" (b): 4 DCs x 4 GPUs
+         ([2, 3, 4], [1, 3, 2]),    # three levels, mixed radices
+         ([4, 8], [4, 2]), ([3, 2, 2], [3, 1, 2])]
+
+
+def _closed_form(SF, S_ED, rule):
+    G = int(np.prod(SF))
+    ag = a2a = 0
+    for l in range(len(SF)):
+        shallower = int(np.prod(SF[:l])) if rule == "printed" else 1
+        ag += (S_ED[l] - 1) * shallower
+        a2a += (SF[l] // S_ED[l] - 1) * shallower
+    return G * ag, G * a2a
+
+
+@pytest.mark.parametrize("SF,S_ED", MULTI)
+def test_multilevel_frequency_closed_forms(SF, S_ED):
+    """Counting argument, not a re-run of the rule: at level l a GPU's partners differ from it
+    in coordinate l only (S_ED-1 in its domain with another offset: AG; SF/S_ED-1 in the other
+    domains with its offset: A2A); the printed rule additionally lets every shallower
+    coordinate vary.  One level reduces both to Table 7's G(S-1), G(G/S-1)."""
+    for rule in ("all_other", "printed"):
+        assert po.comm_frequency(SF, S_ED, rule) == _closed_form(SF, S_ED, rule), rule
+    # per GPU and level as well (every GPU has the same number of partners)
+    G = int(np.prod(SF))
+    for m in range(G):
+        for l in range(len(SF)):
+            types = [po.comm_type(m, n, l, SF, S_ED) for n in range(G) if n != m]
+            assert types.count(po.AG) == S_ED[l] - 1
+            assert types.count(po.A2A) == SF[l] // S_ED[l] - 1
+
+
+def test_both_readings_on_the_papers_4x4_example():
+    SF, S_ED = [4, 4], [2, 4]
+    assert po.comm_frequency(SF, S_ED, "all_other") == (16 * (1 + 3), 16 * (1 + 0))
+    assert po.comm_frequency(SF, S_ED, "printed") == (16 * (1 + 3 * 4), 16 * (1 + 0))
+    # what the printed rule adds: GPU 0 of DC 0 gathers from GPU 1 of every DC at the GPU level
+    assert po.comm_type(0, 5, 1, SF, S_ED, "printed") == po.AG
+    assert po.comm_type(0, 5, 1, SF, S_ED, "all_other") == po.NONE
+    # the DC level is the same under both (nothing shallower exists)
+    for m in range(16):
+        for n in range(16):
+            assert po.comm_type(m, n, 0, SF, S_ED, "printed") == po.comm_type(m, n, 0, SF, S_ED)
+
+
+def _hops(src, dst, SF):
+    """Walk from src to dst changing one coordinate at a time, shallowest level first:
+    yields (level, from_rank, to_rank) for every coordinate that differs."""
+    cur = po.location(src, SF)
+    want = po.location(dst, SF)
+    for l in range(len(SF)):
+        if cur[l] != want[l]:
+            nxt = list(cur)
+            nxt[l] = want[l]
+            yield l, po.rank_of(cur, SF), po.rank_of(nxt, SF)
+            cur = nxt
+
+
+@pytest.mark.parametrize("SF,S_ED", MULTI)
+def test_multilevel_placement_hop_structure(SF, S_ED):
+    """Domain rule with several levels (Sec. 4.1): tokens of a non-resident expert leave the
+    local GPU by all-to-all hops only, one for every level at which the home lies in another
+    domain, and land on a GPU that shares a domain with the home at every level, i.e. one that
+    the home's expert reaches by all-gather hops only."""
+    G = int(np.prod(SF))
+    L = len(SF)
+    for per in (1, 2):
+        E = G * per
+        for m in range(G):
+            dest = po.expert_dest_rank(m, E, SF, S_ED)
+            lm = po.location(m, SF)
+            resident = 0
+            for e in range(E):
+                h = e // per
+                lh = po.location(h, SF)
+                other_domain = [l for l in range(L) if lm[l] // S_ED[l] != lh[l] // S_ED[l]]
+                hops = list(_hops(m, dest[e], SF))
+                assert [l for l, _, _ in hops] == other_domain
+                for l, a, b in hops:
+                    assert po.comm_type(a, b, l, SF, S_ED) == po.A2A
+                for l, a, b in _hops(dest[e], h, SF):
+                    assert po.comm_type(a, b, l, SF, S_ED) == po.AG
+                resident += dest[e] == m
+                assert (dest[e] == m) == (not other_domain)
+            # the resident experts are those of the GPUs sharing every domain with m
+            assert resident == per * int(np.prod(S_ED))
+            # remote destinations: one per combination of other domains
+            n_dest = int(np.prod([SF[l] // S_ED[l] for l in range(L)]))
+            assert len(set(dest)) == n_dest

@@ -75,3 +75,53 @@ def test_plan_feeds_the_benchmark_style_placement():
     dest = moe.moe_plan_expert_dest_rank(0, 16, [4], [2])
     assert [e for e in range(16) if dest[e] == 0] == list(range(8))
     assert set(dest[8:]) == {2}                              # other domain, offset 0
+
+
+MULTI = [([4, 4], [2, 4]), ([2, 3, 4], [1, 3, 2]), ([4, 8], [4, 2])]
+
+
+@pytest.mark.parametrize("SF,S_ED", MULTI)
+def test_multilevel_rules_counts_and_hops_through_the_abi(SF, S_ED):
+    """Several levels through the C ABI: both rules against the oracle and against their
+    closed-form counts; the hop structure of the placement map (A2A hops from the local GPU to
+    the destination, one per level whose domains differ; AG hops from there to the home)."""
+    ALL, PRN = moe.binding.MOE_PLAN_RULE_ALL_OTHER, moe.binding.MOE_PLAN_RULE_PRINTED
+    G, L = int(np.prod(SF)), len(SF)
+    for rule, name in ((ALL, "all_other"), (PRN, "printed")):
+        shallower = [int(np.prod(SF[:l])) if rule == PRN else 1 for l in range(L)]
+        want = (G * sum((S_ED[l] - 1) * shallower[l] for l in range(L)),
+                G * sum((SF[l] // S_ED[l] - 1) * shallower[l] for l in range(L)))
+        assert moe.moe_plan_comm_frequency(SF, S_ED, rule) == want == po.comm_frequency(SF, S_ED, name)
+        for m in range(G):
+            for n in range(G):
+                for l in range(L):
+                    assert moe.moe_plan_comm_type(m, n, l, SF, S_ED, rule) == \
+                        po.comm_type(m, n, l, SF, S_ED, name)
+    assert moe.moe_plan_comm_frequency(SF, S_ED) == moe.moe_plan_comm_frequency(SF, S_ED, ALL)
+
+    def hops(src, dst):
+        cur, want = moe.moe_plan_location(src, SF), moe.moe_plan_location(dst, SF)
+        for l in range(L):
+            if cur[l] != want[l]:
+                nxt = list(cur)
+                nxt[l] = want[l]
+                yield l, po.rank_of(cur, SF), po.rank_of(nxt, SF)
+                cur = nxt
+
+    E = 2 * G
+    for m in range(G):
+        dest = moe.moe_plan_expert_dest_rank(m, E, SF, S_ED)
+        lm = moe.moe_plan_location(m, SF)
+        for e in range(E):
+            h = e // 2
+            lh = moe.moe_plan_location(h, SF)
+            other = [l for l in range(L) if lm[l] // S_ED[l] != lh[l] // S_ED[l]]
+            hs = list(hops(m, dest[e]))
+            assert [l for l, _, _ in hs] == other
+            assert all(moe.moe_plan_comm_type(a, b, l, SF, S_ED) == moe.binding.MOE_COMM_A2A
+                       for l, a, b in hs)
+            assert all(moe.moe_plan_comm_type(a, b, l, SF, S_ED) == moe.binding.MOE_COMM_AG
+                       for l, a, b in hops(dest[e], h))
+        assert sum(d == m for d in dest) == 2 * int(np.prod(S_ED))
+    with pytest.raises(moe.MoEError):
+        moe.moe_plan_comm_type(0, 1, 0, SF, S_ED, 7)
