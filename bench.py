@@ -29,10 +29,89 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3       # fp32 vector
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per launch of the dominant kernel (read + written), from the two rocprofv3
-# --pmc passes (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0, factors from the plain 512 MiB copy of
-# --copy-calibration) summarised in profiles/hotpath_mixtral_kernel_trace_and_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"mixtral": 6476.2e6 + 469.8e6}
+
+
+def traffic_from_profile(workload: str, kernel: str):
+    """HBM-side bytes per launch of `kernel` (read + written) as the committed rocprofv3
+    summary of this workload has them: profiles/hotpath_<workload>_kernel_trace_and_traffic.md,
+    table of the two --pmc passes (FETCH_SIZE and WRITE_SIZE, already scaled by the factors of
+    the plain 512 MiB copy: columns 'read MB' and 'written MB').  None when there is no such
+    file or row."""
+    path = os.path.join(ROOT, "profiles", f"hotpath_{workload}_kernel_trace_and_traffic.md")
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return None
+    in_table = False
+    for line in lines:
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 5 and cells[1].startswith("FETCH_SIZE") and cells[2].startswith("read MB"):
+            in_table = True
+            continue
+        if in_table and len(cells) >= 5 and cells[0].startswith(kernel):
+            try:
+                return (float(cells[2]) + float(cells[4])) * 1e6
+            except ValueError:
+                continue
+    return None
+
+
+def measure_ceilings(n_loc: int, d: int, f: int, x_packed, W1_0):
+    """What the part gives, measured in this process by committed code: a plain copy kernel
+    with dispatch's 1:2 read:write mix (and 1:1), the bare MFMA issue loop (zero and varied
+    operands), and the library's dense GEMM of the gate/up shape on the workload's data (one
+    torch.matmul of [n_loc, d] x [d, 2f]; not grouped, no SwiGLU)."""
+    import torch
+    import paper_2510_19470_amd as moe
+    dev = x_packed.device
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps):
+        fn()
+        fn()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+    out = {}
+    n = 512 << 20
+    src = torch.empty(n, dtype=torch.uint8, device=dev)
+    src.fill_(1)
+    dst = torch.empty(2 * n, dtype=torch.uint8, device=dev)
+    t = timed(lambda: moe.moe_measure_copy(src, dst, 2), 10)
+    out["copy_read1_write2_gbs"] = 3 * n / (t * 1e-3) / 1e9
+    t = timed(lambda: moe.moe_measure_copy(src, dst, 1), 10)
+    out["copy_read1_write1_gbs"] = 2 * n / (t * 1e-3) / 1e9
+    out["copy_bytes_read"] = n
+    del src, dst
+    blocks = torch.cuda.get_device_properties(dev).multi_processor_count
+    sink = torch.empty(blocks * 512, dtype=torch.float32, device=dev)
+    for rnd, key in ((False, "mfma_issue_zero_operands_tflops"), (True, "mfma_issue_varied_operands_tflops")):
+        fl = [0.0]
+
+        def go():
+            fl[0] = moe.moe_measure_mfma(sink, blocks, 4000, rnd)
+        t = timed(go, 5)
+        out[key] = fl[0] / (t * 1e-3) / 1e12
+    del sink
+    # library GEMM of the gate/up shape on the workload data: x_packed rows of the compute
+    # region against one expert's W1 repeated to 2f rows
+    A = x_packed[:n_loc]
+    reps_w = max(1, (2 * f + W1_0.shape[0] - 1) // W1_0.shape[0])
+    Wt = W1_0.repeat(reps_w, 1)[:2 * f].contiguous().t()       # [2f, d] in memory, as the experts are
+    C = torch.empty((n_loc, 2 * f), dtype=A.dtype, device=dev)
+    t = timed(lambda: torch.matmul(A, Wt, out=C), 5)
+    out["library_gemm_tflops"] = 2.0 * n_loc * d * 2 * f / (t * 1e-3) / 1e12
+    out["library_gemm_shape"] = [int(n_loc), int(d), int(2 * f)]
+    del C, Wt
+    out["note"] = ("measured in this run: moe_measure_copy (512 MiB read, one 16-byte piece per "
+                   "thread), moe_measure_mfma (8 wavefronts per compute unit issuing "
+                   "v_mfma_f32_32x32x16_bf16 from registers), torch.matmul bf16 on the workload's "
+                   "packed tokens")
+    return out
 
 
 def cpu_baseline(cfg, inp, sample_tokens: int):
@@ -66,8 +145,11 @@ def cpu_baseline(cfg, inp, sample_tokens: int):
     except Exception:
         cores = os.cpu_count() or 1
     return {"value": T / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {T} of {cfg.T} tokens of '{cfg.name}', float64 NumPy oracle, "
-                      f"resident experts only, {dt:.2f} s"}
+            "host_cpu_count": os.cpu_count(),
+            "sample": f"first {T} of {cfg.T} tokens of '{cfg.name}', NumPy oracle computing in "
+                      f"float64 on the stored bf16 values (upcast exactly through float32), "
+                      f"resident experts only, {dt:.2f} s; cores = BLAS threads used, "
+                      f"host_cpu_count = os.cpu_count()"}
 
 
 def sr_compression_bench(ctx, rows: int, cols: int, cr: int = 50, reps: int = 10):
@@ -126,6 +208,9 @@ def main() -> int:
     ap.add_argument("--cpu-sample-tokens", type=int, default=0,
                     help="tokens of the oracle baseline sample (0 = sized for ~10-30 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the other configurations (small, finegrained, train) and the "
+                         "measured ceilings that the default run adds outside the timed region")
     ap.add_argument("--no-sr", action="store_true",
                     help="skip the shared/residual compression measurement (one expert matrix, "
                          "outside the timed steps)")
@@ -159,7 +244,33 @@ def main() -> int:
         return 3
     if args.table3_sweep:
         return table3_sweep(args)
-    print(json.dumps(run(wl.CONFIGS[args.config], args)))
+    rec = run(wl.CONFIGS[args.config], args)
+    if not args.no_others and args.config == "mixtral":
+        # the other large configurations, outside the headline's timed region: fewer steps,
+        # no oracle, no compression measurement
+        import copy
+        a2 = copy.copy(args)
+        a2.no_sr = a2.no_cpu_baseline = True
+        a2.graph, a2.chunks, a2.copy_calibration = False, 0, False
+        a2.steps, a2.warmup = min(args.steps, 10), max(args.warmup, 5)
+        rec["other_configs"] = {}
+        for name in ("small", "finegrained", "train"):
+            r = run(wl.CONFIGS[name], a2, with_ceilings=False)
+            rec["other_configs"][name] = {
+                "workload": r["config"]["workload"], "n_loc_rows": r["config"]["n_loc_rows"],
+                "steps": a2.steps, "warmup": a2.warmup,
+                "ms_per_step": r["ms_per_step"], "tokens_per_s": r["value"],
+                "gate_up_frac_of_peak": r["grouped_gemm"]["frac_of_peak_gate_up"],
+                "down_frac_of_peak": r["grouped_gemm"]["frac_of_peak_down"],
+                "ffn_call_frac_of_peak": r["grouped_gemm"]["frac_of_peak_whole_call"],
+                "dispatch_frac_of_hbm_peak": r["hbm"]["dispatch_frac"],
+                "combine_frac_of_hbm_peak": r["hbm"]["combine_frac"],
+                "call_ms": r["call_ms"],
+                **({"ffn_bwd_frac_of_peak": r["grouped_gemm"]["frac_of_peak_bwd_call"],
+                    "ffn_fwd_bwd_frac_of_peak": r["grouped_gemm"]["frac_of_peak_fwd_bwd"]}
+                   if "frac_of_peak_bwd_call" in r["grouped_gemm"] else {}),
+            }
+    print(json.dumps(rec))
     return 0
 
 
@@ -195,7 +306,7 @@ def table3_sweep(args) -> int:
     return 0
 
 
-def run(cfg, args) -> dict:
+def run(cfg, args, with_ceilings: bool = True) -> dict:
     """One workload: warm-up, the timed steps, the breakdown pass and the extras; returns the
     record that main() prints."""
     import torch
@@ -364,7 +475,7 @@ def run(cfg, args) -> dict:
                       else "ffn_gate_up_kernel<float>",
             "bound": "mfma" if mfma else "alu",
             "achieved": ach_up, "peak": peak, "unit": "TFLOP/s", "frac": ach_up / peak,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if mfma else None,
+            "traffic": traffic_from_profile(cfg.name, "ffn_mfma_kernel<0") if mfma and cfg.gated else None,
             "algorithmic_bytes": (n_up * n_res * d * f + n_loc * d + n_loc * f) * elem,
             "avg_launch_ms": ffn_ms[1], "flops_per_launch": flops_up, "launches": n_rec,
         },
@@ -391,6 +502,27 @@ def run(cfg, args) -> dict:
                               "note": "steps of the breakdown pass (an event after every call)"},
         "input_generation_s": t_gen,
     }
+    if cfg.backward:
+        # 12 n_loc d f for the data and weight gradients (8 for the two-matrix expert)
+        flops_bwd = (2.0 * (n_up + 1) * 2) * n_loc * d * f
+        t_b = call_ms["expert_ffn_bwd"] * 1e-3
+        g = rec["grouped_gemm"]
+        g["bwd_call_tflops"] = flops_bwd / t_b / 1e12
+        g["frac_of_peak_bwd_call"] = g["bwd_call_tflops"] / peak
+        g["frac_of_peak_fwd_bwd"] = ((flops_up + flops_down + flops_bwd) /
+                                     (t_b + call_ms["expert_ffn"] * 1e-3) / 1e12 / peak)
+    if mfma and with_ceilings and not args.no_others:
+        w0 = next(w for w in lay.W1 if w is not None)
+        c = measure_ceilings(n_loc, d, f, disp.x_packed, w0)
+        rec["ceilings"] = c
+        rec["roofline"]["frac_of_measured"] = ach_up / c["mfma_issue_varied_operands_tflops"]
+        rec["roofline"]["measured_ceiling"] = ("mfma_issue_varied_operands_tflops: the bare MFMA "
+                                               "issue loop on varied bf16 operands, this run")
+        rec["roofline"]["vs_library_gemm"] = ach_up / c["library_gemm_tflops"]
+        rec["hbm"]["dispatch_frac_of_measured_copy"] = \
+            rec["hbm"]["dispatch_gbs"] / c["copy_read1_write2_gbs"]
+        rec["hbm"]["combine_frac_of_measured_copy"] = \
+            rec["hbm"]["combine_gbs"] / c["copy_read1_write1_gbs"]
     if mfma and not args.no_sr:
         rec["sr_compression"] = sr_compression_bench(lay.ctx, f, d)
     if cfg.backward:

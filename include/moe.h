@@ -379,6 +379,20 @@ int moe_profile_ffn(moe_ctx* ctx, int32_t n_calls);
 int moe_profile_ffn_launches(moe_ctx* ctx, int32_t mask);
 int moe_profile_ffn_read(moe_ctx* ctx, float* ms, int32_t* n_recorded);
 
+/* Measured ceilings for the roofline report (Sec. 3.1 prices a GeMM with the compute
+ * efficiency C of the device: these two kernels measure what the device gives a kernel that
+ * does nothing but copy, or nothing but issue matrix instructions).
+ * moe_measure_copy: one launch that reads `bytes` (a multiple of 16) from src once and writes
+ * them to `fanout` (1..16) consecutive copies in dst (fanout * bytes, no overlap with src);
+ * both [dev], 16-byte aligned.
+ * moe_measure_mfma: one launch of `blocks` blocks of 8 wavefronts that each issue
+ * iters * 32 v_mfma_f32_32x32x16_bf16 from registers (operands zero, or varied bf16 values
+ * with random_operands != 0); sink [dev][blocks * 512] floats receives a checksum;
+ * *flops_out [host] (may be NULL) = the floating-point operations of the launch. */
+int moe_measure_copy(const void* src, void* dst, int64_t bytes, int32_t fanout, void* stream);
+int moe_measure_mfma(float* sink, int32_t blocks, int32_t iters, int32_t random_operands,
+                     double* flops_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

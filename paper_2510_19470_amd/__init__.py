@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     moe_route_logits, moe_set_ffn_path, moe_set_placement, moe_strerror, moe_profile_ffn, moe_profile_ffn_launches,
     moe_profile_ffn_read, moe_plan_location, moe_plan_comm_type, moe_plan_comm_frequency,
     moe_plan_expert_dest_rank, moe_plan_model, moe_sr_keep_count, moe_sr_encode, moe_sr_decode,
-    moe_route_bwd, MoEPipeline,
+    moe_route_bwd, MoEPipeline, moe_measure_copy, moe_measure_mfma,
 )

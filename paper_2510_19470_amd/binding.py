@@ -97,6 +97,10 @@ def load_library(build_if_missing: bool = True):
     lib.moe_sr_decode.argtypes = [P, P, P, P, I64, I64, P, P]
     lib.moe_sr_encode.restype = c_int
     lib.moe_sr_decode.restype = c_int
+    lib.moe_measure_copy.argtypes = [P, P, I64, c_int32, P]
+    lib.moe_measure_mfma.argtypes = [P, c_int32, c_int32, c_int32, POINTER(ctypes.c_double), P]
+    lib.moe_measure_copy.restype = c_int
+    lib.moe_measure_mfma.restype = c_int
     lib.moe_profile_ffn.argtypes = [P, c_int32]
     lib.moe_profile_ffn_read.argtypes = [P, POINTER(c_float), POINTER(c_int32)]
     for name in ("moe_create", "moe_destroy", "moe_set_placement", "moe_set_ffn_path", "moe_route",
@@ -354,6 +358,20 @@ def moe_profile_ffn_read(ctx):
     _check(load_library().moe_profile_ffn_read(ctx.handle, ms, ctypes.byref(n)),
            "moe_profile_ffn_read")
     return [float(v) for v in ms], int(n.value)
+
+
+def moe_measure_copy(src, dst, fanout: int = 1) -> None:
+    """One launch: reads src (uint8 tensor) once, writes `fanout` copies into dst."""
+    _check(load_library().moe_measure_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(),
+                                           fanout, _stream()), "moe_measure_copy")
+
+
+def moe_measure_mfma(sink, blocks: int, iters: int, random_operands: bool) -> float:
+    """One launch of the bare MFMA issue loop; returns its floating-point operation count."""
+    fl = ctypes.c_double(0.0)
+    _check(load_library().moe_measure_mfma(_ptr(sink), blocks, iters, int(random_operands),
+                                           ctypes.byref(fl), _stream()), "moe_measure_mfma")
+    return float(fl.value)
 
 
 # ------------------------------------------------------------------ shared/residual compression

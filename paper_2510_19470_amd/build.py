@@ -13,7 +13,8 @@ BUILD_DIR = os.path.join(ROOT, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libmoe_hip.so")
 
 SOURCES = ["moe_api.hip", "route.hip", "dispatch.hip", "combine.hip", "gemm_generic.hip",
-           "ffn_mfma.hip", "wgrad_tr.hip", "sr.hip", "route_bwd.hip", "pipeline.hip", "plan.cpp"]
+           "ffn_mfma.hip", "wgrad_tr.hip", "sr.hip", "route_bwd.hip", "pipeline.hip", "ceilings.hip",
+           "plan.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
