@@ -364,7 +364,7 @@ def run(cfg, args, with_ceilings: bool = True) -> dict:
         mark(0)
         moe.moe_route(lay.ctx, x, lay.Wg, lay.bias, topk_idx=topk_idx, topk_w=topk_w)
         mark(1)
-        moe.moe_dispatch(lay.ctx, x, topk_idx, out=disp)
+        moe.moe_dispatch_routed(lay.ctx, x, topk_idx, out=disp)   # the routing moe_route just wrote
         mark(2)
         moe.moe_expert_ffn(lay.ctx, disp.x_packed, disp.expert_counts, disp.expert_offsets,
                            lay.W1, lay.W3, lay.W2, y_packed=y_packed, G_save=G, U_save=U)
@@ -438,7 +438,7 @@ def run(cfg, args, with_ceilings: bool = True) -> dict:
         b_.record()
         torch.cuda.synchronize()
         return a.elapsed_time(b_) / reps
-    warm_dispatch_ms = warm(lambda: moe.moe_dispatch(lay.ctx, x, topk_idx, out=disp))
+    warm_dispatch_ms = warm(lambda: moe.moe_dispatch_routed(lay.ctx, x, topk_idx, out=disp))
     warm_combine_ms = warm(lambda: moe.moe_combine(lay.ctx, y_packed, disp.slot_to_row, topk_w, out=out))
     n_loc = int(disp.rank_counts[cfg.local_rank].item())
     n_res = len(wl.resident_experts(cfg))

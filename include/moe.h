@@ -80,7 +80,7 @@ const char* moe_strerror(int status);
  * tiles; the tile lists (32 bytes per 256-row block and column block); [T_max, E] fp32 logits;
  * S/1024 * E + O(E) integers for the dispatch.  The first moe_expert_ffn_bwd adds [S, 2f] in
  * dtype, the first moe_route_bwd that wants dWg ceil(T_max/128) * E * d floats.
- * MOE_EUNSUPPORTED: S > 2^22, or S/64 + E > 65535 (grid limit of the vector-ALU kernels). */
+ * MOE_EUNSUPPORTED: S > 2^22. */
 int moe_create(moe_ctx** out, const moe_config* cfg);
 int moe_destroy(moe_ctx* ctx);
 
@@ -132,6 +132,23 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int32_t T
                  void* x_packed, int32_t* slot_to_row, int32_t* row_to_slot,
                  int32_t* expert_counts, int32_t* expert_offsets, int32_t* rank_counts,
                  int32_t* rank_offsets, void* stream);
+
+/* moe_dispatch of the routing that the last moe_route on this context wrote: same arguments,
+ * same outputs bit for bit, one kernel launch instead of two.  moe_route's gate kernel holds
+ * the k expert ids of its tokens anyway and leaves the counting step of the dispatch in the
+ * context (per 32 tokens: the rank of every slot among the slots of its expert, the expert
+ * histogram; sums of 16 such histograms); this call turns them into offsets and rows inside
+ * the kernel that copies the token rows.
+ * CONTRACT: topk_idx must be the array the last moe_route on ctx wrote, UNCHANGED since (same
+ * pointer, same T); a caller that edits the routing in between (drops or remaps experts) must
+ * call moe_dispatch.  When the context holds no such side products -- pointer or T differ,
+ * the gate of this configuration is not the fused kernel (fp32 storage, d % 256 != 0),
+ * T_max > 131072, or moe_route ran on a stream that was being captured -- the call is
+ * moe_dispatch.  May be repeated; the side products stay valid until the next moe_route. */
+int moe_dispatch_routed(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int32_t T,
+                        void* x_packed, int32_t* slot_to_row, int32_t* row_to_slot,
+                        int32_t* expert_counts, int32_t* expert_offsets, int32_t* rank_counts,
+                        int32_t* rank_offsets, void* stream);
 
 /* moe_dispatch for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  It needs no moe_ctx (creating

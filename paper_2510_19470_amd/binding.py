@@ -59,6 +59,8 @@ def load_library(build_if_missing: bool = True):
     lib.moe_route.argtypes = [P, P, P, P, c_int32, P, P, P, P]
     lib.moe_route_logits.argtypes = [P, P, c_int32, P, P, P]
     lib.moe_dispatch.argtypes = [P, P, P, c_int32, P, P, P, P, P, P, P, P]
+    lib.moe_dispatch_routed.argtypes = [P, P, P, c_int32, P, P, P, P, P, P, P, P]
+    lib.moe_dispatch_routed.restype = c_int
     lib.moe_dispatch_noalloc.argtypes = [POINTER(MoEConfigC), P, P, P, c_int32, P, P, P, P, P, P, P, P]
     lib.moe_dispatch_noalloc.restype = c_int
     lib.moe_expert_ffn.argtypes = [P, P, P, P, P, P, P, c_int32, P, P, P, P]
@@ -215,8 +217,10 @@ class DispatchOut:
                  "rank_counts", "rank_offsets")
 
 
-def moe_dispatch(ctx, x, topk_idx, out: Optional[DispatchOut] = None, T: Optional[int] = None):
-    """x may be None (maps only).  `out` re-uses previously allocated outputs."""
+def moe_dispatch(ctx, x, topk_idx, out: Optional[DispatchOut] = None, T: Optional[int] = None,
+                 routed: bool = False):
+    """x may be None (maps only).  `out` re-uses previously allocated outputs.  routed: call
+    moe_dispatch_routed (topk_idx is what the last moe_route on ctx wrote, unchanged)."""
     k, E, R, d = ctx.cfg.k, ctx.cfg.E, ctx.cfg.R, ctx.cfg.d
     T = topk_idx.shape[0] if T is None else T
     dev = topk_idx.device
@@ -230,11 +234,17 @@ def moe_dispatch(ctx, x, topk_idx, out: Optional[DispatchOut] = None, T: Optiona
         out.expert_offsets = torch.empty(E, **i32)
         out.rank_counts = torch.empty(R, **i32)
         out.rank_offsets = torch.empty(R + 1, **i32)
-    _check(load_library().moe_dispatch(
-        ctx.handle, _ptr(x), _ptr(topk_idx), T, _ptr(out.x_packed), _ptr(out.slot_to_row),
-        _ptr(out.row_to_slot), _ptr(out.expert_counts), _ptr(out.expert_offsets),
-        _ptr(out.rank_counts), _ptr(out.rank_offsets), _stream()), "moe_dispatch")
+    lib = load_library()
+    fn = lib.moe_dispatch_routed if routed else lib.moe_dispatch
+    _check(fn(ctx.handle, _ptr(x), _ptr(topk_idx), T, _ptr(out.x_packed), _ptr(out.slot_to_row),
+              _ptr(out.row_to_slot), _ptr(out.expert_counts), _ptr(out.expert_offsets),
+              _ptr(out.rank_counts), _ptr(out.rank_offsets), _stream()),
+           "moe_dispatch_routed" if routed else "moe_dispatch")
     return out
+
+
+def moe_dispatch_routed(ctx, x, topk_idx, out: Optional[DispatchOut] = None, T: Optional[int] = None):
+    return moe_dispatch(ctx, x, topk_idx, out, T, routed=True)
 
 
 def moe_dispatch_noalloc(cfg: MoEConfigC, dest_rank_dev, x, topk_idx, out: DispatchOut, T=None):

@@ -29,17 +29,6 @@
 
 namespace {
 
-// Lanes of the wavefront holding the same value as this lane (value in [0,256) or -1 for
-// "none"): one ballot per bit of the value, no loop over the distinct values.
-__device__ __forceinline__ unsigned long long match_same(int e, int nbits) {
-  unsigned long long m = __ballot(e >= 0);
-  for (int b = 0; b < nbits; ++b) {
-    const unsigned long long bal = __ballot((e >> b) & 1);
-    m &= ((e >> b) & 1) ? bal : ~bal;
-  }
-  return m;
-}
-
 constexpr int COUNT_THREADS = DISPATCH_CHUNK;  // one slot per thread, 16 wavefronts
 constexpr int COUNT_WAVES = COUNT_THREADS / 64;
 
@@ -116,7 +105,13 @@ constexpr int SCATTER_PF = 8;   // 16-byte pieces of its token row a lane fetche
 // those loads are in flight, and writes the packed rows with non-temporal stores, one burst
 // of writes that bypasses the cache; measured 104 -> 89 us on a 403 MB packed buffer, but
 // 42 -> 58 us on one of 134 MB, which the cache absorbs when it is written normally.
-template <int K_MAX, bool STREAM>
+// ROUTED: the counting was done by the fused gate kernel of moe_route.  chunk_hist is then the
+// histogram of every gate block of 32 tokens, totals2 the sums of every super-block of 16 gate
+// blocks (n_super of them), slot_rank the rank of a slot inside its gate block.  The 4 tokens
+// of a block lie in one gate block, so the number of slots of every expert before that gate
+// block is summed once per block, in LDS: the super-blocks before its own (their sum over all
+// super-blocks is the expert's total) plus the gate blocks before it in its own super-block.
+template <int K_MAX, bool STREAM, bool ROUTED>
 __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     const u32x4* __restrict__ x, const int32_t* __restrict__ topk_idx,
     const int32_t* __restrict__ chunk_hist, int32_t* __restrict__ totals2,
@@ -124,22 +119,25 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     int E, int R, int row_vec, int32_t* __restrict__ slot_to_row,
     int32_t* __restrict__ row_to_slot, u32x4* __restrict__ x_packed,
     int32_t* __restrict__ expert_counts, int32_t* __restrict__ expert_offsets,
-    int32_t* __restrict__ rank_counts, int32_t* __restrict__ rank_offsets) {
+    int32_t* __restrict__ rank_counts, int32_t* __restrict__ rank_offsets,
+    const int32_t* __restrict__ slot_rank, int n_super) {
   __shared__ int32_t scan[MOE_MAX_EXPERTS + 1];   // by position in segment order
   __shared__ int32_t offs[MOE_MAX_EXPERTS];       // expert id -> first row of its segment
   __shared__ int32_t rcnt[MOE_MAX_RANKS + 1];
+  __shared__ int32_t tot_s[MOE_MAX_EXPERTS];      // ROUTED: slots per expert
+  __shared__ int32_t pre_s[MOE_MAX_EXPERTS];      // ROUTED: ... in the gate blocks before this one
   const int tid = threadIdx.x, lane = tid & 63;
   const int t = (int)((blockIdx.x * (size_t)blockDim.x + tid) >> 6);   // wave-uniform
   const bool live = t < T;
   // ---- small loads nothing else depends on, then the token row
   int32_t* ctr = totals2 + 2 * MOE_MAX_EXPERTS;
-  const int call = ctr[1] - 1;   // the number the count kernel of this call saw
+  const int call = ROUTED ? 0 : ctr[1] - 1;   // the number the count kernel of this call saw
   int pos = 0;
   if (tid < E) pos = seg_pos[tid];
   int e = -1, rk = -1;
   if (live && lane < k) {
     e = topk_idx[t * k + lane];
-    rk = slot_to_row[t * k + lane];
+    rk = ROUTED ? slot_rank[t * k + lane] : slot_to_row[t * k + lane];
   }
   const u32x4* src = x + (size_t)(live ? t : 0) * row_vec;
   u32x4 pre[SCATTER_PF];
@@ -150,8 +148,34 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
       pre[u] = __builtin_nontemporal_load(src + lane + 64 * u);
   }
   int mine = 0;
-  if (tid < E) mine = totals2[(call & 1) * MOE_MAX_EXPERTS + tid];
-  if (blockIdx.x == 0 && tid == 0) ctr[0] = call + 1;
+  if (ROUTED) {
+    // thread = (expert tid % EP, part tid / EP): the parts share the rows to be summed
+    int EP = 1;
+    while (EP < E) EP <<= 1;
+    const int ex = tid & (EP - 1), part = tid / EP, parts = 256 / EP;
+    const int gb = (int)(blockIdx.x * 4) / GATE_BLOCK_TOKENS, sc = gb / RT_SUPER;
+    tot_s[tid] = 0;
+    pre_s[tid] = 0;
+    int tot = 0, pre = 0;
+    if (ex < E) {
+      for (int r = part; r < n_super; r += parts) {
+        const int v = totals2[(size_t)r * E + ex];
+        tot += v;
+        pre += r < sc ? v : 0;
+      }
+      for (int g = sc * RT_SUPER + part; g < gb; g += parts) pre += chunk_hist[(size_t)g * E + ex];
+    }
+    lds_barrier();
+    if (ex < E) {
+      if (tot != 0) atomicAdd(&tot_s[ex], tot);   // integer adds in LDS: order does not matter
+      if (pre != 0) atomicAdd(&pre_s[ex], pre);
+    }
+    lds_barrier();
+    if (tid < E) mine = tot_s[tid];
+  } else {
+    if (tid < E) mine = totals2[(call & 1) * MOE_MAX_EXPERTS + tid];
+    if (blockIdx.x == 0 && tid == 0) ctr[0] = call + 1;
+  }
   // ---- expert offsets: inclusive scan of the totals taken in segment order
   if (tid < E) scan[pos + 1] = mine;
   if (tid == 0) scan[0] = 0;
@@ -189,16 +213,21 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
   if ((unsigned)e >= (unsigned)E || rk < 0) e = -1;
   // the histograms of the chunks before the slot's own, summed for all k slots at once:
   // lane = (slot j, part p) with 64 / K_MAX parts per slot
-  constexpr int PARTS = 64 / K_MAX;
-  const int j_of = lane / PARTS, p_of = lane % PARTS;
-  const int ej = __shfl(e, j_of, 64);
-  const int cj = (t * k + j_of) / DISPATCH_CHUNK;
-  int part = 0;
-  if (j_of < k && ej >= 0)
-    for (int c = p_of; c < cj; c += PARTS) part += chunk_hist[(size_t)c * E + ej];
+  int base;
+  if (ROUTED) {
+    base = e >= 0 ? pre_s[e] : 0;
+  } else {
+    constexpr int PARTS = 64 / K_MAX;
+    const int j_of = lane / PARTS, p_of = lane % PARTS;
+    const int ej = __shfl(e, j_of, 64);
+    const int cj = (t * k + j_of) / DISPATCH_CHUNK;
+    int part = 0;
+    if (j_of < k && ej >= 0)
+      for (int c = p_of; c < cj; c += PARTS) part += chunk_hist[(size_t)c * E + ej];
 #pragma unroll
-  for (int off = PARTS / 2; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
-  const int base = __shfl(part, lane * PARTS, 64);   // lane j < K_MAX: the sum of slot j
+    for (int off = PARTS / 2; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
+    base = __shfl(part, lane * PARTS, 64);   // lane j < K_MAX: the sum of slot j
+  }
   int row = -1;
   if (lane < k) {
     const int s = t * k + lane;
@@ -261,10 +290,10 @@ int launch_dispatch_on(const int32_t* seg_pos, const int32_t* dest_rank, int32_t
 #define LAUNCH_SCATTER(KM)                                                                       \
   if (stream) LAUNCH_SCATTER2(KM, true); else LAUNCH_SCATTER2(KM, false)
 #define LAUNCH_SCATTER2(KM, ST)                                                                  \
-  hipLaunchKernelGGL((dispatch_scatter_kernel<KM, ST>), dim3(grid), dim3(256), 0, s, (const u32x4*)x, \
-                     topk_idx, chunk_hist, totals, seg_pos, dest_rank, T, k, E, R, row_vec,        \
-                     slot_to_row, row_to_slot, (u32x4*)x_packed, expert_counts, expert_offsets,  \
-                     rank_counts, rank_offsets)
+  hipLaunchKernelGGL((dispatch_scatter_kernel<KM, ST, false>), dim3(grid), dim3(256), 0, s,       \
+                     (const u32x4*)x, topk_idx, chunk_hist, totals, seg_pos, dest_rank, T, k, E, \
+                     R, row_vec, slot_to_row, row_to_slot, (u32x4*)x_packed, expert_counts,      \
+                     expert_offsets, rank_counts, rank_offsets, nullptr, 0)
   if (k <= 2) LAUNCH_SCATTER(2);
   else if (k <= 4) LAUNCH_SCATTER(4);
   else if (k <= 8) LAUNCH_SCATTER(8);
@@ -282,6 +311,37 @@ int launch_dispatch_empty(int E, int R, int32_t* expert_counts, int32_t* expert_
 }
 
 }  // namespace
+
+// One launch: the scatter kernel on the side products that the fused gate kernel of the last
+// moe_route left in the context (the caller has checked that they describe topk_idx and T).
+int launch_dispatch_routed(moe_ctx* c, const void* x, const int32_t* topk_idx, int T,
+                           void* x_packed, int32_t* slot_to_row, int32_t* row_to_slot,
+                           int32_t* expert_counts, int32_t* expert_offsets, int32_t* rank_counts,
+                           int32_t* rank_offsets, hipStream_t s) {
+  const int E = c->cfg.E, R = c->cfg.R, k = c->cfg.k;
+  const int S = T * k;
+  const int row_vec = x != nullptr ? c->cfg.d * c->elem / 16 : 0;
+  const int grid = (T + 3) / 4;
+  const int n_blk = (T + GATE_BLOCK_TOKENS - 1) / GATE_BLOCK_TOKENS;
+  const int n_super = (n_blk + RT_SUPER - 1) / RT_SUPER;
+  int32_t* super = c->d_rt_super + (size_t)c->rt_parity * c->rt_super_max * E;
+  const bool stream = (size_t)S * row_vec * 16 > ((size_t)192 << 20);
+#define LAUNCH_ROUTED(KM)                                                                        \
+  if (stream) LAUNCH_ROUTED2(KM, true); else LAUNCH_ROUTED2(KM, false)
+#define LAUNCH_ROUTED2(KM, ST)                                                                   \
+  hipLaunchKernelGGL((dispatch_scatter_kernel<KM, ST, true>), dim3(grid), dim3(256), 0, s,        \
+                     (const u32x4*)x, topk_idx, c->d_rt_hist, super, c->d_seg_pos,               \
+                     c->d_dest_rank, T, k, E, R, row_vec, slot_to_row, row_to_slot,              \
+                     (u32x4*)x_packed, expert_counts, expert_offsets, rank_counts, rank_offsets, \
+                     c->d_rt_rank, n_super)
+  if (k <= 2) LAUNCH_ROUTED(2);
+  else if (k <= 4) LAUNCH_ROUTED(4);
+  else if (k <= 8) LAUNCH_ROUTED(8);
+  else LAUNCH_ROUTED(MOE_MAX_TOPK);
+#undef LAUNCH_ROUTED
+#undef LAUNCH_ROUTED2
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+}
 
 int launch_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int T, void* x_packed,
                     int32_t* slot_to_row, int32_t* row_to_slot, int32_t* expert_counts,

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(const T* __restrict__ 
                                                           const float* __restrict__ bias, int Tn,
                                                           int E, int d, float* __restrict__ logits) {
   __shared__ Smem sm;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;   // row blocks on grid.x (no 65535 limit)
   float acc[4][4];
   zero(acc);
   tile_mac(acc, x + (size_t)m0 * d, d, 1, Tn - m0, Wg + (size_t)n0 * d, 1, d, E - n0, d, sm);
@@ -98,12 +98,12 @@ __global__ __launch_bounds__(256) void ffn_gate_up_kernel(
     const void* const* __restrict__ W1t, const void* const* __restrict__ W3t, int d, int f,
     T* __restrict__ H, T* __restrict__ Gs, T* __restrict__ Us) {
   __shared__ Smem sm;
-  if ((int)blockIdx.y >= sched->n_mtiles) return;
-  const MTile tl = mt[blockIdx.y];
+  if ((int)blockIdx.x >= sched->n_mtiles) return;
+  const MTile tl = mt[blockIdx.x];
   const T* W1 = (const T*)W1t[tl.expert];
   const bool gated = W3t != nullptr;
   const T* W3 = gated ? (const T*)W3t[tl.expert] : nullptr;
-  const int n0 = blockIdx.x * BN;
+  const int n0 = blockIdx.y * BN;
   float g[4][4], u[4][4];
   zero(g);
   zero(u);
@@ -138,10 +138,10 @@ __global__ __launch_bounds__(256) void ffn_down_kernel(const T* __restrict__ H,
                                                        const void* const* __restrict__ W2t, int d,
                                                        int f, T* __restrict__ y) {
   __shared__ Smem sm;
-  if ((int)blockIdx.y >= sched->n_mtiles) return;
-  const MTile tl = mt[blockIdx.y];
+  if ((int)blockIdx.x >= sched->n_mtiles) return;
+  const MTile tl = mt[blockIdx.x];
   const T* W2 = (const T*)W2t[tl.expert];
-  const int n0 = blockIdx.x * BN;
+  const int n0 = blockIdx.y * BN;
   float acc[4][4];
   zero(acc);
   tile_mac(acc, H + (size_t)tl.row0 * f, f, 1, tl.rows, W2 + (size_t)n0 * f, 1, f, d - n0, f, sm);
@@ -168,10 +168,10 @@ __global__ __launch_bounds__(256) void ffn_bwd_dh_kernel(
     const void* const* __restrict__ W2t, int d, int f, T* __restrict__ dG, T* __restrict__ dU,
     T* __restrict__ H) {
   __shared__ Smem sm;
-  if ((int)blockIdx.y >= sched->n_mtiles) return;
-  const MTile tl = mt[blockIdx.y];
+  if ((int)blockIdx.x >= sched->n_mtiles) return;
+  const MTile tl = mt[blockIdx.x];
   const T* W2 = (const T*)W2t[tl.expert];  // [d,f]: B(k=c, n) = W2[c*f + n]
-  const int n0 = blockIdx.x * BN;
+  const int n0 = blockIdx.y * BN;
   float acc[4][4];
   zero(acc);
   tile_mac(acc, dy + (size_t)tl.row0 * d, d, 1, tl.rows, W2 + n0, f, 1, f - n0, d, sm);
@@ -207,12 +207,12 @@ __global__ __launch_bounds__(256) void ffn_bwd_dx_kernel(
     const MTile* __restrict__ mt, const void* const* __restrict__ W1t,
     const void* const* __restrict__ W3t, int d, int f, T* __restrict__ dx) {
   __shared__ Smem sm;
-  if ((int)blockIdx.y >= sched->n_mtiles) return;
-  const MTile tl = mt[blockIdx.y];
+  if ((int)blockIdx.x >= sched->n_mtiles) return;
+  const MTile tl = mt[blockIdx.x];
   const T* W1 = (const T*)W1t[tl.expert];  // [f,d]: B(k=n_f, n=c) = W1[n_f*d + c]
   const bool gated = W3t != nullptr;
   const T* W3 = gated ? (const T*)W3t[tl.expert] : nullptr;
-  const int n0 = blockIdx.x * BN;
+  const int n0 = blockIdx.y * BN;
   float acc[4][4];
   zero(acc);
   tile_mac(acc, dG + (size_t)tl.row0 * f, f, 1, tl.rows, W1 + n0, d, 1, d - n0, f, sm);
@@ -304,11 +304,11 @@ int ffn_generic_t(moe_ctx* c, bool gated, const void* xp, void* y, void* G, void
   const void* const* W1 = c->d_wtab + 0 * MOE_MAX_EXPERTS;
   const void* const* W3 = gated ? c->d_wtab + 1 * MOE_MAX_EXPERTS : nullptr;
   const void* const* W2 = c->d_wtab + 2 * MOE_MAX_EXPERTS;
-  hipLaunchKernelGGL((ffn_gate_up_kernel<T>), dim3((f + BN - 1) / BN, mtiles), dim3(256), 0, s,
+  hipLaunchKernelGGL((ffn_gate_up_kernel<T>), dim3(mtiles, (f + BN - 1) / BN), dim3(256), 0, s,
                      (const T*)xp, c->d_sched[0], c->d_mtiles[0], W1, W3, d, f, (T*)H, (T*)G,
                      (T*)U);
   prof_mark(c, 2, s);
-  hipLaunchKernelGGL((ffn_down_kernel<T>), dim3((d + BN - 1) / BN, mtiles), dim3(256), 0, s,
+  hipLaunchKernelGGL((ffn_down_kernel<T>), dim3(mtiles, (d + BN - 1) / BN), dim3(256), 0, s,
                      (const T*)H, c->d_sched[0], c->d_mtiles[0], W2, d, f, (T*)y);
   prof_mark(c, 3, s);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
@@ -326,10 +326,10 @@ int ffn_bwd_generic_t(moe_ctx* c, bool gated, const void* dy, const void* xp, co
   const void* const* dW1 = c->d_wtab + 3 * MOE_MAX_EXPERTS;
   const void* const* dW3 = c->d_wtab + 4 * MOE_MAX_EXPERTS;
   const void* const* dW2 = c->d_wtab + 5 * MOE_MAX_EXPERTS;
-  hipLaunchKernelGGL((ffn_bwd_dh_kernel<T>), dim3((f + BN - 1) / BN, mtiles), dim3(256), 0, s,
+  hipLaunchKernelGGL((ffn_bwd_dh_kernel<T>), dim3(mtiles, (f + BN - 1) / BN), dim3(256), 0, s,
                      (const T*)dy, (const T*)G, gated ? (const T*)U : nullptr, c->d_sched[0],
                      c->d_mtiles[0], W2, d, f, (T*)dG, (T*)dU, (T*)H);
-  hipLaunchKernelGGL((ffn_bwd_dx_kernel<T>), dim3((d + BN - 1) / BN, mtiles), dim3(256), 0, s,
+  hipLaunchKernelGGL((ffn_bwd_dx_kernel<T>), dim3(mtiles, (d + BN - 1) / BN), dim3(256), 0, s,
                      (const T*)dG, (const T*)dU, c->d_sched[0], c->d_mtiles[0], W1, W3, d, f,
                      (T*)dxp);
   const dim3 g_df((f + BN - 1) / BN, (d + BM - 1) / BM, E);  // output [d,f]
@@ -350,7 +350,7 @@ int launch_gate_logits(const moe_ctx* c, const void* x, const void* Wg, const fl
                        float* logits, hipStream_t s) {
   if (T == 0) return MOE_OK;
   const int E = c->cfg.E, d = c->cfg.d;
-  const dim3 grid((E + BN - 1) / BN, (T + BM - 1) / BM);
+  const dim3 grid((T + BM - 1) / BM, (E + BN - 1) / BN);
   if (c->cfg.dtype == MOE_BF16)
     hipLaunchKernelGGL((gate_logits_kernel<uint16_t>), grid, dim3(256), 0, s, (const uint16_t*)x,
                        (const uint16_t*)Wg, bias, T, E, d, logits);

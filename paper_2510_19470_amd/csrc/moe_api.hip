@@ -22,6 +22,9 @@ void free_all(moe_ctx* c) {
   (void)hipFree(c->d_chunk_hist);
   (void)hipFree(c->d_totals);
   (void)hipFree(c->d_logits);
+  (void)hipFree(c->d_rt_rank);
+  (void)hipFree(c->d_rt_hist);
+  (void)hipFree(c->d_rt_super);
   (void)hipFree(c->d_wtab);
   for (int i = 0; i < 2; ++i) {
     (void)hipFree(c->d_sched[i]);
@@ -111,9 +114,6 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
   const long long S = (long long)cfg->T_max * cfg->k;
   if (S > (1ll << 22)) return MOE_EUNSUPPORTED;                           // grid / int32 headroom
   if (S * std::max(cfg->d, cfg->f) > (1ll << 40)) return MOE_EUNSUPPORTED;
-  // the vector-ALU kernels put the 64-row blocks of the segments (and of the tokens) on grid.y
-  if (S / GENERIC_BM + cfg->E > 65535 || cfg->T_max / GENERIC_BM + 1 > 65535)
-    return MOE_EUNSUPPORTED;
 
   moe_ctx* c = new (std::nothrow) moe_ctx();
   if (c == nullptr) return MOE_ENOMEM;
@@ -149,6 +149,17 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
     ok = ok && dev_alloc(&c->d_order_up, n) == hipSuccess;
     ok = ok && dev_alloc(&c->d_order_down, n) == hipSuccess;
     ok = ok && dev_alloc(&c->d_split_ws, (size_t)c->n_cu * MFMA_BM * 256) == hipSuccess;
+  }
+  // side products of the fused gate kernel (moe_dispatch_routed); left out when the gate is
+  // not fused for this configuration or the histograms would be large
+  const long long n_blk = ((long long)cfg->T_max + GATE_BLOCK_TOKENS - 1) / GATE_BLOCK_TOKENS;
+  if (ok && gate_route_fused_supported(c) && cfg->T_max <= (1 << 17) && n_blk * E <= (1 << 22)) {
+    c->rt_super_max = (int32_t)((n_blk + RT_SUPER - 1) / RT_SUPER);
+    const size_t n_sup = (size_t)2 * std::max(c->rt_super_max, 1) * E;
+    ok = ok && dev_alloc(&c->d_rt_rank, (size_t)S) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_rt_hist, (size_t)n_blk * E) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_rt_super, n_sup) == hipSuccess;
+    ok = ok && hipMemset(c->d_rt_super, 0, n_sup * sizeof(int32_t)) == hipSuccess;
   }
   ok = ok && hipMalloc(&c->d_H, std::max<size_t>((size_t)S * cfg->f * c->elem, 16)) == hipSuccess;
   ok = ok && hipMemset(c->d_totals, 0, sizeof(int32_t) * (2 * MOE_MAX_EXPERTS + 2)) == hipSuccess;
@@ -320,9 +331,31 @@ int moe_route(moe_ctx* c, const void* x, const void* Wg, const float* bias, int3
   if (!aligned16(x) || !aligned16(Wg) || !aligned16(bias) || !aligned16(logits) ||
       !aligned16(topk_idx) || !aligned16(topk_w))
     return MOE_EINVAL;
-  if (gate_route_fused_supported(c))  // one launch, logits only written when asked for
-    return launch_gate_route_fused(c, x, Wg, bias, T, logits, topk_idx, topk_w,
-                                   (hipStream_t)stream);
+  c->rt_valid = 0;
+  if (gate_route_fused_supported(c)) {  // one launch, logits only written when asked for
+    // The counting step of the dispatch rides along unless the stream is being captured: the
+    // buffer the sums go to alternates from call to call on the host, and a replayed graph
+    // would add into the same buffer every time.
+    bool keep = c->d_rt_rank != nullptr;
+    if (keep) {
+      hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+      if (hipStreamIsCapturing((hipStream_t)stream, &cs) != hipSuccess) {
+        (void)hipGetLastError();
+        keep = false;
+      } else if (cs != hipStreamCaptureStatusNone) {
+        keep = false;
+      }
+    }
+    if (keep) c->rt_parity ^= 1;
+    st = launch_gate_route_fused(c, x, Wg, bias, T, logits, topk_idx, topk_w, keep,
+                                 (hipStream_t)stream);
+    if (st == MOE_OK && keep) {
+      c->rt_valid = 1;
+      c->rt_idx = topk_idx;
+      c->rt_T = T;
+    }
+    return st;
+  }
   float* L = logits != nullptr ? logits : c->d_logits;
   st = launch_gate_logits(c, x, Wg, bias, T, L, (hipStream_t)stream);
   if (st != MOE_OK) return st;
@@ -346,6 +379,26 @@ int moe_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int32_t T, 
     return MOE_EINVAL;
   return launch_dispatch(c, x, topk_idx, T, x_packed, slot_to_row, row_to_slot, expert_counts,
                          expert_offsets, rank_counts, rank_offsets, (hipStream_t)stream);
+}
+
+int moe_dispatch_routed(moe_ctx* c, const void* x, const int32_t* topk_idx, int32_t T,
+                        void* x_packed, int32_t* slot_to_row, int32_t* row_to_slot,
+                        int32_t* expert_counts, int32_t* expert_offsets, int32_t* rank_counts,
+                        int32_t* rank_offsets, void* stream) {
+  if (c == nullptr) return MOE_EINVAL;
+  const bool routed = c->rt_valid && T > 0 && c->rt_idx == topk_idx && c->rt_T == T;
+  if (!routed)
+    return moe_dispatch(c, x, topk_idx, T, x_packed, slot_to_row, row_to_slot, expert_counts,
+                        expert_offsets, rank_counts, rank_offsets, stream);
+  if (expert_counts == nullptr || expert_offsets == nullptr || rank_counts == nullptr ||
+      rank_offsets == nullptr || slot_to_row == nullptr || row_to_slot == nullptr)
+    return MOE_EINVAL;
+  if ((x == nullptr) != (x_packed == nullptr)) return MOE_EINVAL;
+  if (!aligned16(x) || !aligned16(x_packed) || !aligned16(slot_to_row) || !aligned16(row_to_slot))
+    return MOE_EINVAL;
+  return launch_dispatch_routed(c, x, topk_idx, T, x_packed, slot_to_row, row_to_slot,
+                                expert_counts, expert_offsets, rank_counts, rank_offsets,
+                                (hipStream_t)stream);
 }
 
 int moe_expert_ffn(moe_ctx* c, const void* x_packed, const int32_t* expert_counts,

@@ -53,6 +53,18 @@ struct moe_ctx {
   int32_t* d_totals;      // [2][MOE_MAX_EXPERTS] per-expert totals, double-buffered per call, then
                           // [2] the call number as the device keeps it
   float* d_logits;        // [T_max][E] when the caller does not want the logits
+  // side products of the fused gate kernel for moe_dispatch_routed (nullptr: not kept):
+  // per 32-token gate block the rank of every slot among the block's slots of the same
+  // expert and the block's expert histogram; per super-block of 16 gate blocks the histogram
+  // sums, accumulated with integer atomics into buffer rt_parity (the launch clears the other)
+  int32_t* d_rt_rank;     // [S_max]
+  int32_t* d_rt_hist;     // [ceil(T_max/32)][E]
+  int32_t* d_rt_super;    // [2][rt_super_max][E]
+  int32_t rt_super_max;
+  int rt_parity;          // buffer the last moe_route accumulated into
+  int rt_valid;           // the side products describe rt_idx / rt_T
+  const int32_t* rt_idx;
+  int32_t rt_T;
   // expert weight pointer tables: device copy [6][MOE_MAX_EXPERTS] (W1, W3, W2, dW1, dW3,
   // dW2), refreshed only when the host tables change
   const void** d_wtab;
@@ -94,6 +106,19 @@ inline void prof_mark(moe_ctx* c, int slot, hipStream_t s) {
 }
 
 #define DISPATCH_CHUNK 1024      // slots per histogram / ranking block
+#define GATE_BLOCK_TOKENS 32     // tokens per block of the fused gate kernel
+#define RT_SUPER 16              // gate blocks per super-block of the routed dispatch
+
+// Lanes of the wavefront holding the same value as this lane (value in [0,256) or -1 for
+// "none"): one ballot per bit of the value, no loop over the distinct values.
+__device__ __forceinline__ unsigned long long match_same(int e, int nbits) {
+  unsigned long long m = __ballot(e >= 0);
+  for (int b = 0; b < nbits; ++b) {
+    const unsigned long long bal = __ballot((e >> b) & 1);
+    m &= ((e >> b) & 1) ? bal : ~bal;
+  }
+  return m;
+}
 #define GENERIC_BM 64
 #define MFMA_BM 256
 
@@ -101,8 +126,14 @@ inline void prof_mark(moe_ctx* c, int slot, hipStream_t s) {
 int launch_route_select(const moe_ctx* c, const float* logits, int T, int32_t* idx, float* w,
                         hipStream_t s);
 bool gate_route_fused_supported(const moe_ctx* c);
+// keep_hist: also write the side products of moe_dispatch_routed (c->d_rt_*, buffer c->rt_parity)
 int launch_gate_route_fused(const moe_ctx* c, const void* x, const void* Wg, const float* bias,
-                            int T, float* logits, int32_t* idx, float* w, hipStream_t s);
+                            int T, float* logits, int32_t* idx, float* w, bool keep_hist,
+                            hipStream_t s);
+int launch_dispatch_routed(moe_ctx* c, const void* x, const int32_t* topk_idx, int T,
+                           void* x_packed, int32_t* slot_to_row, int32_t* row_to_slot,
+                           int32_t* expert_counts, int32_t* expert_offsets, int32_t* rank_counts,
+                           int32_t* rank_offsets, hipStream_t s);
 int launch_gate_logits(const moe_ctx* c, const void* x, const void* Wg, const float* bias, int T,
                        float* logits, hipStream_t s);
 int launch_dispatch(moe_ctx* c, const void* x, const int32_t* topk_idx, int T, void* x_packed,

@@ -157,7 +157,7 @@ int moe_pipeline_forward(moe_pipeline* p, const void* x, const void* Wg, const f
     int32_t* off = expert_offsets + (size_t)c * E;
     status = moe_route(ctx, xc, Wg, bias, Tc, nullptr, idx, w, s);
     if (status == MOE_OK)
-      status = moe_dispatch(ctx, Tc > 0 ? xc : nullptr, idx, Tc, Tc > 0 ? xp : nullptr,
+      status = moe_dispatch_routed(ctx, Tc > 0 ? xc : nullptr, idx, Tc, Tc > 0 ? xp : nullptr,
                             slot_to_row + s0, row_to_slot + s0, cnt, off,
                             rank_counts + (size_t)c * R, rank_offsets + (size_t)c * (R + 1), s);
     if (status == MOE_OK)

@@ -75,10 +75,12 @@ __device__ __forceinline__ float group_sum(float x) {
 // must call this together (dead groups pass live = false).  Round j finds the largest key
 // left (local scan, then a butterfly over the group); the winner is kept by lane j mod W of
 // the group (slot j / W), which later computes and writes that slot's weight.
+// lds_ids (optional): the token's k ids are also stored there (the fused kernel ranks them).
 template <int W, int VPL>
 __device__ __forceinline__ void select_token(const float* row, bool live, int t, int E, int k,
                                              int renormalize, int32_t* __restrict__ topk_idx,
-                                             float* __restrict__ topk_w) {
+                                             float* __restrict__ topk_w,
+                                             int32_t* lds_ids = nullptr) {
   const int lane = threadIdx.x & 63;
   const int gl = lane % W;   // lane inside the group
   constexpr int SLOTS = (MOE_MAX_TOPK + W - 1) / W;
@@ -133,8 +135,10 @@ __device__ __forceinline__ void select_token(const float* row, bool live, int t,
     for (int q = 0; q < SLOTS; ++q) {
       const int j = q * W + gl;
       if (j < k) {
-        topk_idx[(size_t)t * k + j] = mine[q] == 0 ? 0 : key_id(mine[q]);
+        const int id = mine[q] == 0 ? 0 : key_id(mine[q]);
+        topk_idx[(size_t)t * k + j] = id;
         topk_w[(size_t)t * k + j] = expf(key_value(mine[q]) - m) * inv;
+        if (lds_ids != nullptr) lds_ids[j] = id;
       }
     }
   }
@@ -164,17 +168,25 @@ __global__ __launch_bounds__(256) void route_select_kernel(const float* __restri
 // tokens (from L2).  The partial sums meet in LDS, the bias is added, the logits are
 // written out when the caller wants them, and the block selects the top-k of its 32 tokens
 // from LDS.  The token rows are read exactly once: the kernel is bound by HBM.
+// HIST: the block also does the counting step of the dispatch for its 32 * k slots, which it
+// holds anyway: the stable rank of every slot among the block's slots of the same expert
+// (ballots inside a wavefront, an LDS table across the 8 wavefronts), the block's expert
+// histogram, and that histogram added (integer atomics: order-independent) to the sums of
+// the block's super-block of 16; the first block of a super-block clears the super-block's
+// sums in the other buffer, for the next call.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
-constexpr int GATE_TOK = 32;    // tokens per block
+constexpr int GATE_TOK = GATE_BLOCK_TOKENS;    // tokens per block
 constexpr int GATE_WAVES = 8;   // wavefronts per block, each with an eighth of d
 constexpr int GATE_TB = GATE_TOK / 16;
 
-template <int W, int VPL, int NEB>
+template <int W, int VPL, int NEB, bool HIST>
 __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
     const float* __restrict__ bias, int T, int E, int d, int k, int renormalize,
-    float* __restrict__ logits_out, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+    float* __restrict__ logits_out, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    int ebits, int32_t* __restrict__ rt_rank, int32_t* __restrict__ rt_hist,
+    int32_t* __restrict__ super_acc, int32_t* __restrict__ super_clear) {
   constexpr int EG = 16 * NEB;                     // experts per pass over the token rows
   constexpr int EP = W * VPL < 64 ? 64 : W * VPL;  // expert slots kept in LDS
   __shared__ float part[GATE_WAVES][GATE_TOK][EG + 1];
@@ -235,12 +247,47 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
     }
     __syncthreads();
   }
+  // the partial sums are not needed any more (the barrier that ends the loop above): their
+  // LDS holds the block's selected ids [32][k] and the per-wavefront expert counts [8][256]
+  int32_t* ids = reinterpret_cast<int32_t*>(&part[0][0][0]);
+  int32_t* wcnt = ids + GATE_TOK * MOE_MAX_TOPK;
+  static_assert(sizeof(part) >= sizeof(int32_t) * (GATE_TOK * MOE_MAX_TOPK + GATE_WAVES * MOE_MAX_EXPERTS),
+                "the ids and counts of the ranking step live in the partial sums' LDS");
+  if (HIST) {
+    for (int i = tid; i < GATE_TOK * MOE_MAX_TOPK; i += 64 * GATE_WAVES) ids[i] = -1;
+    for (int i = tid; i < GATE_WAVES * MOE_MAX_EXPERTS; i += 64 * GATE_WAVES) wcnt[i] = 0;
+    __syncthreads();
+  }
   constexpr int TOK_PER_WAVE = 64 / W;
   for (int base = 0; base < GATE_TOK; base += GATE_WAVES * TOK_PER_WAVE) {
     const int tok = base + wave * TOK_PER_WAVE + lane / W;
     const bool live = tok < GATE_TOK && t0 + tok < T;
     select_token<W, VPL>(&fin[live ? tok : 0][0], live, t0 + tok, E, k, renormalize, topk_idx,
-                         topk_w);
+                         topk_w, HIST ? ids + (live ? tok : 0) * k : nullptr);
+  }
+  if (HIST) {
+    __syncthreads();
+    // slot s = tok * k + j of the block, one per thread (32 * k <= 512)
+    const int s = tid;
+    const int e = s < GATE_TOK * k ? ids[s] : -1;   // -1: no slot, or a token past T
+    const unsigned long long same = match_same(e, ebits);
+    const int in_wave = __popcll(same & ((1ull << lane) - 1ull));
+    if (e >= 0 && in_wave == 0) wcnt[wave * MOE_MAX_EXPERTS + e] = __popcll(same);
+    __syncthreads();
+    if (e >= 0) {
+      int rank = in_wave;
+      for (int w8 = 0; w8 < wave; ++w8) rank += wcnt[w8 * MOE_MAX_EXPERTS + e];
+      rt_rank[(size_t)blockIdx.x * (GATE_TOK * k) + s] = rank;
+    }
+    if (tid < E) {
+      int n = 0;
+#pragma unroll
+      for (int w8 = 0; w8 < GATE_WAVES; ++w8) n += wcnt[w8 * MOE_MAX_EXPERTS + tid];
+      rt_hist[(size_t)blockIdx.x * E + tid] = n;
+      const size_t sup = (size_t)(blockIdx.x / RT_SUPER) * E + tid;
+      if (n != 0) atomicAdd(&super_acc[sup], n);
+      if (blockIdx.x % RT_SUPER == 0) super_clear[sup] = 0;
+    }
   }
 }
 
@@ -257,11 +304,23 @@ int launch_sel(const float* logits, int T, int E, int k, int renorm, int32_t* id
 
 template <int W, int VPL, int NEB>
 int launch_gate(const moe_ctx* c, const void* x, const void* Wg, const float* bias, int T,
-                float* logits, int32_t* idx, float* w, hipStream_t s) {
+                float* logits, int32_t* idx, float* w, bool keep_hist, hipStream_t s) {
   const int grid = (T + GATE_TOK - 1) / GATE_TOK;
-  hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB>), dim3(grid), dim3(64 * GATE_WAVES), 0, s,
-                     (const uint16_t*)x, (const uint16_t*)Wg, bias, T, c->cfg.E, c->cfg.d,
-                     c->cfg.k, c->cfg.renormalize, logits, idx, w);
+  if (keep_hist) {
+    int ebits = 0;
+    while ((1 << ebits) < c->cfg.E) ++ebits;
+    const size_t half = (size_t)c->rt_super_max * c->cfg.E;
+    hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, true>), dim3(grid),
+                       dim3(64 * GATE_WAVES), 0, s, (const uint16_t*)x, (const uint16_t*)Wg, bias, T,
+                       c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, ebits,
+                       c->d_rt_rank, c->d_rt_hist, c->d_rt_super + (size_t)c->rt_parity * half,
+                       c->d_rt_super + (size_t)(c->rt_parity ^ 1) * half);
+  } else {
+    hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, false>), dim3(grid),
+                       dim3(64 * GATE_WAVES), 0, s, (const uint16_t*)x, (const uint16_t*)Wg, bias, T,
+                       c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, 0, nullptr,
+                       nullptr, nullptr, nullptr);
+  }
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 
@@ -287,20 +346,23 @@ bool gate_route_fused_supported(const moe_ctx* c) {
 }
 
 int launch_gate_route_fused(const moe_ctx* c, const void* x, const void* Wg, const float* bias,
-                            int T, float* logits, int32_t* idx, float* w, hipStream_t s) {
+                            int T, float* logits, int32_t* idx, float* w, bool keep_hist,
+                            hipStream_t s) {
   if (T == 0) return MOE_OK;
   const int E = c->cfg.E;
   // a group of 8 lanes per token (8 tokens per wavefront) up to 64 experts: the selection
   // costs (experts per lane + 3 butterfly levels) per round instead of 6 butterfly levels,
   // and the block's 32 tokens are selected in one pass by four wavefronts
-  if (E <= 2) return launch_gate<2, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 4) return launch_gate<4, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 8) return launch_gate<8, 1, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 16) return launch_gate<8, 2, 1>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 32) return launch_gate<8, 4, 2>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 48) return launch_gate<8, 6, 3>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 64) return launch_gate<8, 8, 4>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 128) return launch_gate<64, 2, 4>(c, x, Wg, bias, T, logits, idx, w, s);
-  if (E <= 256) return launch_gate<64, 4, 4>(c, x, Wg, bias, T, logits, idx, w, s);
+#define GATE(W_, VPL_, NEB_) launch_gate<W_, VPL_, NEB_>(c, x, Wg, bias, T, logits, idx, w, keep_hist, s)
+  if (E <= 2) return GATE(2, 1, 1);
+  if (E <= 4) return GATE(4, 1, 1);
+  if (E <= 8) return GATE(8, 1, 1);
+  if (E <= 16) return GATE(8, 2, 1);
+  if (E <= 32) return GATE(8, 4, 2);
+  if (E <= 48) return GATE(8, 6, 3);
+  if (E <= 64) return GATE(8, 8, 4);
+  if (E <= 128) return GATE(64, 2, 4);
+  if (E <= 256) return GATE(64, 4, 4);
+#undef GATE
   return MOE_EUNSUPPORTED;
 }

@@ -74,7 +74,7 @@ class MoELayer:
         """Runs the four forward calls.  Rows of experts without weights keep whatever
         `y_remote` holds (the rows that would come back from the other ranks)."""
         idx, w, _ = B.moe_route(self.ctx, x, self.Wg, self.bias)
-        disp = B.moe_dispatch(self.ctx, x, idx)
+        disp = B.moe_dispatch_routed(self.ctx, x, idx)   # idx is what moe_route just wrote
         y = y_remote if y_remote is not None else torch.zeros_like(disp.x_packed)
         y, G, U = B.moe_expert_ffn(self.ctx, disp.x_packed, disp.expert_counts, disp.expert_offsets,
                                    self.W1, self.W3, self.W2, y_packed=y, save=save)

@@ -177,3 +177,86 @@ def test_combine_full_size_streaming():
     want = orc.combine(vals(y_st[uniq], cfg.dtype), inv.reshape(-1).astype(np.int32), w_np[ts])
     assert nerr(got[ts], want) <= TOL[cfg.dtype]
     ctx.close()
+
+
+# ------------------------------------------------------------------ routed dispatch
+def _routed_case(cfg, inp, T_call=None, bias=None):
+    """moe_route then moe_dispatch_routed (one launch on the gate kernel's side products):
+    every integer output and the packed rows against the oracle on the GPU's own routing,
+    and against moe_dispatch, bit for bit."""
+    from gpu_common import DEV, moe, i32, to_device, to_host_bits
+    T = cfg.T if T_call is None else T_call
+    ctx = moe.moe_create(T_max=max(cfg.T, 1), d=cfg.d, E=cfg.E, k=cfg.k, f=cfg.f, R=cfg.R,
+                         local_rank=cfg.local_rank, dtype=moe.MOE_BF16)
+    moe.moe_set_placement(ctx, inp.dest_rank)
+    x = to_device(inp.x[:T], cfg.dtype)
+    Wg = to_device(inp.Wg, cfg.dtype)
+    b = None if bias is None else torch.from_numpy(bias).to(DEV)
+    idx, w, _ = moe.moe_route(ctx, x, Wg, b)
+    got = moe.moe_dispatch_routed(ctx, x, idx)
+    torch.cuda.synchronize()
+    idx_np = i32(idx)
+    want = orc.dispatch_maps(idx_np, inp.dest_rank, cfg.R)
+    names = ("expert_counts", "expert_offsets", "rank_counts", "rank_offsets", "slot_to_row",
+             "row_to_slot")
+    for nm, wv in zip(names, want):
+        assert np.array_equal(i32(getattr(got, nm)), wv), nm
+    xp_want = orc.pack_rows(inp.x[:T], want[5], cfg.k)
+    xp_got = to_host_bits(got.x_packed)
+    assert np.array_equal(xp_got, xp_want.view(xp_got.dtype))
+    # the two-launch path on the same routing; then the routed call again (the side products
+    # stay valid), and after another moe_route with fewer tokens
+    two = moe.moe_dispatch(ctx, x, idx)
+    again = moe.moe_dispatch_routed(ctx, x, idx)
+    torch.cuda.synchronize()
+    for nm in names:
+        assert torch.equal(getattr(two, nm), getattr(got, nm)), nm
+        assert torch.equal(getattr(again, nm), getattr(got, nm)), nm
+    if T >= 64:
+        T2 = T // 2 + 3
+        x2 = x[:T2].contiguous()
+        idx2, _, _ = moe.moe_route(ctx, x2, Wg, b)
+        moe.moe_route(ctx, x2, Wg, b, topk_idx=idx2)          # twice in a row: the sums must not pile up
+        g2 = moe.moe_dispatch_routed(ctx, x2, idx2)
+        torch.cuda.synchronize()
+        want2 = orc.dispatch_maps(i32(idx2), inp.dest_rank, cfg.R)
+        for nm, wv in zip(names, want2):
+            assert np.array_equal(i32(getattr(g2, nm)), wv), nm
+        # a routing that moe_route did not write goes through the two-launch path
+        foreign = torch.from_numpy(wl.random_routing(T2, cfg.E, cfg.k, 9)).to(DEV)
+        g3 = moe.moe_dispatch_routed(ctx, x2, foreign)
+        torch.cuda.synchronize()
+        want3 = orc.dispatch_maps(i32(foreign), inp.dest_rank, cfg.R)
+        for nm, wv in zip(names, want3):
+            assert np.array_equal(i32(getattr(g3, nm)), wv), nm
+    ctx.close()
+    return want
+
+
+@pytest.mark.parametrize("name", ["small", "mixtral", "finegrained", "train"])
+def test_dispatch_routed_full_size_configs(name):
+    from gpu_common import say
+    cfg = wl.CONFIGS[name]
+    say(f"[dispatch-routed] config={name} T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} S={cfg.S}")
+    inp = wl.make_inputs(cfg, experts="none")
+    want = _routed_case(cfg, inp, bias=inp.bias)
+    say(f"    n_loc={int(want[2][cfg.local_rank])} of S={cfg.S}")
+
+
+@pytest.mark.parametrize("T,E,k,R,d", [
+    (1, 8, 2, 2, 256), (31, 8, 2, 2, 256), (33, 16, 3, 4, 256), (1000, 256, 16, 8, 256),
+    (5001, 64, 6, 256, 256), (4099, 7, 1, 7, 512), (9000, 128, 8, 4, 256),
+    (600, 48, 5, 3, 256),
+])
+def test_dispatch_routed_edge_shapes(T, E, k, R, d):
+    """Ragged last gate block, one token, the largest expert count and top-k, more than one
+    super-block of gate blocks with a partial last one, every expert-count branch of the
+    gate kernel."""
+    from gpu_common import say
+    say(f"[dispatch-routed-edge] T={T} E={E} k={k} R={R} d={d}")
+    cfg = wl.MoEConfig("routed", 300 + T, "bf16", T=T, d=d, E=E, k=k, f=256, R=R)
+    inp = wl.make_inputs(cfg, experts="none")
+    rng = np.random.default_rng(T)
+    inp.dest_rank = rng.integers(0, R, size=E).astype(np.int32)
+    bias = (-1.0 * np.log(np.arange(E) + 1.0)).astype(np.float32)    # skewed: some experts starve
+    _routed_case(cfg, inp, bias=bias)
