@@ -107,10 +107,9 @@ constexpr int SCATTER_PF = 8;   // 16-byte pieces of its token row a lane fetche
 // 42 -> 58 us on one of 134 MB, which the cache absorbs when it is written normally.
 // ROUTED: the counting was done by the fused gate kernel of moe_route.  chunk_hist is then the
 // histogram of every gate block of 32 tokens, totals2 the sums of every super-block of 16 gate
-// blocks (n_super of them), slot_rank the rank of a slot inside its gate block.  The 4 tokens
-// of a block lie in one gate block, so the number of slots of every expert before that gate
-// block is summed once per block, in LDS: the super-blocks before its own (their sum over all
-// super-blocks is the expert's total) plus the gate blocks before it in its own super-block.
+// blocks, rt_tot the grand totals (one 128-byte line per expert: the gate blocks add to them
+// with atomics), slot_rank the rank of a slot inside its gate block.  A slot's row = its expert's offset + the slots of that expert in the super-blocks
+// before its own + those in the gate blocks before its own inside its super-block + its rank.
 template <int K_MAX, bool STREAM, bool ROUTED>
 __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     const u32x4* __restrict__ x, const int32_t* __restrict__ topk_idx,
@@ -120,12 +119,10 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     int32_t* __restrict__ row_to_slot, u32x4* __restrict__ x_packed,
     int32_t* __restrict__ expert_counts, int32_t* __restrict__ expert_offsets,
     int32_t* __restrict__ rank_counts, int32_t* __restrict__ rank_offsets,
-    const int32_t* __restrict__ slot_rank, int n_super) {
+    const int32_t* __restrict__ slot_rank, const int32_t* __restrict__ rt_tot) {
   __shared__ int32_t scan[MOE_MAX_EXPERTS + 1];   // by position in segment order
   __shared__ int32_t offs[MOE_MAX_EXPERTS];       // expert id -> first row of its segment
   __shared__ int32_t rcnt[MOE_MAX_RANKS + 1];
-  __shared__ int32_t tot_s[MOE_MAX_EXPERTS];      // ROUTED: slots per expert
-  __shared__ int32_t pre_s[MOE_MAX_EXPERTS];      // ROUTED: ... in the gate blocks before this one
   const int tid = threadIdx.x, lane = tid & 63;
   const int t = (int)((blockIdx.x * (size_t)blockDim.x + tid) >> 6);   // wave-uniform
   const bool live = t < T;
@@ -149,29 +146,7 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
   }
   int mine = 0;
   if (ROUTED) {
-    // thread = (expert tid % EP, part tid / EP): the parts share the rows to be summed
-    int EP = 1;
-    while (EP < E) EP <<= 1;
-    const int ex = tid & (EP - 1), part = tid / EP, parts = 256 / EP;
-    const int gb = (int)(blockIdx.x * 4) / GATE_BLOCK_TOKENS, sc = gb / RT_SUPER;
-    tot_s[tid] = 0;
-    pre_s[tid] = 0;
-    int tot = 0, pre = 0;
-    if (ex < E) {
-      for (int r = part; r < n_super; r += parts) {
-        const int v = totals2[(size_t)r * E + ex];
-        tot += v;
-        pre += r < sc ? v : 0;
-      }
-      for (int g = sc * RT_SUPER + part; g < gb; g += parts) pre += chunk_hist[(size_t)g * E + ex];
-    }
-    lds_barrier();
-    if (ex < E) {
-      if (tot != 0) atomicAdd(&tot_s[ex], tot);   // integer adds in LDS: order does not matter
-      if (pre != 0) atomicAdd(&pre_s[ex], pre);
-    }
-    lds_barrier();
-    if (tid < E) mine = tot_s[tid];
+    if (tid < E) mine = rt_tot[tid * RT_TOT_STRIDE];
   } else {
     if (tid < E) mine = totals2[(call & 1) * MOE_MAX_EXPERTS + tid];
     if (blockIdx.x == 0 && tid == 0) ctr[0] = call + 1;
@@ -213,21 +188,24 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
   if ((unsigned)e >= (unsigned)E || rk < 0) e = -1;
   // the histograms of the chunks before the slot's own, summed for all k slots at once:
   // lane = (slot j, part p) with 64 / K_MAX parts per slot
-  int base;
+  constexpr int PARTS = 64 / K_MAX;
+  const int j_of = lane / PARTS, p_of = lane % PARTS;
+  const int ej = __shfl(e, j_of, 64);
+  int part = 0;
   if (ROUTED) {
-    base = e >= 0 ? pre_s[e] : 0;
+    const int gb = t / GATE_BLOCK_TOKENS, sc = gb / RT_SUPER;
+    if (j_of < k && ej >= 0) {
+      for (int r = p_of; r < sc; r += PARTS) part += totals2[(size_t)r * E + ej];
+      for (int g = sc * RT_SUPER + p_of; g < gb; g += PARTS) part += chunk_hist[(size_t)g * E + ej];
+    }
   } else {
-    constexpr int PARTS = 64 / K_MAX;
-    const int j_of = lane / PARTS, p_of = lane % PARTS;
-    const int ej = __shfl(e, j_of, 64);
     const int cj = (t * k + j_of) / DISPATCH_CHUNK;
-    int part = 0;
     if (j_of < k && ej >= 0)
       for (int c = p_of; c < cj; c += PARTS) part += chunk_hist[(size_t)c * E + ej];
-#pragma unroll
-    for (int off = PARTS / 2; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
-    base = __shfl(part, lane * PARTS, 64);   // lane j < K_MAX: the sum of slot j
   }
+#pragma unroll
+  for (int off = PARTS / 2; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
+  const int base = __shfl(part, lane * PARTS, 64);   // lane j < K_MAX: the sum of slot j
   int row = -1;
   if (lane < k) {
     const int s = t * k + lane;
@@ -293,7 +271,7 @@ int launch_dispatch_on(const int32_t* seg_pos, const int32_t* dest_rank, int32_t
   hipLaunchKernelGGL((dispatch_scatter_kernel<KM, ST, false>), dim3(grid), dim3(256), 0, s,       \
                      (const u32x4*)x, topk_idx, chunk_hist, totals, seg_pos, dest_rank, T, k, E, \
                      R, row_vec, slot_to_row, row_to_slot, (u32x4*)x_packed, expert_counts,      \
-                     expert_offsets, rank_counts, rank_offsets, nullptr, 0)
+                     expert_offsets, rank_counts, rank_offsets, nullptr, nullptr)
   if (k <= 2) LAUNCH_SCATTER(2);
   else if (k <= 4) LAUNCH_SCATTER(4);
   else if (k <= 8) LAUNCH_SCATTER(8);
@@ -322,9 +300,10 @@ int launch_dispatch_routed(moe_ctx* c, const void* x, const int32_t* topk_idx, i
   const int S = T * k;
   const int row_vec = x != nullptr ? c->cfg.d * c->elem / 16 : 0;
   const int grid = (T + 3) / 4;
-  const int n_blk = (T + GATE_BLOCK_TOKENS - 1) / GATE_BLOCK_TOKENS;
-  const int n_super = (n_blk + RT_SUPER - 1) / RT_SUPER;
-  int32_t* super = c->d_rt_super + (size_t)c->rt_parity * c->rt_super_max * E;
+  // buffer of the last moe_route: [rt_super_max][E] super-block sums, then the grand totals
+  const size_t half = (size_t)c->rt_super_max * E + (size_t)E * RT_TOT_STRIDE;
+  int32_t* super = c->d_rt_super + (size_t)c->rt_parity * half;
+  const int32_t* rt_tot = super + (size_t)c->rt_super_max * E;
   const bool stream = (size_t)S * row_vec * 16 > ((size_t)192 << 20);
 #define LAUNCH_ROUTED(KM)                                                                        \
   if (stream) LAUNCH_ROUTED2(KM, true); else LAUNCH_ROUTED2(KM, false)
@@ -333,7 +312,7 @@ int launch_dispatch_routed(moe_ctx* c, const void* x, const int32_t* topk_idx, i
                      (const u32x4*)x, topk_idx, c->d_rt_hist, super, c->d_seg_pos,               \
                      c->d_dest_rank, T, k, E, R, row_vec, slot_to_row, row_to_slot,              \
                      (u32x4*)x_packed, expert_counts, expert_offsets, rank_counts, rank_offsets, \
-                     c->d_rt_rank, n_super)
+                     c->d_rt_rank, rt_tot)
   if (k <= 2) LAUNCH_ROUTED(2);
   else if (k <= 4) LAUNCH_ROUTED(4);
   else if (k <= 8) LAUNCH_ROUTED(8);

@@ -155,7 +155,7 @@ int moe_create(moe_ctx** out, const moe_config* cfg) {
   const long long n_blk = ((long long)cfg->T_max + GATE_BLOCK_TOKENS - 1) / GATE_BLOCK_TOKENS;
   if (ok && gate_route_fused_supported(c) && cfg->T_max <= (1 << 17) && n_blk * E <= (1 << 22)) {
     c->rt_super_max = (int32_t)((n_blk + RT_SUPER - 1) / RT_SUPER);
-    const size_t n_sup = (size_t)2 * std::max(c->rt_super_max, 1) * E;
+    const size_t n_sup = (size_t)2 * ((size_t)c->rt_super_max * E + (size_t)E * RT_TOT_STRIDE);
     ok = ok && dev_alloc(&c->d_rt_rank, (size_t)S) == hipSuccess;
     ok = ok && dev_alloc(&c->d_rt_hist, (size_t)n_blk * E) == hipSuccess;
     ok = ok && dev_alloc(&c->d_rt_super, n_sup) == hipSuccess;

@@ -59,7 +59,7 @@ struct moe_ctx {
   // sums, accumulated with integer atomics into buffer rt_parity (the launch clears the other)
   int32_t* d_rt_rank;     // [S_max]
   int32_t* d_rt_hist;     // [ceil(T_max/32)][E]
-  int32_t* d_rt_super;    // [2][rt_super_max][E]
+  int32_t* d_rt_super;    // [2] x ([rt_super_max][E] super-block sums, [E][RT_TOT_STRIDE] totals)
   int32_t rt_super_max;
   int rt_parity;          // buffer the last moe_route accumulated into
   int rt_valid;           // the side products describe rt_idx / rt_T
@@ -108,6 +108,7 @@ inline void prof_mark(moe_ctx* c, int slot, hipStream_t s) {
 #define DISPATCH_CHUNK 1024      // slots per histogram / ranking block
 #define GATE_BLOCK_TOKENS 32     // tokens per block of the fused gate kernel
 #define RT_SUPER 16              // gate blocks per super-block of the routed dispatch
+#define RT_TOT_STRIDE 32         // ints between the grand totals of two experts (one line each)
 
 // Lanes of the wavefront holding the same value as this lane (value in [0,256) or -1 for
 // "none"): one ballot per bit of the value, no loop over the distinct values.

@@ -172,8 +172,8 @@ __global__ __launch_bounds__(256) void route_select_kernel(const float* __restri
 // holds anyway: the stable rank of every slot among the block's slots of the same expert
 // (ballots inside a wavefront, an LDS table across the 8 wavefronts), the block's expert
 // histogram, and that histogram added (integer atomics: order-independent) to the sums of
-// the block's super-block of 16; the first block of a super-block clears the super-block's
-// sums in the other buffer, for the next call.
+// the block's super-block of 16 and to the grand totals; the first block of a super-block
+// clears the super-block's sums in the other buffer (block 0 also its totals), for the next call.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 constexpr int GATE_TOK = GATE_BLOCK_TOKENS;    // tokens per block
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
     const float* __restrict__ bias, int T, int E, int d, int k, int renormalize,
     float* __restrict__ logits_out, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     int ebits, int32_t* __restrict__ rt_rank, int32_t* __restrict__ rt_hist,
-    int32_t* __restrict__ super_acc, int32_t* __restrict__ super_clear) {
+    int32_t* __restrict__ super_acc, int32_t* __restrict__ super_clear, int tot_off) {
   constexpr int EG = 16 * NEB;                     // experts per pass over the token rows
   constexpr int EP = W * VPL < 64 ? 64 : W * VPL;  // expert slots kept in LDS
   __shared__ float part[GATE_WAVES][GATE_TOK][EG + 1];
@@ -285,8 +285,15 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
       for (int w8 = 0; w8 < GATE_WAVES; ++w8) n += wcnt[w8 * MOE_MAX_EXPERTS + tid];
       rt_hist[(size_t)blockIdx.x * E + tid] = n;
       const size_t sup = (size_t)(blockIdx.x / RT_SUPER) * E + tid;
-      if (n != 0) atomicAdd(&super_acc[sup], n);
+      // grand totals: after the super-block rows, one 128-byte line per expert so that the
+      // atomics of all blocks spread over the memory channels
+      const size_t tot = (size_t)tot_off + (size_t)tid * RT_TOT_STRIDE;
+      if (n != 0) {
+        atomicAdd(&super_acc[sup], n);
+        atomicAdd(&super_acc[tot], n);
+      }
       if (blockIdx.x % RT_SUPER == 0) super_clear[sup] = 0;
+      if (blockIdx.x == 0) super_clear[tot] = 0;
     }
   }
 }
@@ -309,17 +316,18 @@ int launch_gate(const moe_ctx* c, const void* x, const void* Wg, const float* bi
   if (keep_hist) {
     int ebits = 0;
     while ((1 << ebits) < c->cfg.E) ++ebits;
-    const size_t half = (size_t)c->rt_super_max * c->cfg.E;
+    const size_t half = (size_t)c->rt_super_max * c->cfg.E + (size_t)c->cfg.E * RT_TOT_STRIDE;
     hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, true>), dim3(grid),
                        dim3(64 * GATE_WAVES), 0, s, (const uint16_t*)x, (const uint16_t*)Wg, bias, T,
                        c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, ebits,
                        c->d_rt_rank, c->d_rt_hist, c->d_rt_super + (size_t)c->rt_parity * half,
-                       c->d_rt_super + (size_t)(c->rt_parity ^ 1) * half);
+                       c->d_rt_super + (size_t)(c->rt_parity ^ 1) * half,
+                       c->rt_super_max * c->cfg.E);
   } else {
     hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, false>), dim3(grid),
                        dim3(64 * GATE_WAVES), 0, s, (const uint16_t*)x, (const uint16_t*)Wg, bias, T,
                        c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, 0, nullptr,
-                       nullptr, nullptr, nullptr);
+                       nullptr, nullptr, nullptr, 0);
   }
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
