@@ -7,14 +7,25 @@
 //   decode: expert' = shared + scattered residual, one pass.
 //
 // The selection is exact.  The magnitude of a float32 is monotone in its low 31 bits, so the
-// k-th largest magnitude is found by a radix select over that 31-bit key: three histogram
-// passes (12 + 12 + 7 bits, LDS-private histograms added to 16 global copies with integer
-// atomics, so the result does not depend on the order), each followed by a one-block kernel
-// that picks the bin holding the k-th largest.  A fourth pass counts, per chunk of 8192
-// elements, the keys above the threshold and the keys equal to it; a one-block scan turns
-// the counts into output positions (of the equal keys only the first k - #above in index
-// order are taken); a fifth pass writes the list.  Every pass re-reads expert and shared
-// (2 x 5 reads per element): the kernels are HBM-bound, nothing but the output is written.
+// k-th largest magnitude is found by a radix select over that 31-bit key (12 + 12 + 7 bits;
+// LDS-private histograms added to 16 global copies with integer atomics, so the result does
+// not depend on the order; after each level a one-block kernel picks the bin holding the
+// k-th largest).  Expert and shared are streamed TWICE:
+//   1. histogram of the top 12 key bits -> the bin b0 of the k-th largest;
+//   2. every element whose top bits are >= b0 (the entries certainly kept plus the candidates
+//      of bin b0: a few per cent of the matrix) is appended, as (residual bits, index), to a
+//      list in the workspace: one contiguous run per chunk of 8192 elements, in index order
+//      inside the run; every block of that pass owns a fixed region of the list and appends
+//      the runs of its chunks there (no atomics; every later step goes through the per-chunk
+//      table of runs).
+// The two lower radix levels, the per-chunk counts of entries above / equal to the threshold,
+// and the emit of the value-index list then read only that list (a few MB).  A one-block scan
+// turns the counts into output positions (of the equal keys the first k - #above in index
+// order are taken), so the output is deterministic.
+// When a block's runs do not fit its region (the list has room for 1/16 of the elements: many
+// equal magnitudes, or k a large fraction of n) the second pass says so in a flag, and the
+// later kernels stream expert and shared again instead of reading the list (three more
+// streams + emit): every kernel after the second pass has both sources.
 #include "moe_internal.h"
 #include "numeric.h"
 
@@ -28,10 +39,21 @@ constexpr int SR_CHUNK = SR_THREADS * SR_PER_THREAD;  // 8192 elements per block
 constexpr int SR_BINS = 4096;
 constexpr int SR_REPL = 16;   // copies of the global histogram (fewer same-address atomics)
 
-struct SrState {          // device-side selection state
+struct SrState {          // device-side selection state (first 8 ints of the workspace)
   uint32_t prefix;        // key bits fixed so far (right-aligned)
   int32_t k_rem;          // entries still to take among the keys that match the prefix
+  int32_t pad[2];
+  uint32_t unused;
+  int32_t overflow;       // 1: the list did not fit, the later passes stream the matrices
+  int32_t pad2[2];
 };
+constexpr int SR_STATE_INTS = 8;
+
+// capacity of the candidate list, in entries of 8 bytes
+__host__ __device__ inline int64_t sr_list_cap(int64_t n) {
+  const int64_t c = n / 16;
+  return c < 65536 ? 65536 : c;
+}
 
 template <typename T>
 __device__ __forceinline__ uint32_t sr_key(T w, T s, float* r) {
@@ -81,33 +103,43 @@ struct SrLane {
 };
 
 // PASS 0: bin = key[30:19];  PASS 1: keys with key[30:19] == prefix, bin = key[18:7];
-// PASS 2: keys with key[30:7] == prefix, bin = key[6:0].
+// PASS 2: keys with key[30:7] == prefix, bin = key[6:0].  Passes 1 and 2 read the candidate
+// list (a wavefront per run) unless it overflowed.
 template <typename T, int PASS>
-__global__ __launch_bounds__(SR_THREADS) void sr_hist_kernel(const T* __restrict__ W,
-                                                             const T* __restrict__ S, int64_t n,
-                                                             const SrState* __restrict__ st,
-                                                             int32_t* __restrict__ hist) {
+__global__ __launch_bounds__(SR_THREADS) void sr_hist_kernel(
+    const T* __restrict__ W, const T* __restrict__ S, int64_t n, const SrState* __restrict__ st,
+    int32_t* __restrict__ hist, const uint2* __restrict__ list,
+    const int32_t* __restrict__ run_start, const int32_t* __restrict__ run_cnt) {
   __shared__ int32_t h[SR_BINS];
-  for (int i = threadIdx.x; i < SR_BINS; i += SR_THREADS) h[i] = 0;
+  constexpr int NB = PASS == 2 ? 128 : SR_BINS;
+  for (int i = threadIdx.x; i < NB; i += SR_THREADS) h[i] = 0;
   __syncthreads();
   const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
   const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
-  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-    SrLane<T> L;
-    L.load(W, S, c * SR_CHUNK + (int64_t)threadIdx.x * SR_PER_THREAD, n);
+  auto add = [&](uint32_t key, bool hit) {
+    int bin;
+    if (PASS == 0) bin = key >> 19;
+    else if (PASS == 1) { hit = hit && (key >> 19) == prefix; bin = (key >> 7) & 0xfffu; }
+    else { hit = hit && (key >> 7) == prefix; bin = key & 0x7fu; }
+    if (hit) atomicAdd(&h[bin], 1);
+  };
+  if (PASS != 0 && !st->overflow) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int WPB = SR_THREADS / 64;
+    for (int64_t c = (int64_t)blockIdx.x * WPB + wave; c < n_chunks; c += (int64_t)gridDim.x * WPB) {
+      const uint2* run = list + run_start[c];
+      const int cnt = run_cnt[c];
+      for (int i = lane; i < cnt; i += 64) add(run[i].x & 0x7fffffffu, true);
+    }
+  } else {
+    for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+      SrLane<T> L;
+      L.load(W, S, c * SR_CHUNK + (int64_t)threadIdx.x * SR_PER_THREAD, n);
 #pragma unroll
-    for (int j = 0; j < SR_PER_THREAD; ++j) {
-      const uint32_t key = L.key[j];
-      bool hit = j < L.cnt;
-      int bin;
-      if (PASS == 0) bin = key >> 19;
-      else if (PASS == 1) { hit = hit && (key >> 19) == prefix; bin = (key >> 7) & 0xfffu; }
-      else { hit = hit && (key >> 7) == prefix; bin = key & 0x7fu; }
-      if (hit) atomicAdd(&h[bin], 1);
+      for (int j = 0; j < SR_PER_THREAD; ++j) add(L.key[j], j < L.cnt);
     }
   }
   __syncthreads();
-  constexpr int NB = PASS == 2 ? 128 : SR_BINS;
   int32_t* mine = hist + (blockIdx.x % SR_REPL) * SR_BINS;
   for (int i = threadIdx.x; i < NB; i += SR_THREADS)
     if (h[i] != 0) atomicAdd(&mine[i], h[i]);
@@ -160,20 +192,44 @@ __global__ __launch_bounds__(1024) void sr_pick_kernel(SrState* __restrict__ st,
       st->prefix = (prefix << BITS) | (uint32_t)b;
       st->k_rem = k_rem - suf[b + 1];
     }
+  if (PASS == 0 && tid == 0) st->overflow = 0;   // the second stream sets it when the list is full
   for (int b = tid; b < SR_REPL * SR_BINS; b += 1024) hist[b] = 0;
 }
 
-// Per chunk: keys above the threshold, keys equal to it.
+// Per chunk: keys above the threshold, keys equal to it; from the chunk's run of the list (a
+// wavefront per run) or, after an overflow, from the matrices (a block per chunk).
 template <typename T>
-__global__ __launch_bounds__(SR_THREADS) void sr_count_kernel(const T* __restrict__ W,
-                                                              const T* __restrict__ S, int64_t n,
-                                                              const SrState* __restrict__ st,
-                                                              int32_t* __restrict__ cnt_gt,
-                                                              int32_t* __restrict__ cnt_eq) {
+__global__ __launch_bounds__(SR_THREADS) void sr_count_kernel(
+    const T* __restrict__ W, const T* __restrict__ S, int64_t n, const SrState* __restrict__ st,
+    int32_t* __restrict__ cnt_gt, int32_t* __restrict__ cnt_eq, const uint2* __restrict__ list,
+    const int32_t* __restrict__ run_start, const int32_t* __restrict__ run_cnt) {
   __shared__ int32_t red[2][SR_THREADS / 64];
   const uint32_t thr = st->prefix;
   const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (!st->overflow) {
+    constexpr int WPB = SR_THREADS / 64;
+    for (int64_t c = (int64_t)blockIdx.x * WPB + wave; c < n_chunks; c += (int64_t)gridDim.x * WPB) {
+      const uint2* run = list + run_start[c];
+      const int cnt = run_cnt[c];
+      int gt = 0, eq = 0;
+      for (int i = lane; i < cnt; i += 64) {
+        const uint32_t key = run[i].x & 0x7fffffffu;
+        gt += key > thr;
+        eq += key == thr;
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        gt += __shfl_xor(gt, off, 64);
+        eq += __shfl_xor(eq, off, 64);
+      }
+      if (lane == 0) {
+        cnt_gt[c] = gt;
+        cnt_eq[c] = eq;
+      }
+    }
+    return;
+  }
   for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
     SrLane<T> L;
     L.load(W, S, c * SR_CHUNK + (int64_t)threadIdx.x * SR_PER_THREAD, n);
@@ -210,47 +266,61 @@ __global__ __launch_bounds__(SR_THREADS) void sr_count_kernel(const T* __restric
 
 // One block: exclusive prefix of the equal-key counts, entries each chunk emits (all of its
 // keys above the threshold plus its share of the first k_rem equal keys), exclusive prefix
-// of those.  Every thread owns a contiguous run of chunks; the runs are chained by two
-// block-wide scans of the per-thread totals.
+// of those.  Rounds of 1024 consecutive chunks (coalesced loads), a block-wide exclusive scan
+// per quantity and round (shuffles inside a wavefront, the 16 wavefront totals through LDS),
+// the totals carried from round to round.
 __global__ __launch_bounds__(1024) void sr_scan_kernel(const SrState* __restrict__ st,
                                                        const int32_t* __restrict__ cnt_gt,
                                                        const int32_t* __restrict__ cnt_eq,
                                                        int64_t n_chunks,
                                                        int32_t* __restrict__ eq_prefix,
                                                        int32_t* __restrict__ out_prefix) {
-  __shared__ int32_t sc[1024];
-  const int tid = threadIdx.x;
-  const int64_t per = (n_chunks + 1023) / 1024;
-  const int64_t c0 = min(n_chunks, tid * per), c1 = min(n_chunks, c0 + per);
+  __shared__ int32_t wtot[2][16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t need_eq = st->k_rem;
-  auto excl_scan = [&](int v) -> int {   // exclusive prefix of v over the block
-    sc[tid] = v;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-      int t = 0;
-      if (tid >= off) t = sc[tid - off];
-      __syncthreads();
-      sc[tid] += t;
-      __syncthreads();
+  int slot = 0;   // the two LDS rows alternate, so one barrier per scan is enough
+  auto excl_scan = [&](int v, int* total) -> int {   // exclusive prefix of v over the block
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += t;
     }
-    const int r = sc[tid] - v;
+    if (lane == 63) wtot[slot][wave] = incl;
     __syncthreads();
-    return r;
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+      const int t = wtot[slot][w];
+      before += w < wave ? t : 0;
+      all += t;
+    }
+    slot ^= 1;
+    *total = all;
+    return before + incl - v;
   };
-  int eq_sum = 0;
-  for (int64_t c = c0; c < c1; ++c) eq_sum += cnt_eq[c];
-  int eq_before = excl_scan(eq_sum);
-  int take_sum = 0;
-  for (int64_t c = c0; c < c1; ++c) {
-    const int eq = cnt_eq[c];
-    eq_prefix[c] = eq_before;
-    take_sum += cnt_gt[c] + max(0, min(eq, need_eq - eq_before));
-    eq_before += eq;
-  }
-  int out_before = excl_scan(take_sum);
-  for (int64_t c = c0; c < c1; ++c) {
-    out_prefix[c] = out_before;
-    out_before += cnt_gt[c] + max(0, min(cnt_eq[c], need_eq - eq_prefix[c]));
+  int eq_carry = 0, out_carry = 0;
+  int eq_next = tid < n_chunks ? cnt_eq[tid] : 0, gt_next = tid < n_chunks ? cnt_gt[tid] : 0;
+  for (int64_t c0 = 0; c0 < n_chunks; c0 += 1024) {
+    const int64_t c = c0 + tid;
+    const bool live = c < n_chunks;
+    const int eq = eq_next, gt = gt_next;
+    if (c + 1024 < n_chunks) {   // the next round's counts are fetched under this round's scans
+      eq_next = cnt_eq[c + 1024];
+      gt_next = cnt_gt[c + 1024];
+    } else {
+      eq_next = gt_next = 0;
+    }
+    int eq_all, take_all;
+    const int eq_before = eq_carry + excl_scan(eq, &eq_all);
+    const int take = gt + max(0, min(eq, need_eq - eq_before));
+    const int out_before = out_carry + excl_scan(take, &take_all);
+    if (live) {
+      eq_prefix[c] = eq_before;
+      out_prefix[c] = out_before;
+    }
+    eq_carry += eq_all;
+    out_carry += take_all;
   }
 }
 
@@ -260,12 +330,42 @@ template <typename T>
 __global__ __launch_bounds__(SR_THREADS) void sr_emit_kernel(
     const T* __restrict__ W, const T* __restrict__ S, int64_t n, const SrState* __restrict__ st,
     const int32_t* __restrict__ eq_prefix, const int32_t* __restrict__ out_prefix, int64_t k,
-    T* __restrict__ values, int32_t* __restrict__ indices) {
+    T* __restrict__ values, int32_t* __restrict__ indices, const uint2* __restrict__ list,
+    const int32_t* __restrict__ run_start, const int32_t* __restrict__ run_cnt) {
   __shared__ int32_t wsum[2][SR_THREADS / 64];
   const uint32_t thr = st->prefix;
   const int32_t need_eq = st->k_rem;
   const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (!st->overflow) {
+    // from the list: a wavefront per run, 64 entries per round, ranks by ballot (lane order
+    // = index order)
+    constexpr int WPB = SR_THREADS / 64;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int64_t c = (int64_t)blockIdx.x * WPB + wave; c < n_chunks; c += (int64_t)gridDim.x * WPB) {
+      const uint2* run = list + run_start[c];
+      const int cnt = run_cnt[c];
+      int eq_rank = eq_prefix[c];
+      int64_t pos = out_prefix[c];
+      for (int i0 = 0; i0 < cnt; i0 += 64) {
+        const bool valid = i0 + lane < cnt;
+        const uint2 en = valid ? run[i0 + lane] : make_uint2(0u, 0u);
+        const uint32_t key = en.x & 0x7fffffffu;
+        const bool iseq = valid && key == thr;
+        const unsigned long long eqm = __ballot(iseq);
+        const bool sel = valid && (key > thr || (iseq && eq_rank + __popcll(eqm & below) < need_eq));
+        const unsigned long long sm = __ballot(sel);
+        const int64_t p = pos + __popcll(sm & below);
+        if (sel && p < k) {   // p < k always holds when the counts are consistent
+          values[p] = from_f32<T>(__uint_as_float(en.x));
+          indices[p] = (int32_t)en.y;
+        }
+        eq_rank += __popcll(eqm);
+        pos += __popcll(sm);
+      }
+    }
+    return;
+  }
   for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
     const int64_t base = c * SR_CHUNK + (int64_t)threadIdx.x * SR_PER_THREAD;
     SrLane<T> L;
@@ -321,6 +421,60 @@ __global__ __launch_bounds__(SR_THREADS) void sr_emit_kernel(
         }
         ++pos;
       }
+    __syncthreads();
+  }
+}
+
+// ---- second stream: the entries whose top 12 key bits reach the bin of the k-th largest go
+// to the list, one run per chunk (index order inside the run).  Block b appends the runs of
+// its chunks to its own region [b * region, (b + 1) * region) of the list.
+template <typename T>
+__global__ __launch_bounds__(SR_THREADS) void sr_compact_kernel(
+    const T* __restrict__ W, const T* __restrict__ S, int64_t n, SrState* __restrict__ st,
+    int64_t region, uint2* __restrict__ list, int32_t* __restrict__ run_start,
+    int32_t* __restrict__ run_cnt) {
+  __shared__ int32_t wsum[SR_THREADS / 64];
+  const uint32_t b0 = st->prefix;
+  const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int64_t used = 0;   // entries of this block's region in use (the same in every thread)
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const int64_t base = c * SR_CHUNK + (int64_t)threadIdx.x * SR_PER_THREAD;
+    SrLane<T> L;
+    L.load(W, S, base, n);
+    uint32_t sel = 0;
+#pragma unroll
+    for (int j = 0; j < SR_PER_THREAD; ++j)
+      if (j < L.cnt && (L.key[j] >> 19) >= b0) sel |= 1u << j;
+    const int mine = __popc(sel);
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int v = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += v;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int before = incl - mine, total = 0;
+#pragma unroll
+    for (int w = 0; w < SR_THREADS / 64; ++w) {
+      before += w < wave ? wsum[w] : 0;
+      total += wsum[w];
+    }
+    const bool fits = used + total <= region;
+    const int64_t run0 = (int64_t)blockIdx.x * region + used;
+    if (threadIdx.x == 0) {
+      run_start[c] = fits ? (int32_t)run0 : 0;
+      run_cnt[c] = fits ? total : 0;
+      if (!fits) st->overflow = 1;
+    }
+    if (fits) {
+      uint2* p = list + run0 + before;
+#pragma unroll
+      for (int j = 0; j < SR_PER_THREAD; ++j)
+        if ((sel >> j) & 1u) *p++ = make_uint2(__float_as_uint(L.r[j]), (uint32_t)(base + j));
+      used += total;
+    }
     __syncthreads();
   }
 }
@@ -407,27 +561,34 @@ template <typename T>
 int encode_t(moe_ctx* c, const T* W, const T* S, int64_t n, int64_t k, T* values, int32_t* indices,
              hipStream_t s) {
   const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
+  const int64_t nc2 = (n_chunks + 1) & ~(int64_t)1;   // keeps the list 8-byte aligned
   const int grid = (int)std::min<int64_t>(n_chunks, (int64_t)c->n_cu * 8);
   SrState* st = reinterpret_cast<SrState*>(c->d_sr_ws);
-  int32_t* hist = c->d_sr_ws + 4;
+  int32_t* hist = c->d_sr_ws + SR_STATE_INTS;
   int32_t* cnt_gt = hist + SR_REPL * SR_BINS;
-  int32_t* cnt_eq = cnt_gt + n_chunks;
-  int32_t* eq_prefix = cnt_eq + n_chunks;
-  int32_t* out_prefix = eq_prefix + n_chunks;
+  int32_t* cnt_eq = cnt_gt + nc2;
+  int32_t* eq_prefix = cnt_eq + nc2;
+  int32_t* out_prefix = eq_prefix + nc2;
+  int32_t* run_start = out_prefix + nc2;
+  int32_t* run_cnt = run_start + nc2;
+  uint2* list = reinterpret_cast<uint2*>(run_cnt + nc2);
   // the histogram is zero on entry: cleared at allocation and by every pick kernel
   const int hgrid = (int)std::min<int64_t>(n_chunks, (int64_t)c->n_cu * 2);
-  hipLaunchKernelGGL((sr_hist_kernel<T, 0>), dim3(hgrid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
-  hipLaunchKernelGGL((sr_pick_kernel<0>), dim3(1), dim3(1024), 0, s, st, hist, (int32_t)k);
-  hipLaunchKernelGGL((sr_hist_kernel<T, 1>), dim3(hgrid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
-  hipLaunchKernelGGL((sr_pick_kernel<1>), dim3(1), dim3(1024), 0, s, st, hist, (int32_t)k);
-  hipLaunchKernelGGL((sr_hist_kernel<T, 2>), dim3(hgrid), dim3(SR_THREADS), 0, s, W, S, n, st, hist);
-  hipLaunchKernelGGL((sr_pick_kernel<2>), dim3(1), dim3(1024), 0, s, st, hist, (int32_t)k);
-  hipLaunchKernelGGL((sr_count_kernel<T>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, cnt_gt,
-                     cnt_eq);
-  hipLaunchKernelGGL(sr_scan_kernel, dim3(1), dim3(1024), 0, s, st, cnt_gt, cnt_eq, n_chunks,
-                     eq_prefix, out_prefix);
-  hipLaunchKernelGGL((sr_emit_kernel<T>), dim3(grid), dim3(SR_THREADS), 0, s, W, S, n, st, eq_prefix,
-                     out_prefix, k, values, indices);
+  const int64_t region = sr_list_cap(n) / hgrid;   // list entries per block of the second stream
+#define SR_LAUNCH(kern, g, b, ...) hipLaunchKernelGGL(kern, dim3(g), dim3(b), 0, s, __VA_ARGS__)
+  SR_LAUNCH((sr_hist_kernel<T, 0>), hgrid, SR_THREADS, W, S, n, st, hist, list, run_start, run_cnt);
+  SR_LAUNCH((sr_pick_kernel<0>), 1, 1024, st, hist, (int32_t)k);
+  SR_LAUNCH((sr_compact_kernel<T>), hgrid, SR_THREADS, W, S, n, st, region, list, run_start, run_cnt);
+  SR_LAUNCH((sr_hist_kernel<T, 1>), hgrid, SR_THREADS, W, S, n, st, hist, list, run_start, run_cnt);
+  SR_LAUNCH((sr_pick_kernel<1>), 1, 1024, st, hist, (int32_t)k);
+  SR_LAUNCH((sr_hist_kernel<T, 2>), hgrid, SR_THREADS, W, S, n, st, hist, list, run_start, run_cnt);
+  SR_LAUNCH((sr_pick_kernel<2>), 1, 1024, st, hist, (int32_t)k);
+  SR_LAUNCH((sr_count_kernel<T>), grid, SR_THREADS, W, S, n, st, cnt_gt, cnt_eq, list, run_start,
+            run_cnt);
+  SR_LAUNCH(sr_scan_kernel, 1, 1024, st, cnt_gt, cnt_eq, n_chunks, eq_prefix, out_prefix);
+  SR_LAUNCH((sr_emit_kernel<T>), grid, SR_THREADS, W, S, n, st, eq_prefix, out_prefix, k, values,
+            indices, list, run_start, run_cnt);
+#undef SR_LAUNCH
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 
@@ -435,7 +596,9 @@ int encode_t(moe_ctx* c, const T* W, const T* S, int64_t n, int64_t k, T* values
 
 size_t sr_workspace_ints(int64_t n) {
   const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
-  return (size_t)(4 + SR_REPL * SR_BINS + 4 * n_chunks);
+  const int64_t nc2 = (n_chunks + 1) & ~(int64_t)1;
+  // state, histograms, six per-chunk arrays, the candidate list (8 bytes per entry)
+  return (size_t)(SR_STATE_INTS + SR_REPL * SR_BINS + 6 * nc2 + 2 * sr_list_cap(n));
 }
 
 int launch_sr_encode(moe_ctx* c, const void* W, const void* S, int64_t n, int64_t k, void* values,
