@@ -209,10 +209,16 @@ struct Unit {
   int ws_unit;              // >= 0: K-split part, index of its partial tile in the workspace
 };
 
-// The idx-th unit of this block.  Tiled modes: XCD x (= blockIdx & 7, the hardware deals
-// blocks round-robin to the XCDs) owns a contiguous range of the tile order and, after it,
-// a contiguous range of the K-split units of the tail; its gridDim/8 blocks take them in
-// turn.  The sequence of a block is dense: once a unit is invalid, all later ones are.
+// The idx-th unit of this block.  The hardware deals blocks round-robin to the XCDs: XCD x
+// (= blockIdx & 7) holds the blocks x, x + 8, ...  The tile order is walked in rounds of
+// gridDim tiles; a round is cut into 8 chunks of consecutive tiles (32 in a full round: 8 row
+// blocks x 4 column blocks that share 12 panels), chunk x goes to XCD x, one tile per block:
+// at any time an XCD works on one chunk.  The last, partial round is cut into 8 equal chunks as
+// well, so that every XCD stays in use.  Going round by round (rather than giving an XCD a
+// contiguous eighth of the whole order) spreads the cheap tiles of short row blocks -- which
+// come in runs -- over all XCDs.  After its whole tiles a block takes its share of the
+// K-split units of the tail (a contiguous range per XCD).  The sequence of a block is dense:
+// once a unit is invalid, all later ones are.
 template <int MODE, bool BKM>
 __device__ __forceinline__ Unit fetch_unit(const GemmArgs& p, int idx) {
   Unit u;
@@ -222,18 +228,22 @@ __device__ __forceinline__ Unit fetch_unit(const GemmArgs& p, int idx) {
   const int n_full = MODE == MODE_DOWN ? p.sched->down_full : total;
   const int split = MODE == MODE_DOWN ? p.sched->down_split : 1;
   const int n_units = MODE == MODE_DOWN ? p.sched->down_split_tiles * split : 0;
-  const int per_xcd = (n_full + 7) >> 3, per_xcd_s = (n_units + 7) >> 3;
-  const int x = blockIdx.x & 7;
-  const int nf = max(0, min(per_xcd, n_full - x * per_xcd));
+  const int per_xcd_s = (n_units + 7) >> 3;
+  const int x = blockIdx.x & 7, slot = (int)(blockIdx.x >> 3);
+  const int G = (int)gridDim.x, gsz = G >> 3;
+  const int rfull = n_full / G, m_last = n_full - rfull * G;   // full rounds, tiles of the last one
+  const int per_last = (m_last + 7) >> 3;
+  const bool in_last = slot < per_last && x * per_last + slot < m_last;
+  const int nfu = rfull + (in_last ? 1 : 0);
   const int ns = max(0, min(per_xcd_s, n_units - x * per_xcd_s));
-  const int q = (int)(blockIdx.x >> 3) + idx * (int)(gridDim.x >> 3);
-  if (q >= nf + ns) return u;
   int L, part = 0, kstart = 0;   // kstart: first k-step of a K-split part
-  if (q < nf) {
-    L = x * per_xcd + q;
+  if (idx < nfu) {
+    L = idx < rfull ? idx * G + x * gsz + slot : rfull * G + x * per_last + slot;
     u.KT = p.K / BK;
   } else {
-    const int su = x * per_xcd_s + (q - nf);
+    const int qs = slot + (idx - nfu) * gsz;   // among the XCD's split units
+    if (qs >= ns) return u;
+    const int su = x * per_xcd_s + qs;
     L = n_full + su / split;
     part = su % split;
     // pairs of k-steps of this part: the first `rem` parts take one pair more
@@ -271,7 +281,8 @@ __device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][
                                            const uint4* lds, const int (&fr_a)[4],
                                            const int (&fr_b)[2], int fr_half, int fr_swz,
                                            uint32_t offa, const char* basea, uint32_t offb,
-                                           const char* baseb, uint32_t a_dst, uint32_t b_dst) {
+                                           const char* baseb, uint32_t a_dst, uint32_t b_dst,
+                                           int nact) {
   const uint4* As = lds + (2 * S) * STAGE_VEC;
   const uint4* Bs = lds + (2 * S + 1) * STAGE_VEC;
   bf16x8 xa[4];
@@ -294,9 +305,15 @@ __device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][
         }
       }
   }
+  // nact (wave-uniform): 32-row blocks of this wavefront's half of the tile that hold rows;
+  // the others are neither read nor multiplied (their accumulators stay zero and are not
+  // stored), the copies and barriers go on as ever
+  const bool act = I < nact;
+  if (act) {
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
-    xa[kk] = __builtin_bit_cast(bf16x8, As[fr_a[I] + ((kk * 2 + fr_half) ^ fr_swz)]);
+    for (int kk = 0; kk < 4; ++kk)
+      xa[kk] = __builtin_bit_cast(bf16x8, As[fr_a[I] + ((kk * 2 + fr_half) ^ fr_swz)]);
+  }
   constexpr int blk = (I + 3) & 3;
   constexpr int st = I == 0 ? (S ^ 1) : S;
   dma16(offa, basea, a_dst + st * 65536 + blk * 4096);
@@ -309,11 +326,13 @@ __device__ __forceinline__ void pp_cluster(f32x16 (&acc)[2][4], bf16x8 (&wb)[2][
   asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   __builtin_amdgcn_sched_barrier(0);
   __builtin_amdgcn_s_setprio(1);
+  if (act) {
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
+    for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      acc[j][I] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[j][kk], xa[kk], acc[j][I], 0, 0, 0);
+      for (int j = 0; j < 2; ++j)
+        acc[j][I] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[j][kk], xa[kk], acc[j][I], 0, 0, 0);
+  }
   __builtin_amdgcn_s_setprio(0);
   __builtin_amdgcn_sched_barrier(0);
   asm volatile("s_barrier" ::: "memory");
@@ -583,13 +602,14 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
     const Unit nxt = fetch_unit<MODE, BKM>(p, idx + 1);
     zero_acc();
     const int KT = cur.KT;
+    const int nact = __builtin_amdgcn_readfirstlane(min(4, max(0, (cur.rows - wm * 128 + 31) >> 5)));
     // steady part: steps 0 .. KT-3; what was read one cluster ago is refilled with the data
     // of its next use (token block i-1 and weight row blocks 8(i-1)+wave of this stage with
     // step k+2; at i == 0 block 3 of the other stage with step k+1)
     for (int kt = 0; kt < KT - 2; kt += 2) {
       const char* a1 = cur.abase + (kt + 1) * 128;  // step kt+1 (+128: kt+2, +256: kt+3)
 #define PP(S, I, OA, BA, OB, BB) \
-  pp_cluster<S, I, BKM>(acc, wb, lds, fr_a, fr_b, fr_half, fr_swz, OA, BA, OB, BB, a_dst, b_dst)
+  pp_cluster<S, I, BKM>(acc, wb, lds, fr_a, fr_b, fr_half, fr_swz, OA, BA, OB, BB, a_dst, b_dst, nact)
       PP(0, 0, a_off[3], a1, b_off[3], bsrc(cur, kt + 1, 1));
       PP(0, 1, a_off[0], a1 + 128, b_off[0], bsrc(cur, kt + 2, 0));
       PP(0, 2, a_off[1], a1 + 128, b_off[1], bsrc(cur, kt + 2, 0));
