@@ -658,7 +658,7 @@ __global__ __launch_bounds__(NT) void ffn_mfma_kernel(const GemmArgs p) {
 // deterministic) and stores the tile like the GEMM's own epilogue.  Eight blocks per split
 // tile, one per accumulator (j, i) of the GEMM's wavefront tile; thread and accumulator
 // indices mean what they mean in ffn_mfma_kernel.  All parts of a quad are loaded before
-// they are added (up to 8 loads in flight per quad).
+// they are added.
 __global__ __launch_bounds__(NT) void ffn_split_reduce_kernel(const GemmArgs p) {
   const int n_tiles = p.sched->down_split_tiles;
   const int tile = blockIdx.x >> 3, ji = blockIdx.x & 7;
@@ -675,16 +675,21 @@ __global__ __launch_bounds__(NT) void ffn_split_reduce_kernel(const GemmArgs p) 
   const bool live = m_local < tl.rows;
   const size_t row = (size_t)(tl.row0 + m_local);
   const int col0 = tl.nblk * 256 + j * 128 + wn * 32 + 4 * fr_half;
+  // every part of all four quads is requested before anything is added (up to 32 loads of
+  // 16 bytes in flight per thread: with one quad at a time the kernel was bound by four
+  // memory latencies in a row)
+  float4 part[4][8];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    float4 part[8];
+  for (int q = 0; q < 4; ++q)
 #pragma unroll
     for (int pt = 0; pt < 8; ++pt)
-      part[pt] = pt < split ? ws[(size_t)pt * (32 * NT) + q * NT] : make_float4(0.f, 0.f, 0.f, 0.f);
-    float4 v = part[0];
+      part[q][pt] = pt < split ? ws[(size_t)pt * (32 * NT) + q * NT] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    float4 v = part[q][0];
 #pragma unroll
     for (int pt = 1; pt < 8; ++pt) {
-      v.x += part[pt].x; v.y += part[pt].y; v.z += part[pt].z; v.w += part[pt].w;
+      v.x += part[q][pt].x; v.y += part[q][pt].y; v.z += part[q][pt].z; v.w += part[q][pt].w;
     }
     if (live)
       *reinterpret_cast<uint2*>(p.C + row * p.N + col0 + 8 * q) =
