@@ -53,6 +53,39 @@ def test_null_arguments_are_rejected_without_a_context():
     assert lib.moe_route_logits(None, None, 4, None, None, None) == -1
     assert lib.moe_dispatch(None, None, None, 4, None, None, None, None, None, None, None, None) == -1
     assert lib.moe_destroy(None) == 0
+    assert lib.moe_dispatch_routed(None, None, None, 4, None, None, None, None, None, None, None,
+                                   None) == -1
+
+
+def test_context_free_entry_points_validate_on_the_host():
+    """moe_dispatch_noalloc and the measurement aids take no context: bad arguments are
+    refused before anything touches the device."""
+    lib = moe.load_library()
+    good = moe.MoEConfigC(0, 64, 8, 2, 0, 2, 0, moe.MOE_BF16, 1)
+    p = ctypes.c_void_p(64)                       # any aligned non-NULL address: never dereferenced
+    args = lambda cfg, dest, T: (cfg, dest, None, p, T, None, p, p, p, p, p, p, None)
+    assert lib.moe_dispatch_noalloc(*args(None, p, 4)) == -1
+    assert lib.moe_dispatch_noalloc(*args(ctypes.byref(good), None, 4)) == -1
+    assert lib.moe_dispatch_noalloc(*args(ctypes.byref(good), p, -1)) == -1
+    for bad in (dict(E=0), dict(E=257), dict(k=3, E=2), dict(k=17, E=32), dict(R=0), dict(R=257),
+                dict(d=12), dict(dtype=5)):
+        kw = dict(T_max=0, d=64, E=8, k=2, f=0, R=2, local_rank=0, dtype=moe.MOE_BF16, renormalize=1)
+        kw.update(bad)
+        cfg = moe.MoEConfigC(*[kw[n] for n, _ in moe.MoEConfigC._fields_])
+        assert lib.moe_dispatch_noalloc(*args(ctypes.byref(cfg), p, 4)) == -1, bad
+    # beyond the static workspace: ceil(T*k/1024) * E > MOE_NOALLOC_MAX_HIST
+    big = moe.MoEConfigC(0, 64, 256, 2, 0, 2, 0, moe.MOE_BF16, 1)
+    assert lib.moe_dispatch_noalloc(*args(ctypes.byref(big), p, 600000)) == -2
+    assert lib.moe_dispatch_noalloc(*args(ctypes.byref(big), p, 1 << 22)) == -2     # T*k > 2^22
+    # x and x_packed must come together; misaligned pointers
+    assert lib.moe_dispatch_noalloc(ctypes.byref(good), p, p, p, 4, None, p, p, p, p, p, p, None) == -1
+    assert lib.moe_dispatch_noalloc(ctypes.byref(good), p, None, ctypes.c_void_p(68), 4, None, p, p,
+                                    p, p, p, p, None) == -1
+    assert lib.moe_measure_copy(None, p, 1024, 1, None) == -1
+    assert lib.moe_measure_copy(p, p, 1000, 1, None) == -1          # not a multiple of 16
+    assert lib.moe_measure_copy(p, p, 1024, 0, None) == -1
+    assert lib.moe_measure_mfma(None, 8, 8, 0, None, None) == -1
+    assert lib.moe_measure_mfma(p, 0, 8, 0, None, None) == -1
 
 
 def test_binding_has_no_cpu_fallback():
