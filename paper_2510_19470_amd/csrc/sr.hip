@@ -147,53 +147,56 @@ __global__ __launch_bounds__(SR_THREADS) void sr_hist_kernel(
 
 // One block: the bin b with  #(keys in bins > b) < k_rem <= #(keys in bins >= b)  is the one
 // that holds the k_rem-th largest key; it is appended to the prefix, k_rem loses the keys
-// above it, and the histogram is cleared for the next pass.
+// above it, and the histogram is cleared for the next pass.  A thread owns 4 consecutive bins
+// (16-byte loads of the 16 copies); the suffix sums over the 1024 threads are a reversed scan
+// inside each wavefront (shuffles) plus the 16 wavefront totals through LDS: one barrier.
 template <int PASS>
 __global__ __launch_bounds__(1024) void sr_pick_kernel(SrState* __restrict__ st,
                                                        int32_t* __restrict__ hist, int32_t k) {
   constexpr int NB = PASS == 2 ? 128 : SR_BINS;
   constexpr int BITS = PASS == 2 ? 7 : 12;
-  __shared__ int32_t suf[SR_BINS + 1];   // suf[b] = sum of hist[b..NB-1]
-  const int tid = threadIdx.x;
-  // each thread sums 4 consecutive bins (or fewer), then a suffix scan over the 1024 partials
-  __shared__ int32_t part[1024];
-  int local[4] = {0, 0, 0, 0};
-  int s4 = 0;
+  __shared__ int32_t wtot[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int4 loc = make_int4(0, 0, 0, 0);
+  if (tid * 4 < NB) {
+    int4 v[SR_REPL];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int b = tid * 4 + j;
-    if (b < NB)
-      for (int rp = 0; rp < SR_REPL; ++rp) local[j] += hist[rp * SR_BINS + b];
-    s4 += local[j];
-  }
-  part[tid] = s4;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {   // inclusive suffix scan
-    int v = 0;
-    if (tid + off < 1024) v = part[tid + off];
-    __syncthreads();
-    part[tid] += v;
-    __syncthreads();
-  }
-  int run = tid + 1 < 1024 ? part[tid + 1] : 0;  // keys in the bins above this thread's four
+    for (int rp = 0; rp < SR_REPL; ++rp)
+      v[rp] = *reinterpret_cast<const int4*>(hist + rp * SR_BINS + tid * 4);
 #pragma unroll
-  for (int j = 3; j >= 0; --j) {
-    const int b = tid * 4 + j;
-    run += local[j];
-    if (b < NB) suf[b] = run;
+    for (int rp = 0; rp < SR_REPL; ++rp) {
+      loc.x += v[rp].x; loc.y += v[rp].y; loc.z += v[rp].z; loc.w += v[rp].w;
+    }
   }
-  if (tid == 0) suf[NB] = 0;
-  __syncthreads();
+  const int s4 = loc.x + loc.y + loc.z + loc.w;
+  // inclusive suffix sum over the lanes of the wavefront: lane l gets the sum of lanes l..63
+  int incl = s4;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int t = __shfl_down(incl, off, 64);
+    if (lane + off < 64) incl += t;
+  }
+  if (lane == 0) wtot[wave] = incl;
   const int32_t k_rem = PASS == 0 ? k : st->k_rem;
   const uint32_t prefix = PASS == 0 ? 0u : st->prefix;
   __syncthreads();
-  for (int b = tid; b < NB; b += 1024)
-    if (suf[b + 1] < k_rem && k_rem <= suf[b]) {   // exactly one b satisfies this
+  int above = incl - s4;   // keys in the bins above this thread's four
+#pragma unroll
+  for (int w = 0; w < 16; ++w) above += w > wave ? wtot[w] : 0;
+  // suf[b] for the thread's bins b = 4 tid + j: keys in bins >= b
+  const int suf3 = above + loc.w, suf2 = suf3 + loc.z, suf1 = suf2 + loc.y, suf0 = suf1 + loc.x;
+  const int sufs[5] = {suf0, suf1, suf2, suf3, above};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int b = tid * 4 + j;
+    if (b < NB && sufs[j + 1] < k_rem && k_rem <= sufs[j]) {   // exactly one b satisfies this
       st->prefix = (prefix << BITS) | (uint32_t)b;
-      st->k_rem = k_rem - suf[b + 1];
+      st->k_rem = k_rem - sufs[j + 1];
     }
+  }
   if (PASS == 0 && tid == 0) st->overflow = 0;   // the second stream sets it when the list is full
-  for (int b = tid; b < SR_REPL * SR_BINS; b += 1024) hist[b] = 0;
+  int4* h4 = reinterpret_cast<int4*>(hist);
+  for (int b = tid; b < SR_REPL * SR_BINS / 4; b += 1024) h4[b] = make_int4(0, 0, 0, 0);
 }
 
 // Per chunk: keys above the threshold, keys equal to it; from the chunk's run of the list (a
@@ -266,15 +269,16 @@ __global__ __launch_bounds__(SR_THREADS) void sr_count_kernel(
 
 // One block: exclusive prefix of the equal-key counts, entries each chunk emits (all of its
 // keys above the threshold plus its share of the first k_rem equal keys), exclusive prefix
-// of those.  Rounds of 1024 consecutive chunks (coalesced loads), a block-wide exclusive scan
-// per quantity and round (shuffles inside a wavefront, the 16 wavefront totals through LDS),
-// the totals carried from round to round.
+// of those.  Rounds of 8192 consecutive chunks, 8 per thread (two 16-byte loads per array);
+// per quantity and round one block-wide exclusive scan of the threads' sums (shuffles inside a
+// wavefront, the 16 wavefront totals through LDS), the totals carried from round to round.
 __global__ __launch_bounds__(1024) void sr_scan_kernel(const SrState* __restrict__ st,
                                                        const int32_t* __restrict__ cnt_gt,
                                                        const int32_t* __restrict__ cnt_eq,
                                                        int64_t n_chunks,
                                                        int32_t* __restrict__ eq_prefix,
                                                        int32_t* __restrict__ out_prefix) {
+  constexpr int PER = 8;
   __shared__ int32_t wtot[2][16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t need_eq = st->k_rem;
@@ -300,24 +304,42 @@ __global__ __launch_bounds__(1024) void sr_scan_kernel(const SrState* __restrict
     return before + incl - v;
   };
   int eq_carry = 0, out_carry = 0;
-  int eq_next = tid < n_chunks ? cnt_eq[tid] : 0, gt_next = tid < n_chunks ? cnt_gt[tid] : 0;
-  for (int64_t c0 = 0; c0 < n_chunks; c0 += 1024) {
-    const int64_t c = c0 + tid;
-    const bool live = c < n_chunks;
-    const int eq = eq_next, gt = gt_next;
-    if (c + 1024 < n_chunks) {   // the next round's counts are fetched under this round's scans
-      eq_next = cnt_eq[c + 1024];
-      gt_next = cnt_gt[c + 1024];
+  for (int64_t c0 = 0; c0 < n_chunks; c0 += 1024 * PER) {
+    const int64_t c = c0 + (int64_t)tid * PER;
+    int eq[PER], gt[PER];
+    if (c + PER <= n_chunks) {   // the arrays start 16-byte aligned and c is a multiple of 8
+      const int4 a0 = *reinterpret_cast<const int4*>(cnt_eq + c), a1 = *reinterpret_cast<const int4*>(cnt_eq + c + 4);
+      const int4 b0 = *reinterpret_cast<const int4*>(cnt_gt + c), b1 = *reinterpret_cast<const int4*>(cnt_gt + c + 4);
+      eq[0] = a0.x; eq[1] = a0.y; eq[2] = a0.z; eq[3] = a0.w; eq[4] = a1.x; eq[5] = a1.y; eq[6] = a1.z; eq[7] = a1.w;
+      gt[0] = b0.x; gt[1] = b0.y; gt[2] = b0.z; gt[3] = b0.w; gt[4] = b1.x; gt[5] = b1.y; gt[6] = b1.z; gt[7] = b1.w;
     } else {
-      eq_next = gt_next = 0;
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        eq[j] = c + j < n_chunks ? cnt_eq[c + j] : 0;
+        gt[j] = c + j < n_chunks ? cnt_gt[c + j] : 0;
+      }
     }
+    int eq_sum = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) eq_sum += eq[j];
     int eq_all, take_all;
-    const int eq_before = eq_carry + excl_scan(eq, &eq_all);
-    const int take = gt + max(0, min(eq, need_eq - eq_before));
-    const int out_before = out_carry + excl_scan(take, &take_all);
-    if (live) {
-      eq_prefix[c] = eq_before;
-      out_prefix[c] = out_before;
+    int eq_before = eq_carry + excl_scan(eq_sum, &eq_all);
+    int take[PER], eqp[PER], take_sum = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      eqp[j] = eq_before;
+      take[j] = gt[j] + max(0, min(eq[j], need_eq - eq_before));
+      take_sum += take[j];
+      eq_before += eq[j];
+    }
+    int out_before = out_carry + excl_scan(take_sum, &take_all);
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      if (c + j < n_chunks) {
+        eq_prefix[c + j] = eqp[j];
+        out_prefix[c + j] = out_before;
+      }
+      out_before += take[j];
     }
     eq_carry += eq_all;
     out_carry += take_all;
@@ -561,7 +583,7 @@ template <typename T>
 int encode_t(moe_ctx* c, const T* W, const T* S, int64_t n, int64_t k, T* values, int32_t* indices,
              hipStream_t s) {
   const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
-  const int64_t nc2 = (n_chunks + 1) & ~(int64_t)1;   // keeps the list 8-byte aligned
+  const int64_t nc2 = (n_chunks + 3) & ~(int64_t)3;   // keeps the per-chunk arrays 16-byte aligned
   const int grid = (int)std::min<int64_t>(n_chunks, (int64_t)c->n_cu * 8);
   SrState* st = reinterpret_cast<SrState*>(c->d_sr_ws);
   int32_t* hist = c->d_sr_ws + SR_STATE_INTS;
@@ -596,7 +618,7 @@ int encode_t(moe_ctx* c, const T* W, const T* S, int64_t n, int64_t k, T* values
 
 size_t sr_workspace_ints(int64_t n) {
   const int64_t n_chunks = (n + SR_CHUNK - 1) / SR_CHUNK;
-  const int64_t nc2 = (n_chunks + 1) & ~(int64_t)1;
+  const int64_t nc2 = (n_chunks + 3) & ~(int64_t)3;
   // state, histograms, six per-chunk arrays, the candidate list (8 bytes per entry)
   return (size_t)(SR_STATE_INTS + SR_REPL * SR_BINS + 6 * nc2 + 2 * sr_list_cap(n));
 }
