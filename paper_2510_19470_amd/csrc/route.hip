@@ -180,7 +180,39 @@ constexpr int GATE_TOK = GATE_BLOCK_TOKENS;    // tokens per block
 constexpr int GATE_WAVES = 8;   // wavefronts per block, each with an eighth of d
 constexpr int GATE_TB = GATE_TOK / 16;
 
-template <int W, int VPL, int NEB, bool HIST>
+// STAGED (d a multiple of 512, E <= 16 * NEB): the token rows do not go from global memory to
+// the MFMA operand registers directly (16 rows x 64 bytes per load instruction) but through
+// LDS, copied there asynchronously in full-row pieces: a stage is the block's 32 rows x 256
+// elements (512 contiguous bytes per row, one copy instruction = 2 rows), three stages of which
+// two are in flight, 16-byte chunks XOR-swizzled by the row so that the fragment reads of 16
+// rows fall on distinct banks.  Wavefront w multiplies k-slice w (32 elements) of every stage;
+// the gate rows still come straight from global memory (L2), two stages ahead, in registers.
+constexpr int GATE_STAGE_K = 256;                      // elements of a row per stage
+constexpr int GATE_STAGE_BYTES = GATE_TOK * GATE_STAGE_K * 2;
+constexpr int GATE_STAGES = 3;
+
+// s_waitcnt vmcnt(N) followed by a barrier, N a compile-time constant
+template <int N>
+__device__ __forceinline__ void gate_wait_barrier() {
+  static_assert(N >= 0 && N <= 8, "wait counts of the staged gate loop");
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  else if constexpr (N == 3) asm volatile("s_waitcnt vmcnt(3)\n\ts_barrier" ::: "memory");
+  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
+  else if constexpr (N == 5) asm volatile("s_waitcnt vmcnt(5)\n\ts_barrier" ::: "memory");
+  else if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");
+  else if constexpr (N == 7) asm volatile("s_waitcnt vmcnt(7)\n\ts_barrier" ::: "memory");
+  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+  else static_assert(N == 0, "unused wait count");
+}
+
+// 16 bytes per lane global -> LDS; the wavefront's 1 KB lands at lds_addr (wave-uniform, via
+// M0) + lane * 16.
+__device__ __forceinline__ void gate_dma16(const void* src, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+template <int W, int VPL, int NEB, bool HIST, bool STAGED>
 __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
     const float* __restrict__ bias, int T, int E, int d, int k, int renormalize,
@@ -189,7 +221,13 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
     int32_t* __restrict__ super_acc, int32_t* __restrict__ super_clear, int tot_off) {
   constexpr int EG = 16 * NEB;                     // experts per pass over the token rows
   constexpr int EP = W * VPL < 64 ? 64 : W * VPL;  // expert slots kept in LDS
-  __shared__ float part[GATE_WAVES][GATE_TOK][EG + 1];
+  // the partial sums [wavefront][token][expert]; the stages of the token rows use the same LDS
+  // before them
+  constexpr int PART_BYTES = GATE_WAVES * GATE_TOK * (EG + 1) * 4;
+  constexpr int SMEM_BYTES = STAGED && GATE_STAGES * GATE_STAGE_BYTES > PART_BYTES
+                                 ? GATE_STAGES * GATE_STAGE_BYTES : PART_BYTES;
+  __shared__ __align__(16) char smem[SMEM_BYTES];
+  float (*part)[GATE_TOK][EG + 1] = reinterpret_cast<float (*)[GATE_TOK][EG + 1]>(smem);
   __shared__ float fin[GATE_TOK][EP + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, q = lane >> 4;
@@ -205,12 +243,82 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
 #pragma unroll
     for (int eb = 0; eb < NEB; ++eb)
       wp[eb] = reinterpret_cast<const uint4*>(Wg + (size_t)min(e0 + 16 * eb + n, E - 1) * d +
-                                              wave * kq + q * 8);
+                                              (STAGED ? wave * 32 : wave * kq) + q * 8);
     f32x4_t acc[NEB][GATE_TB];
 #pragma unroll
     for (int eb = 0; eb < NEB; ++eb)
 #pragma unroll
       for (int tb = 0; tb < GATE_TB; ++tb) acc[eb][tb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    if constexpr (STAGED) {
+      const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
+      const int nit = d / GATE_STAGE_K;   // even: d is a multiple of 512
+      // copies: instruction c (0..15) of a stage fills rows 2c, 2c+1 (lane >> 5), 32 chunk slots
+      // each; slot s of row r holds global chunk s ^ (r & 15).  This wavefront issues c = wave
+      // and c = wave + 8.
+      const char* src[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int r = 2 * (wave + 8 * u) + (lane >> 5);
+        src[u] = reinterpret_cast<const char*>(x + (size_t)min(t0 + r, T - 1) * d) +
+                 (((lane & 31) ^ (r & 15)) << 4);
+      }
+      auto copy = [&](int it) {
+        const uint32_t sb = lds0 + (uint32_t)(it % GATE_STAGES) * GATE_STAGE_BYTES;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+          gate_dma16(src[u] + (size_t)it * (GATE_STAGE_K * 2),
+                     __builtin_amdgcn_readfirstlane(sb + (wave + 8 * u) * 1024));
+      };
+      // fragment of token block tb, k-slice `wave` of the stage: row 16 tb + n, chunk 4 wave + q
+      int frag[GATE_TB];
+#pragma unroll
+      for (int tb = 0; tb < GATE_TB; ++tb)
+        frag[tb] = (16 * tb + n) * (GATE_STAGE_K * 2) + (((4 * wave + q) ^ n) << 4);
+      uint4 wq[2][NEB];
+      auto gate_rows = [&](int buf, int it) {
+#pragma unroll
+        for (int eb = 0; eb < NEB; ++eb) wq[buf][eb] = wp[eb][it * (GATE_STAGE_K / 8)];
+      };
+      auto mac = [&](int buf, int it) {
+        const char* st = smem + (it % GATE_STAGES) * GATE_STAGE_BYTES;
+        uint4 xv[GATE_TB];
+#pragma unroll
+        for (int tb = 0; tb < GATE_TB; ++tb) xv[tb] = *reinterpret_cast<const uint4*>(st + frag[tb]);
+#pragma unroll
+        for (int eb = 0; eb < NEB; ++eb)
+#pragma unroll
+          for (int tb = 0; tb < GATE_TB; ++tb)
+            acc[eb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8_t, wq[buf][eb]), __builtin_bit_cast(bf16x8_t, xv[tb]),
+                acc[eb][tb], 0, 0, 0);
+      };
+      // Iteration j issues the gate rows (NEB loads) and then the copies (2 instructions) of
+      // stage j + 2; the prologue does the same for stages 0 and 1, copies first.  Memory
+      // operations complete in issue order, so at the top of iteration `it` "at most NEB + 2
+      // outstanding" (the gate rows and the copies of it + 1) means that the gate rows and the
+      // copies of stage `it` have arrived; the barrier extends that to the copies of the other
+      // wavefronts and says that everybody is done with stage it - 1, which the copies of it + 2
+      // refill.  A fourth stage (three in flight) was slower: it halves the blocks per CU at 64
+      // experts.  nit >= 4 and even (the launcher checks d).
+      copy(0);
+      gate_rows(0, 0);
+      copy(1);
+      gate_rows(1, 1);
+      for (int it = 0; it < nit - 2; it += 2) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          gate_wait_barrier<NEB + 2>();
+          mac(b, it + b);
+          gate_rows(b, it + b + 2);
+          copy(it + b + 2);
+        }
+      }
+      gate_wait_barrier<NEB + 2>();   // behind stage nit - 2: the gate rows and copies of nit - 1
+      mac(0, nit - 2);
+      gate_wait_barrier<0>();
+      mac(1, nit - 1);
+      __syncthreads();   // every fragment read is done before the partial sums overwrite the stages
+    } else {
 #pragma unroll 4
     for (int ks = 0; ks < kq / 32; ++ks) {   // a k-slice of 32 = 4 chunks of 16 bytes per row
       uint4 xv[GATE_TB], wv[NEB];
@@ -225,6 +333,7 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
           acc[eb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
               __builtin_bit_cast(bf16x8_t, wv[eb]), __builtin_bit_cast(bf16x8_t, xv[tb]),
               acc[eb][tb], 0, 0, 0);
+    }
     }
     // the lane holds token 16*tb + n and experts 16*eb + 4*q + i of this group
 #pragma unroll
@@ -249,9 +358,9 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
   }
   // the partial sums are not needed any more (the barrier that ends the loop above): their
   // LDS holds the block's selected ids [32][k] and the per-wavefront expert counts [8][256]
-  int32_t* ids = reinterpret_cast<int32_t*>(&part[0][0][0]);
+  int32_t* ids = reinterpret_cast<int32_t*>(smem);
   int32_t* wcnt = ids + GATE_TOK * MOE_MAX_TOPK;
-  static_assert(sizeof(part) >= sizeof(int32_t) * (GATE_TOK * MOE_MAX_TOPK + GATE_WAVES * MOE_MAX_EXPERTS),
+  static_assert(PART_BYTES >= (int)sizeof(int32_t) * (GATE_TOK * MOE_MAX_TOPK + GATE_WAVES * MOE_MAX_EXPERTS),
                 "the ids and counts of the ranking step live in the partial sums' LDS");
   if (HIST) {
     for (int i = tid; i < GATE_TOK * MOE_MAX_TOPK; i += 64 * GATE_WAVES) ids[i] = -1;
@@ -313,18 +422,37 @@ template <int W, int VPL, int NEB>
 int launch_gate(const moe_ctx* c, const void* x, const void* Wg, const float* bias, int T,
                 float* logits, int32_t* idx, float* w, bool keep_hist, hipStream_t s) {
   const int grid = (T + GATE_TOK - 1) / GATE_TOK;
+  // token rows through LDS when a stage divides the row and one pass covers all experts
+  if (c->cfg.d % (2 * GATE_STAGE_K) == 0 && c->cfg.d >= 4 * GATE_STAGE_K && c->cfg.E <= 16 * NEB) {
+    int ebits = 0;
+    while ((1 << ebits) < c->cfg.E) ++ebits;
+    const size_t half = (size_t)c->rt_super_max * c->cfg.E + (size_t)c->cfg.E * RT_TOT_STRIDE;
+    if (keep_hist)
+      hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, true, true>), dim3(grid),
+                         dim3(64 * GATE_WAVES), 0, s, (const uint16_t*)x, (const uint16_t*)Wg, bias,
+                         T, c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, ebits,
+                         c->d_rt_rank, c->d_rt_hist, c->d_rt_super + (size_t)c->rt_parity * half,
+                         c->d_rt_super + (size_t)(c->rt_parity ^ 1) * half,
+                         c->rt_super_max * c->cfg.E);
+    else
+      hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, false, true>), dim3(grid),
+                         dim3(64 * GATE_WAVES), 0, s, (const uint16_t*)x, (const uint16_t*)Wg, bias,
+                         T, c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, 0,
+                         nullptr, nullptr, nullptr, nullptr, 0);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
+  }
   if (keep_hist) {
     int ebits = 0;
     while ((1 << ebits) < c->cfg.E) ++ebits;
     const size_t half = (size_t)c->rt_super_max * c->cfg.E + (size_t)c->cfg.E * RT_TOT_STRIDE;
-    hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, true>), dim3(grid),
+    hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, true, false>), dim3(grid),
                        dim3(64 * GATE_WAVES), 0, s, (const uint16_t*)x, (const uint16_t*)Wg, bias, T,
                        c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, ebits,
                        c->d_rt_rank, c->d_rt_hist, c->d_rt_super + (size_t)c->rt_parity * half,
                        c->d_rt_super + (size_t)(c->rt_parity ^ 1) * half,
                        c->rt_super_max * c->cfg.E);
   } else {
-    hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, false>), dim3(grid),
+    hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, false, false>), dim3(grid),
                        dim3(64 * GATE_WAVES), 0, s, (const uint16_t*)x, (const uint16_t*)Wg, bias, T,
                        c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, 0, nullptr,
                        nullptr, nullptr, nullptr, 0);
