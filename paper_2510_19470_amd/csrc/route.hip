@@ -183,13 +183,16 @@ constexpr int GATE_TB = GATE_TOK / 16;
 // STAGED (d a multiple of 512, E <= 16 * NEB): the token rows do not go from global memory to
 // the MFMA operand registers directly (16 rows x 64 bytes per load instruction) but through
 // LDS, copied there asynchronously in full-row pieces: a stage is the block's 32 rows x 256
-// elements (512 contiguous bytes per row, one copy instruction = 2 rows), three stages of which
-// two are in flight, 16-byte chunks XOR-swizzled by the row so that the fragment reads of 16
+// elements (512 contiguous bytes per row, one copy instruction = 2 rows), four stages of which
+// three are in flight, 16-byte chunks XOR-swizzled by the row so that the fragment reads of 16
 // rows fall on distinct banks.  Wavefront w multiplies k-slice w (32 elements) of every stage;
 // the gate rows still come straight from global memory (L2), two stages ahead, in registers.
+// Their loads are issued by hand as well (gate_load16): a load that the compiler tracks makes
+// it wait for "all but the NEB newest memory operations" before the first MFMA, and since it
+// does not count the copies, that wait would also cover the copies of the stages ahead.
 constexpr int GATE_STAGE_K = 256;                      // elements of a row per stage
 constexpr int GATE_STAGE_BYTES = GATE_TOK * GATE_STAGE_K * 2;
-constexpr int GATE_STAGES = 3;
+constexpr int GATE_STAGES = 4;
 
 // s_waitcnt vmcnt(N) followed by a barrier, N a compile-time constant
 template <int N>
@@ -204,6 +207,19 @@ __device__ __forceinline__ void gate_wait_barrier() {
   else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
   else static_assert(N == 0, "unused wait count");
 }
+
+// 16 bytes per lane global -> registers, outside the compiler's bookkeeping of outstanding
+// loads: the value is valid only behind a gate_wait_barrier that covers it and the
+// gate_arrived() that follows.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4_t gate_load16(const void* src) {
+  u32x4_t r;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(src) : "memory");
+  return r;
+}
+// Ties a register filled by gate_load16 to this point of the program: no use of it can be
+// scheduled above the wait that precedes.
+__device__ __forceinline__ void gate_arrived(u32x4_t& r) { asm volatile("" : "+v"(r)); }
 
 // 16 bytes per lane global -> LDS; the wavefront's 1 KB lands at lds_addr (wave-uniform, via
 // M0) + lane * 16.
@@ -274,14 +290,16 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
 #pragma unroll
       for (int tb = 0; tb < GATE_TB; ++tb)
         frag[tb] = (16 * tb + n) * (GATE_STAGE_K * 2) + (((4 * wave + q) ^ n) << 4);
-      uint4 wq[2][NEB];
+      u32x4_t wq[2][NEB];
       auto gate_rows = [&](int buf, int it) {
 #pragma unroll
-        for (int eb = 0; eb < NEB; ++eb) wq[buf][eb] = wp[eb][it * (GATE_STAGE_K / 8)];
+        for (int eb = 0; eb < NEB; ++eb) wq[buf][eb] = gate_load16(wp[eb] + it * (GATE_STAGE_K / 8));
       };
       auto mac = [&](int buf, int it) {
         const char* st = smem + (it % GATE_STAGES) * GATE_STAGE_BYTES;
         uint4 xv[GATE_TB];
+#pragma unroll
+        for (int eb = 0; eb < NEB; ++eb) gate_arrived(wq[buf][eb]);
 #pragma unroll
         for (int tb = 0; tb < GATE_TB; ++tb) xv[tb] = *reinterpret_cast<const uint4*>(st + frag[tb]);
 #pragma unroll
@@ -292,28 +310,30 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
                 __builtin_bit_cast(bf16x8_t, wq[buf][eb]), __builtin_bit_cast(bf16x8_t, xv[tb]),
                 acc[eb][tb], 0, 0, 0);
       };
-      // Iteration j issues the gate rows (NEB loads) and then the copies (2 instructions) of
-      // stage j + 2; the prologue does the same for stages 0 and 1, copies first.  Memory
-      // operations complete in issue order, so at the top of iteration `it` "at most NEB + 2
-      // outstanding" (the gate rows and the copies of it + 1) means that the gate rows and the
+      // Iteration j issues the gate rows of stage j + 2 (NEB loads) and then the copies of stage
+      // j + 3 (2 instructions); the prologue does the same for j = -3, -2, -1 (no gate rows for
+      // j = -3).  Memory operations complete in issue order and nothing else is outstanding in
+      // this loop, so at the top of iteration `it` "at most NEB + 4 outstanding" (the copies of
+      // it + 1, the gate rows of it + 1, the copies of it + 2) means that the gate rows and the
       // copies of stage `it` have arrived; the barrier extends that to the copies of the other
-      // wavefronts and says that everybody is done with stage it - 1, which the copies of it + 2
-      // refill.  A fourth stage (three in flight) was slower: it halves the blocks per CU at 64
-      // experts.  nit >= 4 and even (the launcher checks d).
+      // wavefronts and says that everybody is done with stage it - 1, which the copies of it + 3
+      // refill.  The last two iterations have fewer operations behind them.  nit >= 4 and even
+      // (the launcher checks d).
       copy(0);
       gate_rows(0, 0);
       copy(1);
       gate_rows(1, 1);
+      copy(2);
       for (int it = 0; it < nit - 2; it += 2) {
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-          gate_wait_barrier<NEB + 2>();
+          gate_wait_barrier<NEB + 4>();
           mac(b, it + b);
           gate_rows(b, it + b + 2);
-          copy(it + b + 2);
+          if (it + b + 3 < nit) copy(it + b + 3);
         }
       }
-      gate_wait_barrier<NEB + 2>();   // behind stage nit - 2: the gate rows and copies of nit - 1
+      gate_wait_barrier<NEB + 2>();   // behind stage nit - 2: the copies and gate rows of nit - 1
       mac(0, nit - 2);
       gate_wait_barrier<0>();
       mac(1, nit - 1);
