@@ -15,7 +15,6 @@ namespace {
 
 constexpr int RB_TOK = 128;   // tokens per partial-sum chunk
 constexpr int RB_COLS = 256;  // columns per block of the weight-gradient kernel
-constexpr int RB_EG = 16;     // experts per accumulator group
 
 // One wavefront per token; lane e, e+64, ... own the experts.
 __global__ __launch_bounds__(256) void route_bwd_dlogits_kernel(
@@ -55,9 +54,11 @@ __global__ __launch_bounds__(256) void route_bwd_dlogits_kernel(
 }
 
 // partial[chunk][e][c] = sum over the chunk's tokens of dlogits[t][e] * x[t][c].
-// Block = 256 columns x one chunk of 128 tokens x one group of 16 experts (the chunk's
-// dlogits for those experts staged in LDS); a thread owns one column.
-template <typename T>
+// Block = 256 columns x one chunk of 128 tokens x one group of RB_EG experts (the chunk's
+// dlogits for those experts staged in LDS); a thread owns one column.  RB_EG = 8 or 16: the
+// kernel is bound by its multiply-adds, so 32 accumulators per thread (x read once up to 32
+// experts, but half as many blocks) are slower than two groups of 16.
+template <typename T, int RB_EG>
 __global__ __launch_bounds__(RB_COLS) void route_bwd_dwg_partial_kernel(
     const T* __restrict__ x, const float* __restrict__ dlogits, int Tn, int d, int E,
     float* __restrict__ partial) {
@@ -97,14 +98,22 @@ __global__ __launch_bounds__(RB_COLS) void route_bwd_dwg_partial_kernel(
     if (ee < ne) partial[((size_t)chunk * E + e0 + ee) * d + c] = acc[ee];
 }
 
-// dWg[e][c] = sum over the chunks in ascending order.
+// dWg[e][c] = sum over the chunks in ascending order (8 loads in flight, added in order).
 __global__ __launch_bounds__(256) void route_bwd_dwg_reduce_kernel(const float* __restrict__ partial,
                                                                    int n_chunks, size_t ed,
                                                                    float* __restrict__ dWg) {
   const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   if (i >= ed) return;
   float s = 0.f;
-  for (int ch = 0; ch < n_chunks; ++ch) s += partial[(size_t)ch * ed + i];
+  int ch = 0;
+  for (; ch + 8 <= n_chunks; ch += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(ch + u) * ed + i];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; ch < n_chunks; ++ch) s += partial[(size_t)ch * ed + i];
   dWg[i] = s;
 }
 
@@ -184,13 +193,19 @@ int launch_route_bwd(moe_ctx* c, const void* x, const void* Wg, const float* log
                      topk_w, dtopk_w, T, E, k, rn, dlogits);
   if (dWg != nullptr) {
     const int chunks = (T + RB_TOK - 1) / RB_TOK;
-    const dim3 g((d + RB_COLS - 1) / RB_COLS, chunks, (E + RB_EG - 1) / RB_EG);
-    if (c->cfg.dtype == MOE_BF16)
-      hipLaunchKernelGGL((route_bwd_dwg_partial_kernel<uint16_t>), g, dim3(RB_COLS), 0, s,
-                         (const uint16_t*)x, dlogits, T, d, E, c->d_rbwd_ws);
-    else
-      hipLaunchKernelGGL((route_bwd_dwg_partial_kernel<float>), g, dim3(RB_COLS), 0, s,
-                         (const float*)x, dlogits, T, d, E, c->d_rbwd_ws);
+    const int eg = E <= 8 ? 8 : 16;
+    const dim3 g((d + RB_COLS - 1) / RB_COLS, chunks, (E + eg - 1) / eg);
+#define DWG_PARTIAL(T_, EG_)                                                                  \
+  hipLaunchKernelGGL((route_bwd_dwg_partial_kernel<T_, EG_>), g, dim3(RB_COLS), 0, s,         \
+                     (const T_*)x, dlogits, T, d, E, c->d_rbwd_ws)
+    if (c->cfg.dtype == MOE_BF16) {
+      if (eg == 8) DWG_PARTIAL(uint16_t, 8);
+      else DWG_PARTIAL(uint16_t, 16);
+    } else {
+      if (eg == 8) DWG_PARTIAL(float, 8);
+      else DWG_PARTIAL(float, 16);
+    }
+#undef DWG_PARTIAL
     const size_t ed = (size_t)E * d;
     hipLaunchKernelGGL(route_bwd_dwg_reduce_kernel, dim3((unsigned)((ed + 255) / 256)), dim3(256), 0,
                        s, c->d_rbwd_ws, chunks, ed, dWg);
