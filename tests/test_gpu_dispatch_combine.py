@@ -247,6 +247,8 @@ def test_dispatch_routed_full_size_configs(name):
     (1, 8, 2, 2, 256), (31, 8, 2, 2, 256), (33, 16, 3, 4, 256), (1000, 256, 16, 8, 256),
     (5001, 64, 6, 256, 256), (4099, 7, 1, 7, 512), (9000, 128, 8, 4, 256),
     (600, 48, 5, 3, 256),
+    # d >= 1024: the gate kernel's LDS-staged load path with the ranking epilogue
+    (33, 16, 3, 4, 1024), (4099, 7, 1, 7, 1536), (600, 48, 5, 3, 1024), (1001, 64, 6, 8, 2048),
 ])
 def test_dispatch_routed_edge_shapes(T, E, k, R, d):
     """Ragged last gate block, one token, the largest expert count and top-k, more than one

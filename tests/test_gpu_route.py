@@ -67,10 +67,16 @@ def test_route_gate_projection_and_selection(name, T):
 
 
 @pytest.mark.parametrize("T,E,k,d", [(333, 4, 2, 256), (1000, 24, 3, 512), (515, 48, 6, 256),
-                                     (700, 100, 8, 512), (260, 256, 16, 256), (31, 2, 1, 256)])
+                                     (700, 100, 8, 512), (260, 256, 16, 256), (31, 2, 1, 256),
+                                     # d >= 1024 and a multiple of 512, E <= 64: the token rows
+                                     # go through LDS (4 to 10 stages of 256 elements)
+                                     (333, 4, 2, 1024), (1000, 24, 3, 1536), (515, 48, 6, 1024),
+                                     (700, 64, 8, 2048), (31, 2, 1, 1024), (77, 8, 2, 2560),
+                                     (1, 16, 4, 1024), (100, 100, 8, 1024)])
 def test_fused_gate_every_expert_count_branch(T, E, k, d):
-    """The fused bf16 gate kernel picks its selection group width and expert blocking from E:
-    one case per branch, ragged T, with a bias; indices exact on the GPU's logits."""
+    """The fused bf16 gate kernel picks its selection group width and expert blocking from E
+    and its load path from d: one case per branch, ragged T, with a bias; indices exact on the
+    GPU's logits."""
     from gpu_common import DEV, moe, say, i32, nerr, vals, to_device
     say(f"[route fused] T={T} E={E} k={k} d={d}")
     cfg = wl.MoEConfig("gate", 31 + T + E, "bf16", T=T, d=d, E=E, k=k, f=256, R=1, bias_scale=0.7)
