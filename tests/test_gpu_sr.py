@@ -18,9 +18,7 @@ def _ctx(dtype):
                           dtype=moe.MOE_BF16 if dtype == "bf16" else moe.MOE_F32, renormalize=1)
 
 
-def _run(shape, seed, dtype, k, ties=False, ctx=None):
-    shared, experts = wl.make_sr_inputs(shape, seed, dtype, n_experts=1, ties=ties)
-    expert = experts[0]
+def _check(shared, expert, dtype, k, ctx=None):
     own = ctx is None
     ctx = ctx or _ctx(dtype)
     dS, dW = to_device(shared, dtype), to_device(expert, dtype)
@@ -37,6 +35,11 @@ def _run(shape, seed, dtype, k, ties=False, ctx=None):
         moe.moe_destroy(ctx)
 
 
+def _run(shape, seed, dtype, k, ties=False, ctx=None):
+    shared, experts = wl.make_sr_inputs(shape, seed, dtype, n_experts=1, ties=ties)
+    _check(shared, experts[0], dtype, k, ctx)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("shape,k", [((8, 16), 1), ((8, 16), 128), ((96, 200), 384),
                                      ((257, 1031), 5299), ((1024, 2048), 41943)])
@@ -50,6 +53,27 @@ def test_many_equal_magnitudes(dtype):
     # tie rule (lower index first) decides
     _run((300, 517), 32, dtype, wl_keep((300, 517)), ties=True)
     _run((300, 517), 33, dtype, 300 * 517 // 3, ties=True)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_candidate_list_overflow(dtype):
+    """The candidate list in the workspace has a fixed size (a region per block of the second
+    stream); when a region is too small the later kernels stream the matrices again.  (a) Half
+    of all entries kept: every region overflows.  (b) The first rows of the expert are unrelated
+    to the shared expert (large residuals there, small ones elsewhere): only the regions of the
+    first chunks overflow, and the calls before and after use the list."""
+    shape = (512, 1024)
+    n = shape[0] * shape[1]
+    ctx = _ctx(dtype)
+    shared, experts = wl.make_sr_inputs(shape, 51, dtype, n_experts=1)
+    _check(shared, experts[0], dtype, sr.keep_count(n, 50), ctx)      # fits
+    _check(shared, experts[0], dtype, n // 2, ctx)                     # (a)
+    other, _ = wl.make_sr_inputs(shape, 52, dtype, n_experts=1)
+    mixed = experts[0].copy()
+    mixed[:64] = other[:64]
+    _check(shared, mixed, dtype, 40000, ctx)                           # (b)
+    _check(shared, experts[0], dtype, sr.keep_count(n, 50), ctx)      # fits again
+    moe.moe_destroy(ctx)
 
 
 def wl_keep(shape):
