@@ -211,7 +211,10 @@ __global__ __launch_bounds__(256) void dispatch_scatter_kernel(
     const int s = t * k + lane;
     if (e >= 0) {
       row = offs[e] + base + rk;
-      row_to_slot[row] = s;
+      // ranks and histograms that do not belong to this topk_idx (a caller that changed the
+      // routing in place after moe_route) must not turn into a write outside the buffers
+      if ((unsigned)row >= (unsigned)(T * k)) row = -1;
+      else row_to_slot[row] = s;
     }
     slot_to_row[s] = row;
   }

@@ -349,6 +349,13 @@ int moe_route(moe_ctx* c, const void* x, const void* Wg, const float* bias, int3
     if (keep) c->rt_parity ^= 1;
     st = launch_gate_route_fused(c, x, Wg, bias, T, logits, topk_idx, topk_w, keep,
                                  (hipStream_t)stream);
+    if (keep) {
+      // the launch adds into rows [0, n_sup) of buffer rt_parity and has cleared every row of
+      // the other buffer that could hold sums
+      const int n_blk = (T + GATE_BLOCK_TOKENS - 1) / GATE_BLOCK_TOKENS;
+      c->rt_dirty[c->rt_parity] = std::max(c->rt_dirty[c->rt_parity], (n_blk + RT_SUPER - 1) / RT_SUPER);
+      if (st == MOE_OK) c->rt_dirty[c->rt_parity ^ 1] = 0;
+    }
     if (st == MOE_OK && keep) {
       c->rt_valid = 1;
       c->rt_idx = topk_idx;

@@ -62,6 +62,8 @@ struct moe_ctx {
   int32_t* d_rt_super;    // [2] x ([rt_super_max][E] super-block sums, [E][RT_TOT_STRIDE] totals)
   int32_t rt_super_max;
   int rt_parity;          // buffer the last moe_route accumulated into
+  int32_t rt_dirty[2];    // super-block rows of each buffer that may be non-zero (rows at and
+                          // above it are zero); the next launch clears them in the other buffer
   int rt_valid;           // the side products describe rt_idx / rt_T
   const int32_t* rt_idx;
   int32_t rt_T;

@@ -172,8 +172,9 @@ __global__ __launch_bounds__(256) void route_select_kernel(const float* __restri
 // holds anyway: the stable rank of every slot among the block's slots of the same expert
 // (ballots inside a wavefront, an LDS table across the 8 wavefronts), the block's expert
 // histogram, and that histogram added (integer atomics: order-independent) to the sums of
-// the block's super-block of 16 and to the grand totals; the first block of a super-block
-// clears the super-block's sums in the other buffer (block 0 also its totals), for the next call.
+// the block's super-block of 16 and to the grand totals; the blocks also clear the other
+// buffer for the next call: all of its super-block rows that the host knows may be non-zero
+// (clear_rows, dealt over the blocks), block 0 its totals.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 constexpr int GATE_TOK = GATE_BLOCK_TOKENS;    // tokens per block
@@ -234,7 +235,8 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
     const float* __restrict__ bias, int T, int E, int d, int k, int renormalize,
     float* __restrict__ logits_out, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     int ebits, int32_t* __restrict__ rt_rank, int32_t* __restrict__ rt_hist,
-    int32_t* __restrict__ super_acc, int32_t* __restrict__ super_clear, int tot_off) {
+    int32_t* __restrict__ super_acc, int32_t* __restrict__ super_clear, int tot_off,
+    int clear_rows) {
   constexpr int EG = 16 * NEB;                     // experts per pass over the token rows
   constexpr int EP = W * VPL < 64 ? 64 : W * VPL;  // expert slots kept in LDS
   // the partial sums [wavefront][token][expert]; the stages of the token rows use the same LDS
@@ -421,7 +423,9 @@ __global__ __launch_bounds__(64 * GATE_WAVES) void gate_route_mfma_kernel(
         atomicAdd(&super_acc[sup], n);
         atomicAdd(&super_acc[tot], n);
       }
-      if (blockIdx.x % RT_SUPER == 0) super_clear[sup] = 0;
+      // the other buffer, for the next call: every super-block row that may hold sums (the
+      // call that filled it may have had more tokens than this one), dealt over the blocks
+      for (int r = blockIdx.x; r < clear_rows; r += gridDim.x) super_clear[(size_t)r * E + tid] = 0;
       if (blockIdx.x == 0) super_clear[tot] = 0;
     }
   }
@@ -453,12 +457,12 @@ int launch_gate(const moe_ctx* c, const void* x, const void* Wg, const float* bi
                          T, c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, ebits,
                          c->d_rt_rank, c->d_rt_hist, c->d_rt_super + (size_t)c->rt_parity * half,
                          c->d_rt_super + (size_t)(c->rt_parity ^ 1) * half,
-                         c->rt_super_max * c->cfg.E);
+                         c->rt_super_max * c->cfg.E, c->rt_dirty[c->rt_parity ^ 1]);
     else
       hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, false, true>), dim3(grid),
                          dim3(64 * GATE_WAVES), 0, s, (const uint16_t*)x, (const uint16_t*)Wg, bias,
                          T, c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, 0,
-                         nullptr, nullptr, nullptr, nullptr, 0);
+                         nullptr, nullptr, nullptr, nullptr, 0, 0);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
   }
   if (keep_hist) {
@@ -470,12 +474,12 @@ int launch_gate(const moe_ctx* c, const void* x, const void* Wg, const float* bi
                        c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, ebits,
                        c->d_rt_rank, c->d_rt_hist, c->d_rt_super + (size_t)c->rt_parity * half,
                        c->d_rt_super + (size_t)(c->rt_parity ^ 1) * half,
-                       c->rt_super_max * c->cfg.E);
+                       c->rt_super_max * c->cfg.E, c->rt_dirty[c->rt_parity ^ 1]);
   } else {
     hipLaunchKernelGGL((gate_route_mfma_kernel<W, VPL, NEB, false, false>), dim3(grid),
                        dim3(64 * GATE_WAVES), 0, s, (const uint16_t*)x, (const uint16_t*)Wg, bias, T,
                        c->cfg.E, c->cfg.d, c->cfg.k, c->cfg.renormalize, logits, idx, w, 0, nullptr,
-                       nullptr, nullptr, nullptr, 0);
+                       nullptr, nullptr, nullptr, 0, 0);
   }
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }

@@ -229,6 +229,16 @@ def _routed_case(cfg, inp, T_call=None, bias=None):
         want3 = orc.dispatch_maps(i32(foreign), inp.dest_rank, cfg.R)
         for nm, wv in zip(names, want3):
             assert np.array_equal(i32(getattr(g3, nm)), wv), nm
+        # many tokens, few, many again: the second large call adds into the buffer the first
+        # one used, of which the small call in between cleared only its own part
+        moe.moe_route(ctx, x, Wg, b, topk_idx=idx)
+        moe.moe_route(ctx, x2, Wg, b, topk_idx=idx2)
+        moe.moe_route(ctx, x, Wg, b, topk_idx=idx)
+        g4 = moe.moe_dispatch_routed(ctx, x, idx)
+        torch.cuda.synchronize()
+        assert np.array_equal(i32(idx), idx_np)
+        for nm, wv in zip(names, want):
+            assert np.array_equal(i32(getattr(g4, nm)), wv), nm
     ctx.close()
     return want
 
