@@ -272,3 +272,35 @@ def test_dispatch_routed_edge_shapes(T, E, k, R, d):
     inp.dest_rank = rng.integers(0, R, size=E).astype(np.int32)
     bias = (-1.0 * np.log(np.arange(E) + 1.0)).astype(np.float32)    # skewed: some experts starve
     _routed_case(cfg, inp, bias=bias)
+
+
+def test_dispatch_routed_random_call_sequence():
+    """One context, token counts going up and down at random (1 .. T_max, ragged gate blocks,
+    one to several super-blocks), the routed and the two-launch dispatch mixed: every call's
+    integer outputs against the oracle.  The side products of moe_route live in the context
+    from call to call; nothing of an earlier call may show in a later one."""
+    from gpu_common import DEV, moe, i32, say, to_device
+    T_max, d, E, k, R = 3000, 1024, 24, 3, 4
+    cfg = wl.MoEConfig("routed-seq", 77, "bf16", T=T_max, d=d, E=E, k=k, f=256, R=R)
+    inp = wl.make_inputs(cfg, experts="none")
+    ctx = moe.moe_create(T_max=T_max, d=d, E=E, k=k, f=256, R=R, local_rank=cfg.local_rank,
+                         dtype=moe.MOE_BF16)
+    moe.moe_set_placement(ctx, inp.dest_rank)
+    x_all, Wg = to_device(inp.x, "bf16"), to_device(inp.Wg, "bf16")
+    rng = np.random.default_rng(5)
+    Ts = [3000, 40, 3000, 1, 2999, 513, 512, 1500, 33, 3000, 600, 2000, 31, 3000]
+    names = ("expert_counts", "expert_offsets", "rank_counts", "rank_offsets", "slot_to_row",
+             "row_to_slot")
+    for step, T in enumerate(Ts):
+        lo = int(rng.integers(0, T_max - T + 1))
+        x = x_all[lo:lo + T].contiguous()
+        idx, _, _ = moe.moe_route(ctx, x, Wg, None)
+        if step % 5 == 3:
+            moe.moe_route(ctx, x, Wg, None, topk_idx=idx)      # routed twice, dispatched once
+        got = moe.moe_dispatch(ctx, x, idx) if step % 4 == 2 else moe.moe_dispatch_routed(ctx, x, idx)
+        torch.cuda.synchronize()
+        want = orc.dispatch_maps(i32(idx), inp.dest_rank, R)
+        for nm, wv in zip(names, want):
+            assert np.array_equal(i32(getattr(got, nm)), wv), (step, T, nm)
+    say(f"[dispatch-routed-seq] {len(Ts)} calls on one context: ok")
+    ctx.close()
