@@ -310,6 +310,46 @@ def test_backward_matches_oracle(name, T, path, shape):
     lay.close()
 
 
+def test_layer_call_sequence_varying_token_count():
+    """One layer object (one context, one set of workspaces, tile schedules rebuilt on the
+    device per call), forward + backward with token counts going up and down: every call's
+    output, input gradient and weight gradients against the oracle on that call's tokens."""
+    from gpu_common import TOL, say, nerr, vals, to_device, to_host_f32, i32, layer_from_inputs
+    cfg = wl.scaled(wl.CONFIGS["train"], T=1300, d=1024, f=512, E=8, k=2, R=2, migrated=(6,),
+                    backward=True)
+    inp = wl.make_inputs(cfg)
+    lay = layer_from_inputs(inp)
+    tol = TOL[cfg.dtype]
+    W1, W3, W2 = (_f64_list(a, cfg.dtype) for a in (inp.W1, inp.W3, inp.W2))
+    for step, T in enumerate([1300, 70, 1300, 1, 513, 1299, 256, 1300]):
+        x = to_device(inp.x[:T], cfg.dtype)
+        dout = to_device(inp.dOut[:T], cfg.dtype)
+        fwd = lay.forward(x, save=True)
+        bwd = lay.backward(fwd, dout)
+        torch.cuda.synchronize()
+        idx = i32(fwd["topk_idx"])
+        w = fwd["topk_w"].cpu().numpy().astype(np.float64)
+        cnt, off, _, _, s2r, r2s = orc.dispatch_maps(idx, inp.dest_rank, cfg.R)
+        xp = vals(orc.pack_rows(inp.x[:T], r2s, cfg.k), cfg.dtype)
+        yo, Go, Uo = orc.expert_ffn(xp, cnt, off, W1, W3, W2)
+        out_o = orc.combine(yo, s2r, w)
+        dy_o, dw_o = orc.combine_bwd(vals(inp.dOut[:T], cfg.dtype), yo, s2r, w)
+        dxp_o, dW1_o, dW3_o, dW2_o = orc.expert_ffn_bwd(dy_o, xp, Go, Uo, cnt, off, W1, W3, W2)
+        dx_o = orc.dispatch_bwd(dxp_o, s2r, T, cfg.k)
+        errs = dict(out=nerr(to_host_f32(fwd["out"]), out_o), dx=nerr(to_host_f32(bwd["dx"]), dx_o),
+                    dw=nerr(bwd["dtopk_w"].cpu().numpy(), dw_o))
+        scale = max(max(np.max(np.abs(dW2_o[e])) for e in range(cfg.E)), 1e-30)
+        for e in range(cfg.E):
+            for nm, got, want in (("dW1", bwd["dW1"][e], dW1_o[e]), ("dW3", bwd["dW3"][e], dW3_o[e]),
+                                  ("dW2", bwd["dW2"][e], dW2_o[e])):
+                g = got.cpu().numpy().astype(np.float64)
+                errs[f"{nm}[{e}]"] = float(np.max(np.abs(g - want)) / max(np.max(np.abs(want)), 1e-3 * scale))
+        bad = {k_: v for k_, v in errs.items() if not v <= tol}
+        assert not bad, (step, T, bad)
+    say("[layer-seq] 8 forward+backward calls with varying T on one layer: ok")
+    lay.close()
+
+
 @pytest.mark.parametrize("path", ["mfma", "valu"])
 def test_backward_unwanted_weight_gradients(path):
     """NULL entries in the gradient tables: that gradient is not computed, every other output
