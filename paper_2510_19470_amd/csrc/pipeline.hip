@@ -145,6 +145,10 @@ int moe_pipeline_forward(moe_pipeline* p, const void* x, const void* Wg, const f
     int32_t t0 = 0, t1 = 0;
     (void)moe_pipeline_chunk_range(p, T, c, &t0, &t1);
     const int Tc = t1 - t0;
+    // an empty chunk (T below the chunk count's reach) starts at T, which need not be a multiple
+    // of 4: its calls write only the per-chunk counts, so they get the buffers' own (aligned)
+    // addresses
+    if (Tc == 0) t0 = 0;
     moe_ctx* ctx = p->ctx[c % p->n_streams];
     hipStream_t s = p->streams[c % p->n_streams];
     const size_t s0 = (size_t)t0 * k;   // first slot (= first packed row) of the chunk

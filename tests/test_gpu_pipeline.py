@@ -84,3 +84,44 @@ def test_pipeline_matches_oracle(T, n_chunks, n_streams, dtype, gated):
     assert err <= TOL[dtype]
     pipe.close()
     ctx.close()
+
+
+def test_pipeline_call_sequence_varying_token_count():
+    """One pipeline object, token counts going up and down: each chunk's context keeps the
+    gate kernel's side products from call to call; every call's chunk maps against the oracle
+    and its output against the dense definition."""
+    from gpu_common import DEV, TOL, moe, say, nerr, vals, to_device, to_host_f32, i32
+    dtype, d, f, E, k, R, n_chunks = "bf16", 1024, 512, 16, 2, 4, 3
+    T_max = 2200
+    cfg = wl.MoEConfig("pipe-seq", 99, dtype, T=T_max, d=d, E=E, k=k, f=f, R=R, migrated=(5,))
+    inp = wl.make_inputs(cfg)
+    pipe = moe.MoEPipeline(T_max=T_max, d=d, E=E, k=k, f=f, R=R, local_rank=0, dtype=moe.MOE_BF16,
+                           n_chunks=n_chunks, n_streams=2)
+    pipe.set_placement(inp.dest_rank)
+    Wg = to_device(inp.Wg, dtype)
+    W1 = [to_device(w, dtype) for w in inp.W1]
+    W3 = [to_device(w, dtype) for w in inp.W3]
+    W2 = [to_device(w, dtype) for w in inp.W2]
+    f64 = lambda ws: [vals(a, dtype) for a in ws]
+    W1v, W3v, W2v = f64(inp.W1), f64(inp.W3), f64(inp.W2)
+    for step, T in enumerate([2200, 130, 2200, 7, 1000, 2199]):
+        x = to_device(inp.x[:T], dtype)
+        bufs = pipe.alloc_outputs(T, DEV)
+        pipe.forward(x, Wg, None, W1, W3, W2, bufs)
+        torch.cuda.synchronize()
+        idx = i32(bufs["topk_idx"])
+        for c in range(n_chunks):
+            t0, t1 = pipe.chunk_range(T, c)
+            cnt, off, rcnt, roff, s2r, r2s = orc.dispatch_maps(idx[t0:t1], inp.dest_rank, R)
+            assert np.array_equal(i32(bufs["expert_counts"][c]), cnt), (step, T, c)
+            assert np.array_equal(i32(bufs["expert_offsets"][c]), off), (step, T, c)
+            if t1 > t0:
+                sl = slice(t0 * k, t1 * k)
+                assert np.array_equal(i32(bufs["slot_to_row"][sl]), s2r), (step, T, c)
+                assert np.array_equal(i32(bufs["row_to_slot"][sl]), r2s), (step, T, c)
+        w = bufs["topk_w"].cpu().numpy().astype(np.float64)
+        want = orc.layer_dense(vals(inp.x[:T], dtype), idx, w, W1v, W3v, W2v)
+        err = nerr(to_host_f32(bufs["out"]), want)
+        assert err <= TOL[dtype], (step, T, err)
+    say("[pipeline-seq] 6 calls with varying T on one pipeline: ok")
+    pipe.close()
