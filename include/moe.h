@@ -189,7 +189,12 @@ int moe_dispatch_noalloc(const moe_config* cfg, const int32_t* expert_dest_rank,
  * (Sec. 2.1; Table 2 counts 2*H*M parameters per expert):
  *   g = x_r W1[e]^T, y_r = max(g, 0) W2[e]^T
  * (the paper does not name the activation; ReLU, as in the Transformer FFN it cites).
- * U_save must then be NULL, G_save may receive g. */
+ * U_save must then be NULL, G_save may receive g.
+ * expert_counts, expert_offsets [dev][E] are read on the device (no host copy).  If the segment
+ * of any computed expert does not lie inside the T*k rows of the buffers (negative count or
+ * offset, offset + count > T*k), the call computes nothing: y_packed and the saves are left
+ * untouched; moe_expert_ffn_bwd then leaves dx_packed untouched and writes zeros to the wanted
+ * weight gradients.  No error is reported (the host never sees the arrays). */
 int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* expert_counts,
                    const int32_t* expert_offsets, const void* const* W1, const void* const* W3,
                    const void* const* W2, int32_t T, void* y_packed, void* G_save, void* U_save,

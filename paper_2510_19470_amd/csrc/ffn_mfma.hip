@@ -720,7 +720,7 @@ static int run_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets, 
                      int kt_b, const void* const* up_b0, const void* const* up_b1,
                      const void* const* down_b0, const void* const* down_b1, hipStream_t s) {
   hipLaunchKernelGGL(mfma_sched_kernel, dim3(32), dim3(256), 0, s, counts, offsets,
-                     c->d_wtab + 0 * MOE_MAX_EXPERTS, c->cfg.E, c->S_max, c->max_mtiles[1], nt_a,
+                     c->d_wtab + 0 * MOE_MAX_EXPERTS, c->cfg.E, c->S_call, c->max_mtiles[1], nt_a,
                      nt_b, c->n_cu, kt_b, c->d_sched[1], up_b0, up_b1, down_b0, down_b1,
                      c->d_order_up, c->d_order_down);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;

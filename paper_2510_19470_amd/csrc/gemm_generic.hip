@@ -236,13 +236,15 @@ template <typename T>
 __global__ __launch_bounds__(256) void ffn_bwd_dw_kernel(
     const T* __restrict__ P, const T* __restrict__ Q, const int32_t* __restrict__ counts,
     const int32_t* __restrict__ offsets, const void* const* __restrict__ present,
-    const void* const* __restrict__ dWt, int Mo, int No) {
+    const void* const* __restrict__ dWt, const TileSched* __restrict__ sched, int Mo, int No) {
   __shared__ Smem sm;
   const int e = blockIdx.z;
   float* dW = (float*)dWt[e];
   if (dW == nullptr || present[e] == nullptr) return;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  const int row0 = offsets[e], rows = counts[e];
+  // the schedule kernel of this call has checked the caller's counts and offsets against
+  // the buffer size: no tiles at all (and zeros here) if any segment does not fit
+  const int row0 = offsets[e], rows = sched->n_mtiles > 0 ? counts[e] : 0;
   float acc[4][4];
   zero(acc);
   // A(m, k=r) = P[(row0+r)*Mo + m0+m]; B(k=r, n) = Q[(row0+r)*No + n0+n]
@@ -266,15 +268,24 @@ __global__ __launch_bounds__(256) void ffn_bwd_dw_kernel(
 __global__ __launch_bounds__(256) void build_sched_kernel(const int32_t* __restrict__ counts,
                                                           const int32_t* __restrict__ offsets,
                                                           const void* const* __restrict__ present,
-                                                          int E, int bm, int max_mtiles,
+                                                          int E, int S, int bm, int max_mtiles,
                                                           TileSched* __restrict__ sched,
                                                           MTile* __restrict__ mt) {
   __shared__ int32_t start[MOE_MAX_EXPERTS + 1];
   if (threadIdx.x == 0) {
     int run = 0;
+    bool bad = false;   // a segment that does not lie inside the S rows of the call's buffers
     for (int e = 0; e < E; ++e) {
       start[e] = run;
-      if (present[e] != nullptr) run += (counts[e] + bm - 1) / bm;
+      if (present[e] != nullptr) {
+        const int n = counts[e], o = offsets[e];
+        if (n < 0 || o < 0 || (long)o + n > (long)S) bad = true;
+        else run += (n + bm - 1) / bm;
+      }
+    }
+    if (bad) {   // the caller's arrays are inconsistent: no tiles, nothing is computed
+      run = 0;
+      for (int e = 0; e <= E; ++e) start[e] = 0;
     }
     start[E] = run;
     sched->n_mtiles = run < max_mtiles ? run : max_mtiles;
@@ -335,12 +346,12 @@ int ffn_bwd_generic_t(moe_ctx* c, bool gated, const void* dy, const void* xp, co
   const dim3 g_df((f + BN - 1) / BN, (d + BM - 1) / BM, E);  // output [d,f]
   const dim3 g_fd((d + BN - 1) / BN, (f + BM - 1) / BM, E);  // output [f,d]
   hipLaunchKernelGGL((ffn_bwd_dw_kernel<T>), g_df, dim3(256), 0, s, (const T*)dy, (const T*)H,
-                     counts, offsets, W2, dW2, d, f);
+                     counts, offsets, W2, dW2, c->d_sched[0], d, f);
   hipLaunchKernelGGL((ffn_bwd_dw_kernel<T>), g_fd, dim3(256), 0, s, (const T*)dG, (const T*)xp,
-                     counts, offsets, W1, dW1, f, d);
+                     counts, offsets, W1, dW1, c->d_sched[0], f, d);
   if (gated)
     hipLaunchKernelGGL((ffn_bwd_dw_kernel<T>), g_fd, dim3(256), 0, s, (const T*)dU, (const T*)xp,
-                       counts, offsets, W3, dW3, f, d);
+                       counts, offsets, W3, dW3, c->d_sched[0], f, d);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }
 
@@ -364,7 +375,7 @@ int launch_build_sched(moe_ctx* c, const int32_t* counts, const int32_t* offsets
                        hipStream_t s) {
   const int bm = which == 0 ? GENERIC_BM : MFMA_BM;
   hipLaunchKernelGGL(build_sched_kernel, dim3(1), dim3(256), 0, s, counts, offsets,
-                     c->d_wtab + 0 * MOE_MAX_EXPERTS, c->cfg.E, bm, c->max_mtiles[which],
+                     c->d_wtab + 0 * MOE_MAX_EXPERTS, c->cfg.E, c->S_call, bm, c->max_mtiles[which],
                      c->d_sched[which], c->d_mtiles[which]);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_EHIP;
 }

@@ -426,6 +426,7 @@ int moe_expert_ffn(moe_ctx* c, const void* x_packed, const int32_t* expert_count
   if (!aligned16(x_packed) || !aligned16(y_packed) || !aligned16(G_save) || !aligned16(U_save))
     return MOE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
+  c->S_call = T * c->cfg.k;   // the schedule kernel checks counts and offsets against it
   const void* const* tabs[MOE_WTAB_ROWS] = {W1, W3, W2, nullptr, nullptr, nullptr};
   st = sync_tables(c, tabs, s);
   if (st != MOE_OK) return st;
@@ -491,6 +492,7 @@ int moe_expert_ffn_bwd(moe_ctx* c, const void* dy_packed, const void* x_packed, 
       !aligned16(dx_packed))
     return MOE_EINVAL;
   hipStream_t s = (hipStream_t)stream;
+  c->S_call = T * c->cfg.k;   // the schedule kernel checks counts and offsets against it
   const size_t sf_bytes = std::max<size_t>((size_t)c->S_max * c->cfg.f * c->elem, 16);
   if (c->ffn_path == MOE_FFN_AUTO && ffn_bwd_mfma_supported(c)) {
     // first call: allocate the backward workspace

@@ -83,6 +83,7 @@ struct moe_ctx {
   int n_cu;               // compute units of the device
   float* d_split_ws;      // fp32 partial tiles of the K-split tail: [n_cu][256*256]
   int32_t S_max;          // T_max*k
+  int32_t S_call;         // T*k of the expert-FFN call being launched: the rows its buffers hold
   void* d_H;              // [T_max*k][f]
   void* d_dG;             // [T_max*k][f]   (vector-ALU backward)
   void* d_dU;             // [T_max*k][f]

@@ -151,6 +151,7 @@ __global__ __launch_bounds__(256) void route_bwd_dx_kernel(
     Vec16<T>::load(dx + (size_t)t * d + c, acc);
     for (int j = 0; j < n_terms; ++j) {
       const int e = renormalize ? topk_idx[(size_t)t * k + j] : j;
+      if ((unsigned)e >= (unsigned)E) continue;   // the routing is the caller's: stay inside Wg
       const float g = dlogits[(size_t)t * E + e];
       float w[V];
       Vec16<T>::load(Wg + (size_t)e * d + c, w);

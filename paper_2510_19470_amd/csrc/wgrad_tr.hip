@@ -50,6 +50,8 @@ struct WgradArgs {
   uint8_t list[MOE_MAX_EXPERTS];      // ... their ids, ascending
   const int32_t* counts;
   const int32_t* offsets;
+  const TileSched* sched;     // of the data-gradient GEMMs of the same call: n_mtiles == 0 when
+                              // the caller's counts and offsets do not fit the buffers
   const uint16_t* zero_row;   // 512 bytes of zeros
 };
 
@@ -94,7 +96,9 @@ __global__ __launch_bounds__(NT) void wgrad_tr_kernel(const WgradArgs p) {
   const int nblk = r2 / gm, mblk = 4 * mg + r2 % gm;
   float* dW = (float*)J.dWt[e];
   if (dW == nullptr) return;   // this gradient is not wanted
-  const int n_e = p.counts[e];
+  // counts and offsets are the caller's; the schedule kernel of this call has checked them
+  // against the buffer size (no tiles at all if any segment does not fit: zeros come out)
+  const int n_e = p.sched->n_mtiles > 0 ? p.counts[e] : 0;
   const int row0 = p.offsets[e];
   const int NH = (n_e + HK - 1) / HK;
 
@@ -220,6 +224,7 @@ int launch_wgrad_tr(moe_ctx* c, bool gated, const void* dy, const void* xp, cons
   a.E = E;
   a.counts = counts;
   a.offsets = offsets;
+  a.sched = c->d_sched[1];
   for (int e = 0; e < E; ++e)   // host copy of the pointer tables: resident, some dW wanted
     if (c->h_wtab[0][e] != nullptr &&
         (c->h_wtab[3][e] != nullptr || c->h_wtab[4][e] != nullptr || c->h_wtab[5][e] != nullptr))

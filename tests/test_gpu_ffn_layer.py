@@ -351,6 +351,56 @@ def test_layer_call_sequence_varying_token_count():
 
 
 @pytest.mark.parametrize("path", ["mfma", "valu"])
+@pytest.mark.parametrize("fault", ["beyond", "negative_count", "negative_offset"])
+def test_inconsistent_counts_compute_nothing(path, fault):
+    """Counts and offsets are device arrays the host never reads.  A segment that does not lie
+    inside the T*k rows of the buffers makes the call compute nothing: outputs untouched,
+    weight gradients zero, and the next call with the right arrays is as ever."""
+    from gpu_common import DEV, moe, to_device, layer_from_inputs
+    cfg = wl.scaled(wl.CONFIGS["train"], T=400, d=256, f=256, E=8, k=2, R=2, migrated=(5,),
+                    backward=True)
+    inp = wl.make_inputs(cfg)
+    lay = layer_from_inputs(inp)
+    moe.moe_set_ffn_path(lay.ctx, moe.MOE_FFN_AUTO if path == "mfma" else moe.MOE_FFN_VALU)
+    x = to_device(inp.x, cfg.dtype)
+    idx, w, _ = moe.moe_route(lay.ctx, x, lay.Wg, lay.bias)
+    disp = moe.moe_dispatch(lay.ctx, x, idx)
+    good = moe.moe_expert_ffn(lay.ctx, disp.x_packed, disp.expert_counts, disp.expert_offsets,
+                              lay.W1, lay.W3, lay.W2, save=True)
+    torch.cuda.synchronize()
+    cnt, off = disp.expert_counts.clone(), disp.expert_offsets.clone()
+    e = int(torch.argmax(cnt).item())
+    if fault == "beyond":
+        off[e] = cfg.S - int(cnt[e].item()) + 1
+    elif fault == "negative_count":
+        cnt[e] = -5
+    else:
+        off[e] = -1
+    y0 = torch.full((cfg.S, cfg.d), 3.0, dtype=disp.x_packed.dtype, device=DEV)
+    G0 = torch.full((cfg.S, cfg.f), 5.0, dtype=disp.x_packed.dtype, device=DEV)
+    U0 = torch.full((cfg.S, cfg.f), 7.0, dtype=disp.x_packed.dtype, device=DEV)
+    y, G, U = moe.moe_expert_ffn(lay.ctx, disp.x_packed, cnt, off, lay.W1, lay.W3, lay.W2,
+                                 y_packed=y0, G_save=G0, U_save=U0, save=True)
+    torch.cuda.synchronize()
+    assert torch.all(y == 3.0) and torch.all(G == 5.0) and torch.all(U == 7.0)
+    dy = torch.ones_like(disp.x_packed)
+    dx0 = torch.full((cfg.S, cfg.d), 9.0, dtype=disp.x_packed.dtype, device=DEV)
+    dxp, dW1, dW3, dW2 = moe.moe_expert_ffn_bwd(lay.ctx, dy, disp.x_packed, good[1], good[2], cnt,
+                                                off, lay.W1, lay.W3, lay.W2, dx_packed=dx0)
+    torch.cuda.synchronize()
+    assert torch.all(dxp == 9.0)
+    for tab in (dW1, dW3, dW2):
+        for g in tab:
+            assert g is None or torch.all(g == 0)
+    # the right arrays again: bit-identical to the first call
+    again = moe.moe_expert_ffn(lay.ctx, disp.x_packed, disp.expert_counts, disp.expert_offsets,
+                               lay.W1, lay.W3, lay.W2, save=True)
+    torch.cuda.synchronize()
+    assert torch.equal(again[0], good[0])
+    lay.close()
+
+
+@pytest.mark.parametrize("path", ["mfma", "valu"])
 def test_backward_unwanted_weight_gradients(path):
     """NULL entries in the gradient tables: that gradient is not computed, every other output
     is bit-identical to the call that asks for all of them (the kernels are deterministic)."""
