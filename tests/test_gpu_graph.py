@@ -11,10 +11,12 @@ import moe_workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("gated", [True, False])
-def test_captured_step_replays_bit_identically(gated):
+# d = 1024: the gate kernel's LDS-staged load path, which under capture runs without the
+# ranking epilogue
+@pytest.mark.parametrize("gated,d_model", [(True, 512), (False, 512), (True, 1024)])
+def test_captured_step_replays_bit_identically(gated, d_model):
     from gpu_common import DEV, moe, say, to_device, layer_from_inputs
-    cfg = wl.scaled(wl.CONFIGS["train"], T=1024, d=512, f=512, E=8, k=2, R=4, migrated=(5,),
+    cfg = wl.scaled(wl.CONFIGS["train"], T=1024, d=d_model, f=512, E=8, k=2, R=4, migrated=(5,),
                     backward=True, gated=gated)
     say(f"[graph] T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} f={cfg.f} gated={gated}")
     inp = wl.make_inputs(cfg)
