@@ -259,6 +259,9 @@ def test_dispatch_routed_full_size_configs(name):
     (600, 48, 5, 3, 256),
     # d >= 1024: the gate kernel's LDS-staged load path with the ranking epilogue
     (33, 16, 3, 4, 1024), (4099, 7, 1, 7, 1536), (600, 48, 5, 3, 1024), (1001, 64, 6, 8, 2048),
+    # the largest context that keeps the gate kernel's side products (2^17 tokens: 4096 gate
+    # blocks, 256 super-blocks), and one token more (no side products: the two-launch path)
+    (131072, 8, 2, 2, 256), (131073, 8, 2, 2, 256),
 ])
 def test_dispatch_routed_edge_shapes(T, E, k, R, d):
     """Ragged last gate block, one token, the largest expert count and top-k, more than one
