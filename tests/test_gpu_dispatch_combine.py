@@ -262,6 +262,8 @@ def test_dispatch_routed_full_size_configs(name):
     # the largest context that keeps the gate kernel's side products (2^17 tokens: 4096 gate
     # blocks, 256 super-blocks), and one token more (no side products: the two-launch path)
     (131072, 8, 2, 2, 256), (131073, 8, 2, 2, 256),
+    # more than 512 gate blocks (32 super-blocks and a partial one), 48 and 64 experts
+    (16417, 48, 5, 3, 1024), (16415, 64, 6, 8, 1024),
 ])
 def test_dispatch_routed_edge_shapes(T, E, k, R, d):
     """Ragged last gate block, one token, the largest expert count and top-k, more than one

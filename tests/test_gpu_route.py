@@ -72,7 +72,10 @@ def test_route_gate_projection_and_selection(name, T):
                                      # go through LDS (4 to 10 stages of 256 elements)
                                      (333, 4, 2, 1024), (1000, 24, 3, 1536), (515, 48, 6, 1024),
                                      (700, 64, 8, 2048), (31, 2, 1, 1024), (77, 8, 2, 2560),
-                                     (1, 16, 4, 1024), (100, 100, 8, 1024)])
+                                     (1, 16, 4, 1024), (100, 100, 8, 1024),
+                                     # more than 512 gate blocks (two per compute unit and
+                                     # more), 48 and 64 experts, ragged last block
+                                     (16417, 48, 5, 1024), (16415, 64, 6, 1024)])
 def test_fused_gate_every_expert_count_branch(T, E, k, d):
     """The fused bf16 gate kernel picks its selection group width and expert blocking from E
     and its load path from d: one case per branch, ragged T, with a bias; indices exact on the
@@ -97,3 +100,24 @@ def test_fused_gate_every_expert_count_branch(T, E, k, d):
     assert torch.equal(idx, idx2)
     assert torch.max(torch.abs(w - w2)).item() <= 1e-6
     ctx.close()
+
+
+def test_fused_gate_without_side_products():
+    """A context too large to keep the ranking side products runs the gate kernel without its
+    ranking epilogue (as under stream capture): same indices and weights, bit for bit, as the
+    kernel with the epilogue."""
+    from gpu_common import moe, say, to_device
+    T, E, k, d = 16417, 64, 6, 1024
+    cfg = wl.MoEConfig("gate-nohist", 5150, "bf16", T=T, d=d, E=E, k=k, f=256, R=1)
+    inp = wl.make_inputs(cfg, experts="none")
+    x, Wg = to_device(inp.x, "bf16"), to_device(inp.Wg, "bf16")
+    big = moe.moe_create(T_max=(1 << 17) + 64, d=d, E=E, k=k, f=256, R=1, dtype=moe.MOE_BF16)
+    ref = moe.moe_create(T_max=T, d=d, E=E, k=k, f=256, R=1, dtype=moe.MOE_BF16)
+    i1, w1, l1 = moe.moe_route(big, x, Wg, None, want_logits=True)
+    i2, w2, l2 = moe.moe_route(ref, x, Wg, None, want_logits=True)
+    torch.cuda.synchronize()
+    assert torch.equal(i1, i2) and torch.equal(w1, w2) and torch.equal(l1, l2)
+    assert np.array_equal(i1.cpu().numpy(), orc.topk_select(l1.cpu().numpy(), k))
+    say("[route fused] without side products: identical")
+    big.close()
+    ref.close()
