@@ -141,7 +141,9 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int32_t T
  * the kernel that copies the token rows.
  * CONTRACT: topk_idx must be the array the last moe_route on ctx wrote, UNCHANGED since (same
  * pointer, same T); a caller that edits the routing in between (drops or remaps experts) must
- * call moe_dispatch.  When the context holds no such side products -- pointer or T differ,
+ * call moe_dispatch (with an edited routing the maps come out wrong, but every write stays
+ * inside the output buffers: rows outside [0, T*k) are refused on the device).  When the
+ * context holds no such side products -- pointer or T differ,
  * the gate of this configuration is not the fused kernel (fp32 storage, d % 256 != 0),
  * T_max > 131072, or moe_route ran on a stream that was being captured -- the call is
  * moe_dispatch.  May be repeated; the side products stay valid until the next moe_route. */
